@@ -1,0 +1,52 @@
+"""Pins for oracle/decode.py: the structural facts Sec. 3 and Sec. 4.2 fix (Eq. 1, Eq. 2, block rules)."""
+import numpy as np
+import pytest
+
+from oracle.decode import decode_full
+from paper_2604_15750_amd import inputs
+
+
+@pytest.fixture(scope="module")
+def tiny():
+    cfg = inputs.TINY
+    return cfg, inputs.weights_to_numpy(inputs.make_weights(cfg)), inputs.make_prompts(cfg, 1, 64)[0]
+
+
+PARAM_SETS = {
+    "paper": dict(inputs.PAPER_PARAMS, l_max=32),
+    "scaled": dict(inputs.PAPER_PARAMS, l_max=32, lam=0.9, tau_low=0.05, tau_high=0.3, gamma=-14.0),
+    "cumulative": dict(inputs.PAPER_PARAMS, l_max=16, lam=0.98, rule=1, tau_low=0.1, tau_high=0.5, gamma=-12.0),
+    "threshold": dict(inputs.PAPER_PARAMS, l_max=32, lam=0.8, tau_high=0.2, mode=1),
+}
+
+
+@pytest.mark.parametrize("name", list(PARAM_SETS))
+def test_decode_invariants(tiny, name):
+    cfg, W, prompt = tiny
+    prm = PARAM_SETS[name]
+    N, P, mask = 64, 64, cfg["mask_id"]
+    trace = []
+    r = decode_full(cfg, W, prompt, N, prm, trace)
+    y = r["tokens"]
+    assert (y[:P] == prompt).all() and not (y == mask).any()  # final sequence is mask-free
+    assert sum(r["blocks"]) == N and r["blocks"][0] == prm["l_min"]  # partition + cold start
+    assert all(prm["l_min"] <= L <= prm["l_max"] for L in r["blocks"][:-1]) and r["blocks"][-1] <= prm["l_max"]
+    assert sum(r["steps"]) == N and min(r["steps"]) >= 1  # every step decodes at least one token
+    assert len(r["blocks"]) <= r["nfe"] <= N and r["nfe"] == sum(t["op"] == "pass" for t in trace)
+    # Eq. 2: a step writes only masked positions of the current block, each with its own prediction
+    for t in trace:
+        if t["op"] == "select":
+            assert not (t["selected"] & ~t["eligible"]).any()
+            assert t["eligible"].any() and t["selected"][np.argmax(np.where(t["eligible"], t["stats"]["conf"], -1))]
+        if t["op"] == "pass":
+            assert t["span_start"] + t["commit_len"] <= P + N
+            if t["kind"] == "inblock":
+                assert (t["tokens"] == mask).any() and t["commit_len"] == 0
+            else:
+                assert not (t["tokens"][: t["commit_len"]] == mask).any()  # only clean tokens reach the cache
+        if t["op"] == "boundary":
+            assert (t["kl"] >= 0).all() and min(t["W"], prm["l_min"]) <= t["L"] <= t["W"] <= prm["l_max"]
+    again = decode_full(cfg, W, prompt, N, prm)
+    assert (again["tokens"] == y).all() and again["nfe"] == r["nfe"]
+    if name != "paper":
+        assert max(r["steps"]) > 1 and len(set(r["blocks"][:-1])) > 1, (r["blocks"], r["steps"])  # both decisions are exercised
