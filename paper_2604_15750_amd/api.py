@@ -1,0 +1,235 @@
+"""ctypes binding of libdlm (include/dlm.h): argument marshalling only.
+
+Every function has the name of the C entry point it calls.  Device buffers are
+torch tensors (torch only allocates memory and supplies the stream); host
+arrays are plain int lists.  A missing library is an error: there is no
+fallback path.
+"""
+import ctypes as C
+import os
+
+import torch  # loaded first so that libdlm binds to the HIP runtime torch already opened
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libdlm.so")
+_lib = None
+
+DLM_F32, DLM_BF16 = 0, 1
+ERRORS = {-1: "DLM_EINVAL", -2: "DLM_ESHAPE", -3: "DLM_ECAPACITY", -4: "DLM_ENOMEM", -5: "DLM_EHIP"}
+
+
+class DlmError(RuntimeError):
+    def __init__(self, code, msg):
+        super().__init__(f"{ERRORS.get(code, code)}: {msg}")
+        self.code = code
+
+
+class dlm_config(C.Structure):
+    _fields_ = [(n, C.c_int32) for n in
+                ("n_layers", "d_model", "n_q_heads", "n_kv_heads", "head_dim", "d_ffn", "vocab", "mask_id", "dtype")] + \
+               [("rms_eps", C.c_float), ("rope_theta", C.c_float)]
+
+
+class dlm_weights(C.Structure):
+    _fields_ = [("embed", C.c_void_p), ("wqkv", C.POINTER(C.c_void_p)), ("wo", C.POINTER(C.c_void_p)),
+                ("w_gate_up", C.POINTER(C.c_void_p)), ("w_down", C.POINTER(C.c_void_p)), ("norm1", C.POINTER(C.c_void_p)),
+                ("norm2", C.POINTER(C.c_void_p)), ("final_norm", C.c_void_p), ("lm_head", C.c_void_p)]
+
+
+_I32P = C.POINTER(C.c_int32)
+
+
+class dlm_step_desc(C.Structure):
+    _fields_ = [("n_seqs", C.c_int32)] + [(n, _I32P) for n in
+                ("slot", "row_offsets", "span_start", "commit_len", "kl_first", "kl_count", "save_first", "save_count", "tok_start")] + \
+               [(n, C.c_void_p) for n in ("tokens", "logits", "max_logit", "lse", "entropy", "kl", "conf", "argmax")]
+
+
+class dlm_boundary_params(C.Structure):
+    _fields_ = [("lam", C.c_float), ("l_min", C.c_int32), ("smooth_radius", C.c_int32), ("norm_mode", C.c_int32), ("rule", C.c_int32)]
+
+
+class dlm_select_params(C.Structure):
+    _fields_ = [("tau_low", C.c_float), ("tau_high", C.c_float), ("gamma", C.c_float), ("mode", C.c_int32)]
+
+
+EXPORTS = ["dlm_last_error", "dlm_model_create", "dlm_model_destroy", "dlm_state_create", "dlm_state_destroy", "dlm_state_reset",
+           "dlm_state_kv_len", "dlm_step", "block_boundary", "select_parallel", "dlm_vocab_stats_workspace", "dlm_vocab_stats",
+           "dlm_gemm_nt", "dlm_attention", "dlm_profile_enable", "dlm_profile_read"]
+
+
+def lib():
+    """The loaded library; raises if it has not been built."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(LIB_PATH):
+            raise RuntimeError(f"{LIB_PATH} is missing: run `python -m paper_2604_15750_amd.build` (there is no fallback path)")
+        L = C.CDLL(LIB_PATH)
+        L.dlm_last_error.restype = C.c_char_p
+        L.dlm_vocab_stats_workspace.restype = C.c_size_t
+        L.dlm_vocab_stats_workspace.argtypes = [C.c_int]
+        L.dlm_model_create.argtypes = [C.POINTER(dlm_config), C.POINTER(dlm_weights), C.c_void_p, C.POINTER(C.c_void_p)]
+        L.dlm_model_destroy.argtypes = [C.c_void_p]
+        L.dlm_model_destroy.restype = None
+        L.dlm_state_create.argtypes = [C.c_void_p, C.c_int, C.c_int, C.c_int, C.c_int, C.POINTER(C.c_void_p)]
+        L.dlm_state_destroy.argtypes = [C.c_void_p]
+        L.dlm_state_destroy.restype = None
+        L.dlm_state_reset.argtypes = [C.c_void_p, C.c_int]
+        L.dlm_state_kv_len.argtypes = [C.c_void_p, C.c_int]
+        L.dlm_step.argtypes = [C.c_void_p, C.POINTER(dlm_step_desc), C.c_void_p]
+        L.block_boundary.argtypes = [C.c_void_p, C.c_void_p, _I32P, _I32P, C.c_int, C.POINTER(dlm_boundary_params), C.c_void_p,
+                                     C.c_void_p, C.c_void_p, C.c_void_p]
+        L.select_parallel.argtypes = [C.c_void_p, C.c_int, C.c_int, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, _I32P, _I32P, _I32P,
+                                      C.c_int, C.c_int, C.POINTER(dlm_select_params), C.c_int, C.c_void_p, C.c_void_p, C.c_void_p,
+                                      C.c_void_p]
+        L.dlm_vocab_stats.argtypes = [C.c_void_p, C.c_void_p, C.c_int, C.c_int, C.c_int, C.c_int] + [C.c_void_p] * 7 + \
+                                     [C.c_size_t, C.c_void_p]
+        L.dlm_gemm_nt.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_int, C.c_int, C.c_int, C.c_int, C.c_void_p]
+        L.dlm_attention.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p] + [C.c_int] * 6 + [C.c_void_p]
+        L.dlm_profile_enable.argtypes = [C.c_void_p, C.c_int]
+        L.dlm_profile_read.argtypes = [C.c_void_p, C.c_int, C.POINTER(C.c_double), C.POINTER(C.c_int64), C.c_int]
+        _lib = L
+    return _lib
+
+
+def _check(rc):
+    if rc < 0:
+        raise DlmError(rc, lib().dlm_last_error().decode())
+    return rc
+
+
+def _ptr(t):
+    return None if t is None else C.c_void_p(t.data_ptr())
+
+
+def _ints(v):
+    return None if v is None else (C.c_int32 * len(v))(*[int(x) for x in v])
+
+
+def _stream():
+    return C.c_void_p(torch.cuda.current_stream().cuda_stream)
+
+
+def dtype_code(t):
+    return {torch.float32: DLM_F32, torch.bfloat16: DLM_BF16}[t if isinstance(t, torch.dtype) else t.dtype]
+
+
+class Model:
+    """dlm_model_create / dlm_model_destroy.  cfg: dict of inputs.model_config; W: dict of device tensors."""
+
+    def __init__(self, cfg, W):
+        self.cfg = dict(cfg)
+        dt = DLM_F32 if cfg["dtype"] == "f32" else DLM_BF16
+        c = dlm_config(cfg["n_layers"], cfg["d_model"], cfg["n_q_heads"], cfg["n_kv_heads"], cfg["head_dim"], cfg["d_ffn"],
+                       cfg["vocab"], cfg["mask_id"], dt, cfg["rms_eps"], cfg["rope_theta"])
+        arr = lambda ts: (C.c_void_p * len(ts))(*[t.data_ptr() for t in ts])
+        keep = [arr(W[k]) for k in ("wqkv", "wo", "w_gate_up", "w_down", "norm1", "norm2")]
+        w = dlm_weights(W["embed"].data_ptr(), *keep, W["final_norm"].data_ptr(), W["lm_head"].data_ptr())
+        h = C.c_void_p()
+        _check(lib().dlm_model_create(C.byref(c), C.byref(w), _stream(), C.byref(h)))
+        torch.cuda.current_stream().synchronize()  # the caller may now drop W
+        self.handle = h
+        self.torch_dtype = torch.float32 if dt == DLM_F32 else torch.bfloat16
+
+    def close(self):
+        if self.handle:
+            lib().dlm_model_destroy(self.handle)
+            self.handle = None
+
+    __del__ = close
+
+
+class State:
+    """dlm_state_create / dlm_state_destroy."""
+
+    def __init__(self, model, max_seqs, max_seq_len, max_rows, max_lookahead):
+        self.model = model
+        h = C.c_void_p()
+        _check(lib().dlm_state_create(model.handle, max_seqs, max_seq_len, max_rows, max_lookahead, C.byref(h)))
+        self.handle = h
+        self.max_rows = max_rows
+
+    def reset(self, slot):
+        _check(lib().dlm_state_reset(self.handle, slot))
+
+    def kv_len(self, slot):
+        return _check(lib().dlm_state_kv_len(self.handle, slot))
+
+    def profile_enable(self, on):
+        _check(lib().dlm_profile_enable(self.handle, int(on)))
+
+    def profile_read(self, reset=True):
+        ms = (C.c_double * 4)()
+        n = (C.c_int64 * 4)()
+        _check(lib().dlm_profile_read(self.handle, 4, ms, n, int(reset)))
+        names = ("gemm", "attention", "vocab_stats", "other")
+        return {k: (ms[i], n[i]) for i, k in enumerate(names)}
+
+    def close(self):
+        if self.handle:
+            lib().dlm_state_destroy(self.handle)
+            self.handle = None
+
+    __del__ = close
+
+
+class StepOutputs:
+    """Caller-owned output buffers of dlm_step for up to `rows` rows."""
+
+    def __init__(self, rows, vocab, dtype, device):
+        self.logits = torch.empty((rows, vocab), dtype=dtype, device=device)
+        f = lambda: torch.empty(rows, dtype=torch.float32, device=device)
+        self.max_logit, self.lse, self.entropy, self.kl, self.conf = f(), f(), f(), f(), f()
+        self.argmax = torch.empty(rows, dtype=torch.int32, device=device)
+
+
+def dlm_step(state, tokens, out, row_offsets, span_start, commit_len, tok_start, slot=None, kl_first=None, kl_count=None,
+             save_first=None, save_count=None):
+    """tokens: device int32 tensor; out: StepOutputs; the rest: host int lists (see include/dlm.h)."""
+    keep = [_ints(v) for v in (slot, row_offsets, span_start, commit_len, kl_first, kl_count, save_first, save_count, tok_start)]
+    d = dlm_step_desc(len(span_start), *keep, tokens.data_ptr(), out.logits.data_ptr(), out.max_logit.data_ptr(), out.lse.data_ptr(),
+                      out.entropy.data_ptr(), out.kl.data_ptr(), out.conf.data_ptr(), out.argmax.data_ptr())
+    _check(lib().dlm_step(state.handle, C.byref(d), _stream()))
+
+
+def block_boundary(I, H, win_offsets, L_out, lam, l_min, smooth_radius=1, norm_mode=0, rule=0, cold=None, S_out=None, margin_out=None):
+    p = dlm_boundary_params(lam, l_min, smooth_radius, norm_mode, rule)
+    _check(lib().block_boundary(_ptr(I), _ptr(H), _ints(win_offsets), _ints(cold), len(win_offsets) - 1, C.byref(p), _ptr(L_out),
+                                _ptr(S_out), _ptr(margin_out), _stream()))
+
+
+def select_parallel(logits, lse, conf, argmax, tokens, row_start, tok_start, block_len, mask_id, tau_low, tau_high, gamma, mode,
+                    selected_out, n_selected_out, apply_tokens=True, margin_out=None):
+    p = dlm_select_params(tau_low, tau_high, gamma, mode)
+    _check(lib().select_parallel(_ptr(logits), logits.shape[-1], dtype_code(logits), _ptr(lse), _ptr(conf), _ptr(argmax), _ptr(tokens),
+                                 _ints(row_start), _ints(tok_start), _ints(block_len), len(row_start), mask_id, C.byref(p),
+                                 int(apply_tokens), _ptr(selected_out), _ptr(n_selected_out), _ptr(margin_out), _stream()))
+
+
+def dlm_vocab_stats(logits, mask_id, prev=None, workspace=None):
+    rows, vocab = logits.shape
+    dev = logits.device
+    f = lambda: torch.empty(rows, dtype=torch.float32, device=dev)
+    out = dict(max_logit=f(), lse=f(), entropy=f(), kl=f(), conf=f(), argmax=torch.empty(rows, dtype=torch.int32, device=dev))
+    if workspace is None:
+        workspace = torch.empty(lib().dlm_vocab_stats_workspace(rows), dtype=torch.uint8, device=dev)
+    _check(lib().dlm_vocab_stats(_ptr(logits), _ptr(prev), rows, vocab, dtype_code(logits), mask_id, _ptr(out["max_logit"]),
+                                 _ptr(out["lse"]), _ptr(out["entropy"]), _ptr(out["kl"]), _ptr(out["conf"]), _ptr(out["argmax"]),
+                                 _ptr(workspace), workspace.numel(), _stream()))
+    return out
+
+
+def dlm_gemm_nt(x, w):
+    M, K = x.shape
+    N = w.shape[0]
+    y = torch.empty((M, N), dtype=x.dtype, device=x.device)
+    _check(lib().dlm_gemm_nt(_ptr(x), _ptr(w), _ptr(y), M, N, K, dtype_code(x), _stream()))
+    return y
+
+
+def dlm_attention(q, k, v):
+    A, n_q, hd = q.shape
+    T, n_kv, _ = k.shape
+    out = torch.empty_like(q)
+    _check(lib().dlm_attention(_ptr(q), _ptr(k), _ptr(v), _ptr(out), A, T, n_q, n_kv, hd, dtype_code(q), _stream()))
+    return out

@@ -1,0 +1,110 @@
+// Block-vs-prefix attention: every row of a sequence's span attends, without causal mask, to keys
+// [0, n_keys) of the sequence's KV-cache slot (cached prefix + the span's own rows, which the
+// rotary/KV kernel has already written there).  Grouped-query heads share K/V.
+//
+// Generic kernel (any dtype, head_dim 32/64/128): one workgroup per (16-query tile, head,
+// sequence); keys are streamed in tiles through LDS with an online softmax in fp32.
+#include "common.h"
+
+namespace {
+
+constexpr int QT = 16;        // query rows per workgroup
+constexpr int KTILE = 32;     // keys per LDS tile
+constexpr float NEG_BIG = -3.0e38f;
+
+template <typename T, int HD>
+__global__ __launch_bounds__(256) void attention_kernel(const T* __restrict__ q, const T* __restrict__ kcache, const T* __restrict__ vcache,
+                                                        size_t slot_stride, AttnMeta meta, T* __restrict__ out, bool out_tiled, int n_q,
+                                                        int n_kv) {
+  __shared__ float qs[QT][HD];
+  __shared__ float ks[KTILE][HD + 1];
+  __shared__ float vs[KTILE][HD];
+  __shared__ float ps[QT][KTILE];
+  constexpr int EPT = HD / 16;  // output elements per thread
+
+  const int b = blockIdx.z, head = blockIdx.y;
+  const int row0 = meta.row_off[b] + blockIdx.x * QT;
+  const int row_end = meta.row_off[b + 1];
+  if (row0 >= row_end) return;
+  const int n_keys = meta.n_keys[b];
+  const int kvh = head / (n_q / n_kv);
+  const size_t kv_row = (size_t)n_kv * HD;
+  const T* kbase = kcache + (size_t)meta.slot[b] * slot_stride + (size_t)kvh * HD;
+  const T* vbase = vcache + (size_t)meta.slot[b] * slot_stride + (size_t)kvh * HD;
+  const int tid = threadIdx.x, qi = tid >> 4, lx = tid & 15;
+  const float scale = rsqrtf((float)HD);
+
+  for (int i = tid; i < QT * HD; i += 256) {
+    const int r = i / HD, e = i % HD;
+    qs[r][e] = (row0 + r < row_end) ? to_f32(q[(size_t)(row0 + r) * n_q * HD + (size_t)head * HD + e]) * scale : 0.f;
+  }
+  float m = NEG_BIG, l = 0.f, o[EPT];
+#pragma unroll
+  for (int n = 0; n < EPT; ++n) o[n] = 0.f;
+
+  for (int k0 = 0; k0 < n_keys; k0 += KTILE) {
+    __syncthreads();
+    for (int i = tid; i < KTILE * HD; i += 256) {
+      const int kk = i / HD, e = i % HD;
+      const bool ok = k0 + kk < n_keys;
+      ks[kk][e] = ok ? to_f32(kbase[(size_t)(k0 + kk) * kv_row + e]) : 0.f;
+      vs[kk][e] = ok ? to_f32(vbase[(size_t)(k0 + kk) * kv_row + e]) : 0.f;
+    }
+    __syncthreads();
+    // scores: thread (qi, lx) handles keys lx and lx + 16
+    float s0 = 0.f, s1 = 0.f;
+#pragma unroll 8
+    for (int e = 0; e < HD; ++e) {
+      const float qv = qs[qi][e];
+      s0 = fmaf(qv, ks[lx][e], s0);
+      s1 = fmaf(qv, ks[lx + 16][e], s1);
+    }
+    if (k0 + lx >= n_keys) s0 = NEG_BIG;
+    if (k0 + lx + 16 >= n_keys) s1 = NEG_BIG;
+    float tm = fmaxf(s0, s1);
+#pragma unroll
+    for (int ofs = 8; ofs > 0; ofs >>= 1) tm = fmaxf(tm, __shfl_xor(tm, ofs, 64));
+    const float mn = fmaxf(m, tm);
+    const float corr = __expf(m - mn);
+    const float p0 = (k0 + lx < n_keys) ? __expf(s0 - mn) : 0.f;
+    const float p1 = (k0 + lx + 16 < n_keys) ? __expf(s1 - mn) : 0.f;
+    float ts = p0 + p1;
+#pragma unroll
+    for (int ofs = 8; ofs > 0; ofs >>= 1) ts += __shfl_xor(ts, ofs, 64);
+    l = l * corr + ts;
+    m = mn;
+    ps[qi][lx] = p0;
+    ps[qi][lx + 16] = p1;
+    __syncthreads();
+#pragma unroll
+    for (int n = 0; n < EPT; ++n) o[n] *= corr;
+    for (int kk = 0; kk < KTILE; ++kk) {
+      const float p = ps[qi][kk];
+#pragma unroll
+      for (int n = 0; n < EPT; ++n) o[n] = fmaf(p, vs[kk][lx + 16 * n], o[n]);
+    }
+  }
+  const int r = row0 + qi;
+  if (r < row_end) {
+    const int width = n_q * HD;
+#pragma unroll
+    for (int n = 0; n < EPT; ++n) {
+      const int col = head * HD + lx + 16 * n;
+      const size_t idx = out_tiled ? Act<T>::idx(r, col, width) : (size_t)r * width + col;
+      out[idx] = from_f32<T>(o[n] / l);
+    }
+  }
+}
+
+}  // namespace
+
+template <typename T>
+void launch_attention(const T* q, const T* kcache, const T* vcache, size_t slot_stride, const AttnMeta& meta, T* out, bool out_tiled,
+                      int rows, int max_seq_rows, int n_q, int n_kv, int hd, hipStream_t st) {
+  dim3 grid((max_seq_rows + QT - 1) / QT, n_q, meta.n_seqs);
+  if (hd == 32) attention_kernel<T, 32><<<grid, 256, 0, st>>>(q, kcache, vcache, slot_stride, meta, out, out_tiled, n_q, n_kv);
+  else if (hd == 64) attention_kernel<T, 64><<<grid, 256, 0, st>>>(q, kcache, vcache, slot_stride, meta, out, out_tiled, n_q, n_kv);
+  else attention_kernel<T, 128><<<grid, 256, 0, st>>>(q, kcache, vcache, slot_stride, meta, out, out_tiled, n_q, n_kv);
+}
+template void launch_attention<float>(const float*, const float*, const float*, size_t, const AttnMeta&, float*, bool, int, int, int, int, int, hipStream_t);
+template void launch_attention<bf16_t>(const bf16_t*, const bf16_t*, const bf16_t*, size_t, const AttnMeta&, bf16_t*, bool, int, int, int, int, int, hipStream_t);

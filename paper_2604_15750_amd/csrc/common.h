@@ -1,0 +1,145 @@
+// Internal declarations shared by the HIP sources of libdlm (gfx950 only).
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "../../include/dlm.h"
+
+typedef __bf16 bf16_t;
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef __bf16 bf16x4 __attribute__((ext_vector_type(4)));
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+
+#define DLM_WAVE 64
+
+int dlm_fail(int code, const char* fmt, ...);
+#define DLM_HIP(expr)                                                                        \
+  do {                                                                                       \
+    hipError_t e_ = (expr);                                                                  \
+    if (e_ != hipSuccess) return dlm_fail(DLM_EHIP, "%s: %s", #expr, hipGetErrorString(e_)); \
+  } while (0)
+
+// ---- activation layouts -------------------------------------------------------------------
+// fp32 models keep activations row-major.  bf16 models keep every GEMM input in "fragment tiles":
+// element (m, k) of an [M, K] matrix lives in the 1 KiB tile (m/16, k/32), at lane
+// (m%16) + 16*((k%32)/8), slot k%8 -- exactly one operand of the 16x16x32 bf16 matrix-core
+// instruction per tile, so a wavefront fetches an operand as 64 consecutive 16-byte pieces.
+__host__ __device__ inline size_t tile_index(int m, int k, int K) {
+  return ((size_t)(m >> 4) * (size_t)(K >> 5) + (size_t)(k >> 5)) * 512 + (size_t)(((m & 15) + 16 * ((k & 31) >> 3)) * 8 + (k & 7));
+}
+
+template <typename T> struct Act;
+template <> struct Act<float> {
+  static __device__ inline size_t idx(int m, int k, int K) { return (size_t)m * K + k; }
+};
+template <> struct Act<bf16_t> {
+  static __device__ inline size_t idx(int m, int k, int K) { return tile_index(m, k, K); }
+};
+
+__device__ inline float to_f32(float x) { return x; }
+__device__ inline float to_f32(bf16_t x) { return (float)x; }
+template <typename T> __device__ inline T from_f32(float x);
+template <> __device__ inline float from_f32<float>(float x) { return x; }
+template <> __device__ inline bf16_t from_f32<bf16_t>(float x) { return (bf16_t)x; }
+
+__device__ inline float wave_sum(float v) {
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o, 64);
+  return v;
+}
+__device__ inline float wave_max(float v) {
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) v = fmaxf(v, __shfl_xor(v, o, 64));
+  return v;
+}
+
+// ---- per-pass metadata, passed to kernels by value -------------------------------------------
+#define DLM_MAX_SEQS 32
+
+struct SeqMeta {
+  int32_t n_seqs;
+  int32_t row_off[DLM_MAX_SEQS + 1];
+  int32_t span_start[DLM_MAX_SEQS];
+  int32_t slot[DLM_MAX_SEQS];
+  int32_t tok_start[DLM_MAX_SEQS];
+};
+struct StatsMeta {  // which rows are compared with / retained as p^prev; offsets in elements of the retained-logit buffer
+  int32_t kl_first[DLM_MAX_SEQS], kl_count[DLM_MAX_SEQS], save_first[DLM_MAX_SEQS], save_count[DLM_MAX_SEQS];
+  int64_t prev_off[DLM_MAX_SEQS], save_off[DLM_MAX_SEQS];
+};
+struct AttnMeta {
+  int32_t n_seqs;
+  int32_t row_off[DLM_MAX_SEQS + 1];
+  int32_t n_keys[DLM_MAX_SEQS];   // keys [0, n_keys) of the slot's cache are visible to every row of the sequence
+  int32_t slot[DLM_MAX_SEQS];
+};
+struct BoundaryMeta {
+  int32_t win_off[DLM_MAX_SEQS + 1];
+  int32_t cold[DLM_MAX_SEQS];
+};
+struct SelectMeta {
+  int32_t row_start[DLM_MAX_SEQS];
+  int32_t tok_start[DLM_MAX_SEQS];
+  int32_t block_len[DLM_MAX_SEQS];
+};
+struct RowTables {  // device arrays of one pass, [rows]
+  int32_t* row_seq;   // packed sequence index of the row
+  int32_t* row_pos;   // absolute position
+  int32_t* row_tok;   // index of the row's token in the caller's token array
+  float* rope_cos;    // [rows, hd/2]
+  float* rope_sin;
+  int64_t* prev_row;  // element offset of the row's retained p^prev logits, or -1
+  int64_t* save_row;  // element offset where the row's logits are retained, or -1
+};
+
+// ---- launchers (callers have validated shapes) -------------------------------------------------
+// bf16 weight tiling: W [N, K] row-major -> tiles of 16 rows x 32 k, pairs of row-tiles interleaved
+// along k: tile (nt, kt) at ((nt/2 * K/32 + kt) * 2 + nt%2) KiB.
+void launch_pack_weight(const bf16_t* w, bf16_t* out, int N, int K, hipStream_t st);
+void launch_pack_act(const bf16_t* x, bf16_t* out, int M, int K, hipStream_t st);  // row-major -> fragment tiles (rows padded to 16 with zeros)
+// Y = X * W^T.  xt: fragment-tiled [Mpad, K]; wt: tiled weights.  Exactly one of out_f32 / out_bf16
+// is non-null: out_f32 [splits][M][N] partial sums (splits from gemm_bf16_splits), out_bf16 [M][N] (splits = 1).
+int gemm_bf16_splits(int M, int N, int K);
+void launch_gemm_bf16(const bf16_t* xt, const bf16_t* wt, float* out_f32, bf16_t* out_bf16, int M, int N, int K, int splits, hipStream_t st);
+void launch_gemm_f32(const float* x, const float* w, float* y, int M, int N, int K, hipStream_t st);
+
+void launch_prepare(const SeqMeta& meta, const StatsMeta& sm, RowTables t, int rows, int vocab, int head_dim, float theta, hipStream_t st);
+template <typename T>
+void launch_embed_norm(const T* embed, const int32_t* tokens, const RowTables& t, const float* gain, float eps, float* h, T* x, int rows, int d, hipStream_t st);
+// h += sum_s part[s]; x = rmsnorm(h) * gain   (x in the activation layout of T)
+template <typename T>
+void launch_reduce_residual_norm(const float* part, int splits, float* h, const float* gain, float eps, T* x, int rows, int d, hipStream_t st);
+// act = silu(gate) * up from part [splits][rows][2*ffn]
+template <typename T>
+void launch_silu_mul(const float* part, int splits, T* act, int rows, int ffn, hipStream_t st);
+// rotary embedding of Q and K; Q -> q [rows, n_q*hd] row-major; K, V -> cache[slot][pos]
+template <typename T>
+void launch_rope_kv(const float* part, int splits, const RowTables& t, const SeqMeta& meta, T* q, T* kcache, T* vcache,
+                    size_t slot_stride, int rows, int n_q, int n_kv, int hd, hipStream_t st);
+// softmax(q k^T / sqrt(hd)) v over keys [0, n_keys) of the row's slot; q row-major, out in the activation layout [rows, n_q*hd]
+template <typename T>
+void launch_attention(const T* q, const T* kcache, const T* vcache, size_t slot_stride, const AttnMeta& meta, T* out, bool out_tiled,
+                      int rows, int max_seq_rows, int n_q, int n_kv, int hd, hipStream_t st);
+
+struct StatsOut {
+  float *max_logit, *lse, *entropy, *kl, *conf;
+  int32_t* argmax;
+};
+struct StatsRows {
+  const int64_t* prev_row;  // DEVICE [rows] or null: offset (elements) of the row's p^prev logits in prev_base, -1 = none
+  const int64_t* save_row;  // DEVICE [rows] or null: offset where the row's logits are copied, -1 = none
+  const void* prev_base;
+  void* save_base;
+  const float* prev_lse;    // indexed by prev_row / vocab; null = recompute from the logits
+  float* save_lse;          // indexed by save_row / vocab
+};
+size_t stats_workspace_bytes(int rows);
+template <typename T>
+void launch_vocab_stats(const T* logits, int rows, int vocab, int mask_id, const StatsRows& sr, const StatsOut& o, void* workspace, hipStream_t st);
+
+void launch_block_boundary(const float* I, const float* H, const BoundaryMeta& meta, int n_seqs, dlm_boundary_params p, int32_t* L_out,
+                           float* S_out, float* margin_out, hipStream_t st);
+template <typename T>
+void launch_select(const T* logits, int vocab, const float* lse, const float* conf, const int32_t* argmax, int32_t* tokens,
+                   const SelectMeta& meta, int n_seqs, int mask_id, dlm_select_params p, int apply, uint8_t* sel, int32_t* nsel,
+                   float* margin, hipStream_t st);

@@ -1,0 +1,160 @@
+// Row-wise glue of the transformer pass: row tables and rotary tables, embedding + RMSNorm,
+// split-K reduction fused with residual add + RMSNorm, SiLU-gating, rotary embedding + KV-cache
+// write.  All fp32 arithmetic; bf16 outputs are written in the fragment tiling the GEMM reads.
+#include "common.h"
+
+namespace {
+
+// one workgroup per row: row -> (sequence, position, token index, retained-logit offsets), rotary table
+__global__ void prepare_kernel(SeqMeta meta, StatsMeta sm, RowTables t, int rows, int vocab, int head_dim, float theta) {
+  const int r = blockIdx.x;
+  int b = 0;
+  while (b + 1 < meta.n_seqs && r >= meta.row_off[b + 1]) ++b;
+  const int rel = r - meta.row_off[b];
+  const int pos = meta.span_start[b] + rel;
+  if (threadIdx.x == 0) {
+    t.row_seq[r] = b;
+    t.row_pos[r] = pos;
+    t.row_tok[r] = meta.tok_start[b] + rel;
+    const int kr = rel - sm.kl_first[b];
+    t.prev_row[r] = (kr >= 0 && kr < sm.kl_count[b]) ? sm.prev_off[b] + (int64_t)kr * vocab : -1;
+    const int sr = rel - sm.save_first[b];
+    t.save_row[r] = (sr >= 0 && sr < sm.save_count[b]) ? sm.save_off[b] + (int64_t)sr * vocab : -1;
+  }
+  const int half = head_dim / 2;
+  for (int i = threadIdx.x; i < half; i += blockDim.x) {
+    const double inv_freq = pow((double)theta, -2.0 * (double)i / (double)head_dim);
+    double s, c;
+    sincos((double)pos * inv_freq, &s, &c);
+    t.rope_cos[(size_t)r * half + i] = (float)c;
+    t.rope_sin[(size_t)r * half + i] = (float)s;
+  }
+}
+
+__device__ inline float block_sum_256(float v, float* buf) {
+  v = wave_sum(v);
+  __syncthreads();
+  if ((threadIdx.x & 63) == 0) buf[threadIdx.x >> 6] = v;
+  __syncthreads();
+  return buf[0] + buf[1] + buf[2] + buf[3];
+}
+
+template <typename T>
+__global__ __launch_bounds__(256) void embed_norm_kernel(const T* __restrict__ embed, const int32_t* __restrict__ tokens, RowTables t,
+                                                         const float* __restrict__ gain, float eps, float* __restrict__ h,
+                                                         T* __restrict__ x, int d) {
+  __shared__ float buf[4];
+  const int r = blockIdx.x;
+  const T* e = embed + (size_t)tokens[t.row_tok[r]] * d;
+  float ss = 0.f;
+  for (int k = threadIdx.x; k < d; k += 256) {
+    float v = to_f32(e[k]);
+    h[(size_t)r * d + k] = v;
+    ss = fmaf(v, v, ss);
+  }
+  const float rinv = rsqrtf(block_sum_256(ss, buf) / (float)d + eps);
+  for (int k = threadIdx.x; k < d; k += 256) x[Act<T>::idx(r, k, d)] = from_f32<T>(to_f32(e[k]) * rinv * gain[k]);
+}
+
+template <typename T>
+__global__ __launch_bounds__(256) void reduce_residual_norm_kernel(const float* __restrict__ part, int splits, size_t split_stride,
+                                                                   float* __restrict__ h, const float* __restrict__ gain, float eps,
+                                                                   T* __restrict__ x, int d) {
+  __shared__ float buf[4];
+  const int r = blockIdx.x;
+  float ss = 0.f;
+  for (int k = threadIdx.x * 4; k < d; k += 1024) {
+    f32x4 v = *(const f32x4*)(h + (size_t)r * d + k);
+    for (int s = 0; s < splits; ++s) v += *(const f32x4*)(part + s * split_stride + (size_t)r * d + k);
+    *(f32x4*)(h + (size_t)r * d + k) = v;
+    ss += v[0] * v[0] + v[1] * v[1] + v[2] * v[2] + v[3] * v[3];
+  }
+  const float rinv = rsqrtf(block_sum_256(ss, buf) / (float)d + eps);
+  for (int k = threadIdx.x * 4; k < d; k += 1024) {
+    f32x4 v = *(const f32x4*)(h + (size_t)r * d + k);
+    f32x4 g = *(const f32x4*)(gain + k);
+#pragma unroll
+    for (int i = 0; i < 4; ++i) x[Act<T>::idx(r, k + i, d)] = from_f32<T>(v[i] * rinv * g[i]);
+  }
+}
+
+template <typename T>
+__global__ __launch_bounds__(256) void silu_mul_kernel(const float* __restrict__ part, int splits, size_t split_stride,
+                                                       T* __restrict__ act, int rows, int ffn) {
+  const int r = blockIdx.y;
+  const int k = (blockIdx.x * 256 + threadIdx.x) * 4;
+  if (k >= ffn) return;
+  const float* base = part + (size_t)r * 2 * ffn;
+  f32x4 g = {0.f, 0.f, 0.f, 0.f}, u = {0.f, 0.f, 0.f, 0.f};
+  for (int s = 0; s < splits; ++s) {
+    g += *(const f32x4*)(base + s * split_stride + k);
+    u += *(const f32x4*)(base + s * split_stride + ffn + k);
+  }
+#pragma unroll
+  for (int i = 0; i < 4; ++i) act[Act<T>::idx(r, k + i, ffn)] = from_f32<T>(g[i] / (1.f + __expf(-g[i])) * u[i]);
+}
+
+// grid (rows, n_q + 2*n_kv heads), hd/2 lanes: one rotary pair per lane
+template <typename T>
+__global__ void rope_kv_kernel(const float* __restrict__ part, int splits, size_t split_stride, RowTables t, SeqMeta meta,
+                               T* __restrict__ q, T* __restrict__ kcache, T* __restrict__ vcache, size_t slot_stride, int n_q,
+                               int n_kv, int hd) {
+  const int r = blockIdx.x, head = blockIdx.y, i = threadIdx.x, half = hd >> 1;
+  const int width = (n_q + 2 * n_kv) * hd;
+  const float* src = part + (size_t)r * width + (size_t)head * hd;
+  float a = 0.f, b = 0.f;
+  for (int s = 0; s < splits; ++s) {
+    a += src[s * split_stride + i];
+    b += src[s * split_stride + i + half];
+  }
+  const int pos = t.row_pos[r];
+  if (head < n_q + n_kv) {  // Q and K heads are rotated
+    const float c = t.rope_cos[(size_t)r * half + i], sn = t.rope_sin[(size_t)r * half + i];
+    const float ra = a * c - b * sn, rb = b * c + a * sn;
+    a = ra;
+    b = rb;
+  }
+  T* dst;
+  if (head < n_q) {
+    dst = q + (size_t)r * n_q * hd + (size_t)head * hd;
+  } else {
+    const size_t row = (size_t)meta.slot[t.row_seq[r]] * slot_stride + (size_t)pos * n_kv * hd;
+    dst = (head < n_q + n_kv) ? kcache + row + (size_t)(head - n_q) * hd : vcache + row + (size_t)(head - n_q - n_kv) * hd;
+  }
+  dst[i] = from_f32<T>(a);
+  dst[i + half] = from_f32<T>(b);
+}
+
+}  // namespace
+
+void launch_prepare(const SeqMeta& meta, const StatsMeta& sm, RowTables t, int rows, int vocab, int head_dim, float theta, hipStream_t st) {
+  prepare_kernel<<<rows, 64, 0, st>>>(meta, sm, t, rows, vocab, head_dim, theta);
+}
+
+template <typename T>
+void launch_embed_norm(const T* embed, const int32_t* tokens, const RowTables& t, const float* gain, float eps, float* h, T* x, int rows, int d, hipStream_t st) {
+  embed_norm_kernel<T><<<rows, 256, 0, st>>>(embed, tokens, t, gain, eps, h, x, d);
+}
+template <typename T>
+void launch_reduce_residual_norm(const float* part, int splits, float* h, const float* gain, float eps, T* x, int rows, int d, hipStream_t st) {
+  reduce_residual_norm_kernel<T><<<rows, 256, 0, st>>>(part, splits, (size_t)rows * d, h, gain, eps, x, d);
+}
+template <typename T>
+void launch_silu_mul(const float* part, int splits, T* act, int rows, int ffn, hipStream_t st) {
+  dim3 grid((ffn / 4 + 255) / 256, rows);
+  silu_mul_kernel<T><<<grid, 256, 0, st>>>(part, splits, (size_t)rows * 2 * ffn, act, rows, ffn);
+}
+template <typename T>
+void launch_rope_kv(const float* part, int splits, const RowTables& t, const SeqMeta& meta, T* q, T* kcache, T* vcache,
+                    size_t slot_stride, int rows, int n_q, int n_kv, int hd, hipStream_t st) {
+  dim3 grid(rows, n_q + 2 * n_kv);
+  rope_kv_kernel<T><<<grid, hd / 2, 0, st>>>(part, splits, (size_t)rows * (n_q + 2 * n_kv) * hd, t, meta, q, kcache, vcache, slot_stride, n_q, n_kv, hd);
+}
+
+#define INST(T)                                                                                                                       \
+  template void launch_embed_norm<T>(const T*, const int32_t*, const RowTables&, const float*, float, float*, T*, int, int, hipStream_t); \
+  template void launch_reduce_residual_norm<T>(const float*, int, float*, const float*, float, T*, int, int, hipStream_t);             \
+  template void launch_silu_mul<T>(const float*, int, T*, int, int, hipStream_t);                                                      \
+  template void launch_rope_kv<T>(const float*, int, const RowTables&, const SeqMeta&, T*, T*, T*, size_t, int, int, int, int, hipStream_t);
+INST(float)
+INST(bf16_t)

@@ -1,0 +1,200 @@
+// Fused vocabulary reduction (paper Sec. 4.2: Eq. 3 and the entropy signal; Sec. 4.3: confidence
+// and prediction).  One pass over each row of logits gives, with the mask token excluded,
+//   m = max z, y = argmax, s = sum e^(z-m), t = sum e^(z-m) (z-m), w = sum e^(z-m) (z-z')
+// and from those  lse = m + ln s,  conf = 1/s,  H = ln s - t/s,  KL(p||p') = w/s - lse + lse'.
+// The kernel is a pure HBM stream: 16-byte loads, several in flight per lane, rows split over
+// enough workgroups to fill 256 CUs; partial states are merged in a fixed order (deterministic).
+#include "common.h"
+
+namespace {
+
+constexpr int TPB = 256;
+constexpr float NEG_BIG = -3.0e38f;   // "minus infinity" that keeps every product finite
+constexpr float MASKED = -1.0e30f;    // logit given to the mask token: e^(MASKED - m) == 0
+
+struct Part {  // online-softmax state of a slice of one row
+  float m, s, t, w;
+  float bv;    // best logit
+  int bi;      // its token id
+  float pm, ps;  // max and sum e^(z'-pm) of the previous-step row (only when its lse is not stored)
+};
+
+__device__ inline Part part_init() { return Part{NEG_BIG, 0.f, 0.f, 0.f, NEG_BIG, 0x7fffffff, NEG_BIG, 0.f}; }
+
+__device__ inline Part part_merge(const Part& a, const Part& b) {
+  Part r;
+  r.m = fmaxf(a.m, b.m);
+  float da = a.m - r.m, db = b.m - r.m;
+  float fa = __expf(da), fb = __expf(db);
+  r.s = fa * a.s + fb * b.s;
+  r.t = fa * (a.t + da * a.s) + fb * (b.t + db * b.s);
+  r.w = fa * a.w + fb * b.w;
+  bool tb = (b.bv > a.bv) || (b.bv == a.bv && b.bi < a.bi);
+  r.bv = tb ? b.bv : a.bv;
+  r.bi = tb ? b.bi : a.bi;
+  r.pm = fmaxf(a.pm, b.pm);
+  r.ps = __expf(a.pm - r.pm) * a.ps + __expf(b.pm - r.pm) * b.ps;
+  return r;
+}
+
+__device__ inline Part part_shfl_xor(const Part& p, int o) {
+  Part r;
+  r.m = __shfl_xor(p.m, o, 64); r.s = __shfl_xor(p.s, o, 64); r.t = __shfl_xor(p.t, o, 64); r.w = __shfl_xor(p.w, o, 64);
+  r.bv = __shfl_xor(p.bv, o, 64); r.bi = __shfl_xor(p.bi, o, 64); r.pm = __shfl_xor(p.pm, o, 64); r.ps = __shfl_xor(p.ps, o, 64);
+  return r;
+}
+
+template <typename T> struct Vec;
+template <> struct Vec<bf16_t> { static constexpr int N = 8; typedef bf16x8 type; };
+template <> struct Vec<float> { static constexpr int N = 4; typedef f32x4 type; };
+
+// absorb N consecutive logits (first token id = v0) into the state
+template <int N, bool KL, bool PREV_SUMS>
+__device__ inline void absorb(Part& p, const float (&z)[N], const float (&zp)[N], int v0) {
+  float vm = z[0];
+#pragma unroll
+  for (int i = 1; i < N; ++i) vm = fmaxf(vm, z[i]);
+  if (vm > p.m) {
+    float d = p.m - vm, a = __expf(d);
+    p.t = a * (p.t + d * p.s);
+    p.s *= a;
+    p.w *= a;
+    p.m = vm;
+#pragma unroll
+    for (int i = 0; i < N; ++i)
+      if (z[i] > p.bv) { p.bv = z[i]; p.bi = v0 + i; }   // ascending ids + strict '>' keep the lowest id
+  }
+#pragma unroll
+  for (int i = 0; i < N; ++i) {
+    float d = z[i] - p.m, e = __expf(d);
+    p.s += e;
+    p.t = fmaf(e, d, p.t);
+    if (KL) p.w = fmaf(e, z[i] - zp[i], p.w);
+  }
+  if (KL && PREV_SUMS) {
+    float pv = zp[0];
+#pragma unroll
+    for (int i = 1; i < N; ++i) pv = fmaxf(pv, zp[i]);
+    if (pv > p.pm) { p.ps *= __expf(p.pm - pv); p.pm = pv; }
+#pragma unroll
+    for (int i = 0; i < N; ++i) p.ps += __expf(zp[i] - p.pm);
+  }
+}
+
+__device__ inline void finalize(const Part& p, int row, bool has_prev, float prev_lse, const StatsOut& o, float* save_lse_slot) {
+  float ls = __logf(p.s);
+  float lse = p.m + ls;
+  o.max_logit[row] = p.m;
+  o.lse[row] = lse;
+  o.conf[row] = 1.0f / p.s;
+  o.entropy[row] = ls - p.t / p.s;
+  o.argmax[row] = p.bi;
+  o.kl[row] = has_prev ? (p.w / p.s - lse + prev_lse) : 0.f;
+  if (save_lse_slot) *save_lse_slot = lse;
+}
+
+// grid (chunks, rows).  Each workgroup reduces elements [c*chunk, (c+1)*chunk) of one row.
+template <typename T, bool VECTOR>
+__global__ __launch_bounds__(TPB) void vocab_stats_kernel(const T* __restrict__ logits, int vocab, int mask_id, int chunk,
+                                                          StatsRows sr, StatsOut o, Part* __restrict__ parts) {
+  constexpr int N = Vec<T>::N;
+  typedef typename Vec<T>::type V;
+  const int row = blockIdx.y, c = blockIdx.x, nchunks = gridDim.x;
+  const T* z_row = logits + (size_t)row * vocab;
+  const int64_t prow = sr.prev_row ? sr.prev_row[row] : (sr.prev_base ? (int64_t)row * vocab : -1);
+  const int64_t srow = sr.save_row ? sr.save_row[row] : -1;
+  const T* p_row = prow >= 0 ? (const T*)sr.prev_base + prow : nullptr;
+  T* s_row = srow >= 0 ? (T*)sr.save_base + srow : nullptr;
+  const bool kl = p_row != nullptr;
+  const bool prev_sums = kl && sr.prev_lse == nullptr;
+  const int lo = c * chunk, hi = min(vocab, lo + chunk);
+
+  Part p = part_init();
+  if (VECTOR) {
+    for (int v = lo + threadIdx.x * N; v < hi; v += TPB * N) {
+      V zv = *(const V*)(z_row + v);
+      float z[N], zp[N];
+#pragma unroll
+      for (int i = 0; i < N; ++i) { z[i] = to_f32(zv[i]); zp[i] = 0.f; }
+      if (s_row) *(V*)(s_row + v) = zv;
+      if (kl) {
+        V pv = *(const V*)(p_row + v);
+#pragma unroll
+        for (int i = 0; i < N; ++i) zp[i] = to_f32(pv[i]);
+      }
+      if (mask_id >= v && mask_id < v + N) { z[mask_id - v] = MASKED; zp[mask_id - v] = MASKED; }
+      if (!kl) absorb<N, false, false>(p, z, zp, v);
+      else if (!prev_sums) absorb<N, true, false>(p, z, zp, v);
+      else absorb<N, true, true>(p, z, zp, v);
+    }
+  } else {
+    for (int v = lo + threadIdx.x; v < hi; v += TPB) {
+      float z[1] = {to_f32(z_row[v])}, zp[1] = {0.f};
+      if (s_row) s_row[v] = z_row[v];
+      if (kl) zp[0] = to_f32(p_row[v]);
+      if (v == mask_id) { z[0] = MASKED; zp[0] = MASKED; }
+      if (!kl) absorb<1, false, false>(p, z, zp, v);
+      else if (!prev_sums) absorb<1, true, false>(p, z, zp, v);
+      else absorb<1, true, true>(p, z, zp, v);
+    }
+  }
+#pragma unroll
+  for (int ofs = 32; ofs > 0; ofs >>= 1) p = part_merge(p, part_shfl_xor(p, ofs));
+  __shared__ Part sh[TPB / 64];
+  if ((threadIdx.x & 63) == 0) sh[threadIdx.x >> 6] = p;
+  __syncthreads();
+  if (threadIdx.x == 0) {
+    Part r = sh[0];
+    for (int i = 1; i < TPB / 64; ++i) r = part_merge(r, sh[i]);
+    if (nchunks == 1) {
+      float pl = 0.f;
+      if (kl) pl = sr.prev_lse ? sr.prev_lse[prow / vocab] : r.pm + __logf(r.ps);
+      finalize(r, row, kl, pl, o, srow >= 0 && sr.save_lse ? sr.save_lse + srow / vocab : nullptr);
+    } else {
+      parts[(size_t)row * nchunks + c] = r;
+    }
+  }
+}
+
+__global__ void vocab_stats_merge_kernel(const Part* __restrict__ parts, int rows, int nchunks, int vocab, StatsRows sr, StatsOut o) {
+  int row = blockIdx.x * blockDim.x + threadIdx.x;
+  if (row >= rows) return;
+  Part r = parts[(size_t)row * nchunks];
+  for (int c = 1; c < nchunks; ++c) r = part_merge(r, parts[(size_t)row * nchunks + c]);
+  const int64_t prow = sr.prev_row ? sr.prev_row[row] : (sr.prev_base ? (int64_t)row * vocab : -1);
+  const int64_t srow = sr.save_row ? sr.save_row[row] : -1;
+  float pl = 0.f;
+  if (prow >= 0) pl = sr.prev_lse ? sr.prev_lse[prow / vocab] : r.pm + __logf(r.ps);
+  finalize(r, row, prow >= 0, pl, o, srow >= 0 && sr.save_lse ? sr.save_lse + srow / vocab : nullptr);
+}
+
+constexpr int MAX_CHUNKS = 32;
+
+int pick_chunks(int rows, int vocab, int vec) {
+  int want = (2048 + rows - 1) / rows;  // aim at >= 2048 workgroups
+  int maxc = (vocab + TPB * vec * 2 - 1) / (TPB * vec * 2);  // at least two vectors per lane
+  int c = want < maxc ? want : maxc;
+  if (c > MAX_CHUNKS) c = MAX_CHUNKS;
+  return c < 1 ? 1 : c;
+}
+
+}  // namespace
+
+size_t stats_workspace_bytes(int rows) { return (size_t)rows * MAX_CHUNKS * sizeof(Part); }
+
+template <typename T>
+void launch_vocab_stats(const T* logits, int rows, int vocab, int mask_id, const StatsRows& sr, const StatsOut& o, void* workspace, hipStream_t st) {
+  constexpr int N = Vec<T>::N;
+  const bool vec = vocab % N == 0;
+  int nch = pick_chunks(rows, vocab, N);
+  int chunk = (vocab + nch - 1) / nch;
+  chunk = (chunk + TPB * N - 1) / (TPB * N) * (TPB * N);
+  nch = (vocab + chunk - 1) / chunk;
+  dim3 grid(nch, rows);
+  if (vec) vocab_stats_kernel<T, true><<<grid, TPB, 0, st>>>(logits, vocab, mask_id, chunk, sr, o, (Part*)workspace);
+  else vocab_stats_kernel<T, false><<<grid, TPB, 0, st>>>(logits, vocab, mask_id, chunk, sr, o, (Part*)workspace);
+  if (nch > 1) vocab_stats_merge_kernel<<<(rows + 63) / 64, 64, 0, st>>>((const Part*)workspace, rows, nch, vocab, sr, o);
+}
+
+template void launch_vocab_stats<float>(const float*, int, int, int, const StatsRows&, const StatsOut&, void*, hipStream_t);
+template void launch_vocab_stats<bf16_t>(const bf16_t*, int, int, int, const StatsRows&, const StatsOut&, void*, hipStream_t);
