@@ -130,9 +130,10 @@ int dlm_step(dlm_state* s, const dlm_step_desc* d, void* stream);
 
 /* ---- block_boundary ------------------------------------------------------------------------ */
 
-/* DepGA-Block (Sec. 4.2).  For sequence b the candidate window is the W_b = win_offsets[b+1] -
- * win_offsets[b] positions after the frontier (the caller sizes it: W = min(L_max, L_remain),
- * 1 <= W_b <= 256); I = last-block influence (Eq. 3), H = entropy of those positions.
+/* DepGA-Block (Sec. 4.2).  For sequence b the candidate window is the W_b = win_len[b] positions
+ * after the frontier, stored at I[win_start[b] ...], H[win_start[b] ...] (the caller sizes it:
+ * W = min(L_max, L_remain), 1 <= W_b <= 256); I = last-block influence (Eq. 3), H = entropy of
+ * those positions (the kl and entropy outputs of dlm_step can be passed as they are).
  * Both signals are smoothed (centred moving average of radius smooth_radius, truncated at the
  * window edges) and normalised inside the window (norm_mode 0: by the window mean, 1: by the
  * window max, 2: min-max, 3: not at all), S_k = I~_k - lambda H~_k (Eq. 4), and
@@ -140,7 +141,7 @@ int dlm_step(dlm_state* s, const dlm_step_desc* d, void* stream);
  *   rule 1: before the first k whose prefix sum S_0 + ... + S_k < 0 (the cumulative form, Sec. 4.4),
  * whole window if there is none; L is clipped to [l_min, W_b] (the window wins).  cold[b] != 0:
  * first block, L = min(l_min, W_b) and the signals are not read (cold may be NULL).
- * Outputs: L_out DEVICE [n_seqs]; S_out DEVICE [sum W_b] (nullable); margin_out DEVICE [n_seqs]
+ * Outputs: L_out DEVICE [n_seqs]; S_out DEVICE, indexed like I (nullable); margin_out DEVICE [n_seqs]
  * (nullable) = the smallest |decision quantity| examined up to the crossing.
  * Errors: DLM_EINVAL (null, n_seqs < 1, lambda <= 0, l_min < 1, bad mode/rule, radius < 0),
  * DLM_ECAPACITY (W_b < 1 or > 256, n_seqs > 32). */
@@ -149,7 +150,7 @@ typedef struct {
   int32_t l_min, smooth_radius, norm_mode, rule;
 } dlm_boundary_params;
 
-int block_boundary(const float* I, const float* H, const int32_t* win_offsets, const int32_t* cold,
+int block_boundary(const float* I, const float* H, const int32_t* win_start, const int32_t* win_len, const int32_t* cold,
                    int n_seqs, const dlm_boundary_params* p, int32_t* L_out, float* S_out,
                    float* margin_out, void* stream);
 

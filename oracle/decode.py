@@ -34,13 +34,14 @@ from .select import select_parallel
 from .stats import vocab_stats
 
 
-def decode_full(cfg, W, prompt, n_gen, prm, trace=None):
+def decode_full(cfg, W, prompt, n_gen, prm, trace=None, max_passes=None):
     """prm: dict(l_min, l_max, lam, smooth_radius, norm_mode, rule, tau_low, tau_high, gamma, mode).
 
     Returns dict(tokens [P+N], nfe, blocks [list of L], steps [tokens written per
     denoising step]).  If trace is a list, one record per forward pass and per
     decision is appended (inputs and outputs, for replay against another
-    implementation).
+    implementation).  max_passes stops the decode early after that many forward
+    passes (for sampling the first passes of a large model); the result is then partial.
     """
     mask = cfg["mask_id"]
     P, N = len(prompt), n_gen
@@ -50,8 +51,13 @@ def decode_full(cfg, W, prompt, n_gen, prm, trace=None):
     nfe, blocks, steps = 0, [], []
     l_min, l_max = prm["l_min"], prm["l_max"]
 
+    class _Stop(Exception):
+        pass
+
     def run_pass(kind, start, rows, commit):
         nonlocal nfe
+        if max_passes is not None and nfe >= max_passes:
+            raise _Stop
         toks = y[start : start + rows].copy()
         z = forward_span(cfg, W, cache, toks, start, commit)
         nfe += 1
@@ -59,45 +65,48 @@ def decode_full(cfg, W, prompt, n_gen, prm, trace=None):
             trace.append(dict(op="pass", kind=kind, span_start=start, tokens=toks, commit_len=commit, logits=z))
         return z
 
-    Lk = min(2 * l_max, N)
-    z = run_pass("prefill", 0, P + Lk, P)
-    prev_base, prev_z = P, z[P:]
-    F = P
-    L, _, _ = block_boundary(np.zeros(min(l_max, N)), np.zeros(min(l_max, N)), prm["lam"], l_min, cold_start=True)
-    zb = prev_z[:L]
-    while True:
-        blocks.append(L)
-        while True:  # denoising steps of block [F, F+L)
-            st = vocab_stats(zb, mask)
-            elig = y[F : F + L] == mask
-            sel, mrg = select_parallel(
-                zb, st["lse"], st["conf"], st["argmax"], elig,
-                prm["tau_low"], prm["tau_high"], prm["gamma"], prm.get("mode", 0),
+    try:
+        Lk = min(2 * l_max, N)
+        z = run_pass("prefill", 0, P + Lk, P)
+        prev_base, prev_z = P, z[P:]
+        F = P
+        L, _, _ = block_boundary(np.zeros(min(l_max, N)), np.zeros(min(l_max, N)), prm["lam"], l_min, cold_start=True)
+        zb = prev_z[:L]
+        while True:
+            blocks.append(L)
+            while True:  # denoising steps of block [F, F+L)
+                st = vocab_stats(zb, mask)
+                elig = y[F : F + L] == mask
+                sel, mrg = select_parallel(
+                    zb, st["lse"], st["conf"], st["argmax"], elig,
+                    prm["tau_low"], prm["tau_high"], prm["gamma"], prm.get("mode", 0),
+                )
+                if trace is not None:
+                    trace.append(dict(op="select", F=F, L=L, stats=st, eligible=elig.copy(), selected=sel.copy(), margin=mrg))
+                idx = np.nonzero(sel)[0]
+                assert idx.size >= 1 and elig[idx].all()
+                y[F + idx] = st["argmax"][idx]  # Eq. 2
+                steps.append(int(idx.size))
+                if not (y[F : F + L] == mask).any():
+                    break
+                zb = run_pass("inblock", F, L, 0)
+            R = END - (F + L)
+            if R == 0:
+                break
+            Lk = min(2 * l_max, R)
+            Wn = min(l_max, R)
+            z = run_pass("boundary", F, L + Lk, L)
+            look = z[L:]
+            off = F + L - prev_base
+            st = vocab_stats(look[:Wn], mask, z_prev=prev_z[off : off + Wn])
+            Lnext, S, mrg = block_boundary(
+                st["kl"], st["entropy"], prm["lam"], l_min, prm["smooth_radius"], prm["norm_mode"], prm["rule"]
             )
             if trace is not None:
-                trace.append(dict(op="select", F=F, L=L, stats=st, eligible=elig.copy(), selected=sel.copy(), margin=mrg))
-            idx = np.nonzero(sel)[0]
-            assert idx.size >= 1 and elig[idx].all()
-            y[F + idx] = st["argmax"][idx]  # Eq. 2
-            steps.append(int(idx.size))
-            if not (y[F : F + L] == mask).any():
-                break
-            zb = run_pass("inblock", F, L, 0)
-        R = END - (F + L)
-        if R == 0:
-            break
-        Lk = min(2 * l_max, R)
-        Wn = min(l_max, R)
-        z = run_pass("boundary", F, L + Lk, L)
-        look = z[L:]
-        off = F + L - prev_base
-        st = vocab_stats(look[:Wn], mask, z_prev=prev_z[off : off + Wn])
-        Lnext, S, mrg = block_boundary(
-            st["kl"], st["entropy"], prm["lam"], l_min, prm["smooth_radius"], prm["norm_mode"], prm["rule"]
-        )
-        if trace is not None:
-            trace.append(dict(op="boundary", F=F + L, W=Wn, kl=st["kl"], entropy=st["entropy"], L=Lnext, S=S, margin=mrg))
-        prev_base, prev_z = F + L, look
-        F, L = F + L, Lnext
-        zb = look[:L]
+                trace.append(dict(op="boundary", F=F + L, W=Wn, kl=st["kl"], entropy=st["entropy"], L=Lnext, S=S, margin=mrg))
+            prev_base, prev_z = F + L, look
+            F, L = F + L, Lnext
+            zb = look[:L]
+    except _Stop:
+        pass
     return dict(tokens=y, nfe=nfe, blocks=blocks, steps=steps)

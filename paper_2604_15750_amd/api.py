@@ -77,7 +77,7 @@ def lib():
         L.dlm_state_reset.argtypes = [C.c_void_p, C.c_int]
         L.dlm_state_kv_len.argtypes = [C.c_void_p, C.c_int]
         L.dlm_step.argtypes = [C.c_void_p, C.POINTER(dlm_step_desc), C.c_void_p]
-        L.block_boundary.argtypes = [C.c_void_p, C.c_void_p, _I32P, _I32P, C.c_int, C.POINTER(dlm_boundary_params), C.c_void_p,
+        L.block_boundary.argtypes = [C.c_void_p, C.c_void_p, _I32P, _I32P, _I32P, C.c_int, C.POINTER(dlm_boundary_params), C.c_void_p,
                                      C.c_void_p, C.c_void_p, C.c_void_p]
         L.select_parallel.argtypes = [C.c_void_p, C.c_int, C.c_int, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, _I32P, _I32P, _I32P,
                                       C.c_int, C.c_int, C.POINTER(dlm_select_params), C.c_int, C.c_void_p, C.c_void_p, C.c_void_p,
@@ -192,9 +192,10 @@ def dlm_step(state, tokens, out, row_offsets, span_start, commit_len, tok_start,
     _check(lib().dlm_step(state.handle, C.byref(d), _stream()))
 
 
-def block_boundary(I, H, win_offsets, L_out, lam, l_min, smooth_radius=1, norm_mode=0, rule=0, cold=None, S_out=None, margin_out=None):
+def block_boundary(I, H, win_start, win_len, L_out, lam, l_min, smooth_radius=1, norm_mode=0, rule=0, cold=None, S_out=None,
+                   margin_out=None):
     p = dlm_boundary_params(lam, l_min, smooth_radius, norm_mode, rule)
-    _check(lib().block_boundary(_ptr(I), _ptr(H), _ints(win_offsets), _ints(cold), len(win_offsets) - 1, C.byref(p), _ptr(L_out),
+    _check(lib().block_boundary(_ptr(I), _ptr(H), _ints(win_start), _ints(win_len), _ints(cold), len(win_start), C.byref(p), _ptr(L_out),
                                 _ptr(S_out), _ptr(margin_out), _stream()))
 
 

@@ -72,7 +72,7 @@ __global__ __launch_bounds__(TPB) void block_boundary_kernel(const float* __rest
   __shared__ double buf[NW];
   __shared__ int first_neg[NW];
   const int b = blockIdx.x, k = threadIdx.x;
-  const int off = meta.win_off[b], W = meta.win_off[b + 1] - off;
+  const int off = meta.win_start[b], W = meta.win_len[b];
   if (meta.cold[b]) {  // first block: conservative cold start
     if (k < W && S_out) S_out[off + k] = 0.f;
     if (k == 0) {

@@ -74,7 +74,8 @@ struct AttnMeta {
   int32_t slot[DLM_MAX_SEQS];
 };
 struct BoundaryMeta {
-  int32_t win_off[DLM_MAX_SEQS + 1];
+  int32_t win_start[DLM_MAX_SEQS];
+  int32_t win_len[DLM_MAX_SEQS];
   int32_t cold[DLM_MAX_SEQS];
 };
 struct SelectMeta {

@@ -408,9 +408,9 @@ extern "C" int dlm_step(dlm_state* s, const dlm_step_desc* d, void* stream) {
 }
 
 // ---- block_boundary / select_parallel ------------------------------------------------------------
-extern "C" int block_boundary(const float* I, const float* H, const int32_t* win_offsets, const int32_t* cold, int n_seqs,
+extern "C" int block_boundary(const float* I, const float* H, const int32_t* win_start, const int32_t* win_len, const int32_t* cold, int n_seqs,
                               const dlm_boundary_params* p, int32_t* L_out, float* S_out, float* margin_out, void* stream) {
-  REQUIRE(I && H && win_offsets && p && L_out, DLM_EINVAL, "block_boundary: null argument");
+  REQUIRE(I && H && win_start && win_len && p && L_out, DLM_EINVAL, "block_boundary: null argument");
   REQUIRE(n_seqs >= 1, DLM_EINVAL, "block_boundary: n_seqs %d < 1", n_seqs);
   REQUIRE(n_seqs <= DLM_MAX_SEQS, DLM_ECAPACITY, "block_boundary: n_seqs %d > %d", n_seqs, DLM_MAX_SEQS);
   REQUIRE(p->lambda > 0.f, DLM_EINVAL, "block_boundary: lambda must be positive");
@@ -421,12 +421,13 @@ extern "C" int block_boundary(const float* I, const float* H, const int32_t* win
   BoundaryMeta meta;
   memset(&meta, 0, sizeof meta);
   for (int b = 0; b < n_seqs; ++b) {
-    const int W = win_offsets[b + 1] - win_offsets[b];
+    const int W = win_len[b];
     REQUIRE(W >= 1 && W <= 256, DLM_ECAPACITY, "block_boundary: window %d of sequence %d not in [1,256]", W, b);
-    REQUIRE(win_offsets[b] >= 0, DLM_EINVAL, "block_boundary: negative offset");
+    REQUIRE(win_start[b] >= 0, DLM_EINVAL, "block_boundary: negative offset");
     meta.cold[b] = cold ? (cold[b] != 0) : 0;
+    meta.win_start[b] = win_start[b];
+    meta.win_len[b] = W;
   }
-  for (int b = 0; b <= n_seqs; ++b) meta.win_off[b] = win_offsets[b];
   launch_block_boundary(I, H, meta, n_seqs, *p, L_out, S_out, margin_out, (hipStream_t)stream);
   return DLM_OK;
 }

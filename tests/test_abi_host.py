@@ -41,14 +41,15 @@ def test_block_boundary_argument_errors():
     L = api.lib()
     one = C.c_void_p(16)  # never dereferenced: validation fails first
     p = api.dlm_boundary_params(1.2, 8, 1, 0, 0)
-    off = (C.c_int32 * 2)(0, 4)
-    call = lambda I=one, H=one, o=off, n=1, pp=p, Lo=one: L.block_boundary(I, H, o, None, n, C.byref(pp), Lo, None, None, None)
+    z = (C.c_int32 * 1)(0)
+    off = (C.c_int32 * 1)(4)
+    call = lambda I=one, H=one, o=off, n=1, pp=p, Lo=one: L.block_boundary(I, H, z, o, None, n, C.byref(pp), Lo, None, None, None)
     assert call(I=None) == -1 and "null" in _err()
     assert call(Lo=None) == -1
     assert call(n=0) == -1
     assert call(n=33) == -3
-    assert call(o=(C.c_int32 * 2)(0, 0)) == -3 and "window" in _err()
-    assert call(o=(C.c_int32 * 2)(0, 257)) == -3
+    assert call(o=(C.c_int32 * 1)(0)) == -3 and "window" in _err()
+    assert call(o=(C.c_int32 * 1)(257)) == -3
     for bad in (api.dlm_boundary_params(0.0, 8, 1, 0, 0), api.dlm_boundary_params(1.2, 0, 1, 0, 0),
                 api.dlm_boundary_params(1.2, 8, -1, 0, 0), api.dlm_boundary_params(1.2, 8, 1, 4, 0),
                 api.dlm_boundary_params(1.2, 8, 1, 0, 2)):

@@ -133,7 +133,7 @@ def test_block_boundary(device, norm_mode, rule):
         L = torch.empty(n, dtype=torch.int32, device=device)
         S = torch.empty(int(off[-1]), dtype=torch.float32, device=device)
         mg = torch.empty(n, dtype=torch.float32, device=device)
-        api.block_boundary(torch.from_numpy(I).to(device), torch.from_numpy(H).to(device), off.tolist(), L, lam, l_min, r, norm_mode,
+        api.block_boundary(torch.from_numpy(I).to(device), torch.from_numpy(H).to(device), off[:-1].tolist(), Ws, L, lam, l_min, r, norm_mode,
                            rule, cold=cold, S_out=S, margin_out=mg)
         torch.cuda.synchronize()
         L, S, mg = L.cpu().numpy(), S.cpu().numpy(), mg.cpu().numpy()
