@@ -92,7 +92,7 @@ class KVCache:
 
     @property
     def kv_len(self):
-        return self.k[0].shape[0]
+        return self.k[0].shape[0] if self.k else 0
 
 
 def forward_span(cfg, W, cache, tokens, span_start, commit_len):

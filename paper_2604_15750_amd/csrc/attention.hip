@@ -2,8 +2,8 @@
 // [0, n_keys) of the sequence's KV-cache slot (cached prefix + the span's own rows, which the
 // rotary/KV kernel has already written there).  Grouped-query heads share K/V.
 //
-// Generic kernel (any dtype, head_dim 32/64/128): one workgroup per (16-query tile, head,
-// sequence); keys are streamed in tiles through LDS with an online softmax in fp32.
+// fp32 kernel (head_dim 32/64/128, row-major cache [pos][n_kv*hd]): one workgroup per (16-query
+// tile, head, sequence); keys are streamed in tiles through LDS with an online softmax in fp32.
 #include "common.h"
 
 namespace {
@@ -96,15 +96,154 @@ __global__ __launch_bounds__(256) void attention_kernel(const T* __restrict__ q,
   }
 }
 
+// ---- bf16 kernel on the matrix cores --------------------------------------------------------------
+// The bf16 KV cache is kept per (slot, kv head) in matrix-core fragment tiles (kv_k_index /
+// kv_v_index), so a wavefront fetches a K operand (16 keys x 32 dims) or a V^T operand
+// (16 dims x 32 keys) as 64 consecutive 16-byte pieces.  One workgroup per (16-query tile, head,
+// sequence); its four wavefronts take every fourth block of 32 keys with their own online-softmax
+// state and are merged through LDS.  S^T = K Q^T puts 8 keys of one query in each lane (the lane's
+// query is lane%16 in both S^T and O^T), so the probabilities feed the second product straight
+// from registers: the V tiling stores keys in the order the first product emits them.
+template <int HD>
+__global__ __launch_bounds__(256) void attention_mfma_kernel(const bf16_t* __restrict__ q, const bf16_t* __restrict__ kcache,
+                                                             const bf16_t* __restrict__ vcache, size_t slot_stride, size_t head_stride,
+                                                             AttnMeta meta, bf16_t* __restrict__ out, bool out_tiled, int n_q, int n_kv) {
+  constexpr int KS = HD / 32, DT = HD / 16;
+  __shared__ float sm[4][16], sl[4][16];
+  __shared__ float so[4][HD][17];
+
+  const int b = blockIdx.z, head = blockIdx.y;
+  const int row0 = meta.row_off[b] + blockIdx.x * 16;
+  const int row_end = meta.row_off[b + 1];
+  if (row0 >= row_end) return;
+  const int n_keys = meta.n_keys[b];
+  const int kvh = head / (n_q / n_kv);
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, g = lane >> 4, c = lane & 15;
+  const float scale = rsqrtf((float)HD);
+  const bf16x8 zero8 = {0, 0, 0, 0, 0, 0, 0, 0};
+
+  bf16x8 qf[KS];
+  {
+    const int r = row0 + c;
+#pragma unroll
+    for (int t = 0; t < KS; ++t)
+      qf[t] = r < row_end ? *(const bf16x8*)(q + (size_t)r * n_q * HD + (size_t)head * HD + 32 * t + 8 * g) : zero8;
+  }
+  const bf16x8* kt = (const bf16x8*)(kcache + (size_t)meta.slot[b] * slot_stride + (size_t)kvh * head_stride);
+  const bf16x8* vt = (const bf16x8*)(vcache + (size_t)meta.slot[b] * slot_stride + (size_t)kvh * head_stride);
+
+  float m = NEG_BIG, l = 0.f;
+  f32x4 o[DT];
+#pragma unroll
+  for (int dt = 0; dt < DT; ++dt) o[dt] = f32x4{0.f, 0.f, 0.f, 0.f};
+
+  const int nblk = (n_keys + 31) >> 5;
+  for (int blk = wave; blk < nblk; blk += 4) {
+    f32x4 s0 = {0.f, 0.f, 0.f, 0.f}, s1 = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+    for (int t = 0; t < KS; ++t) {
+      const bf16x8 k0 = kt[((size_t)(blk * 2) * KS + t) * 64 + lane];
+      const bf16x8 k1 = kt[((size_t)(blk * 2 + 1) * KS + t) * 64 + lane];
+      s0 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(k0, qf[t], s0, 0, 0, 0);
+      s1 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(k1, qf[t], s1, 0, 0, 0);
+    }
+    // lane holds, for query c, keys blk*32 + 4g + i (s0) and + 16 (s1)
+    const int key0 = blk * 32 + 4 * g;
+    float sv[8];
+    bool ok[8];
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      ok[i] = key0 + i < n_keys;
+      ok[4 + i] = key0 + 16 + i < n_keys;
+      sv[i] = ok[i] ? s0[i] * scale : NEG_BIG;
+      sv[4 + i] = ok[4 + i] ? s1[i] * scale : NEG_BIG;
+    }
+    float mx = sv[0];
+#pragma unroll
+    for (int i = 1; i < 8; ++i) mx = fmaxf(mx, sv[i]);
+    mx = fmaxf(mx, __shfl_xor(mx, 16, 64));
+    mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
+    const float mn = fmaxf(m, mx);
+    const float corr = __expf(m - mn);
+    float pv[8], ps = 0.f;
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+      pv[i] = ok[i] ? __expf(sv[i] - mn) : 0.f;
+      ps += pv[i];
+    }
+    ps += __shfl_xor(ps, 16, 64);
+    ps += __shfl_xor(ps, 32, 64);
+    l = l * corr + ps;
+    m = mn;
+    const bf16x8 pb = {(bf16_t)pv[0], (bf16_t)pv[1], (bf16_t)pv[2], (bf16_t)pv[3], (bf16_t)pv[4], (bf16_t)pv[5], (bf16_t)pv[6], (bf16_t)pv[7]};
+#pragma unroll
+    for (int dt = 0; dt < DT; ++dt) {
+      const bf16x8 vf = vt[((size_t)blk * DT + dt) * 64 + lane];
+      o[dt] *= corr;
+      o[dt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(vf, pb, o[dt], 0, 0, 0);
+    }
+  }
+  // merge the four wavefronts
+  if (g == 0) { sm[wave][c] = m; sl[wave][c] = l; }
+#pragma unroll
+  for (int dt = 0; dt < DT; ++dt)
+#pragma unroll
+    for (int i = 0; i < 4; ++i) so[wave][16 * dt + 4 * g + i][c] = o[dt][i];
+  __syncthreads();
+  constexpr int CH = HD / 16;  // each thread finishes CH consecutive dims of one query
+  const int qi = tid & 15, d0 = (tid >> 4) * CH;
+  float M = fmaxf(fmaxf(sm[0][qi], sm[1][qi]), fmaxf(sm[2][qi], sm[3][qi]));
+  float w[4], Lsum = 0.f;
+#pragma unroll
+  for (int wv = 0; wv < 4; ++wv) { w[wv] = __expf(sm[wv][qi] - M); Lsum += w[wv] * sl[wv][qi]; }
+  const int r = row0 + qi;
+  if (r < row_end) {
+    const int width = n_q * HD;
+#pragma unroll
+    for (int j = 0; j < CH; ++j) {
+      const int d = d0 + j;
+      float acc = 0.f;
+#pragma unroll
+      for (int wv = 0; wv < 4; ++wv) acc += w[wv] * so[wv][d][qi];
+      const int col = head * HD + d;
+      const size_t idx = out_tiled ? tile_index(r, col, width) : (size_t)r * width + col;
+      out[idx] = (bf16_t)(acc / Lsum);
+    }
+  }
+}
+
+// K [T, n_kv, hd] and V row-major -> the tiled cache layout of one slot (test helper for dlm_attention)
+__global__ void pack_kv_kernel(const bf16_t* __restrict__ k, const bf16_t* __restrict__ v, bf16_t* __restrict__ kt, bf16_t* __restrict__ vt,
+                               int T, int n_kv, int hd, size_t head_stride) {
+  const size_t total = (size_t)T * n_kv * hd;
+  for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < total; i += (size_t)gridDim.x * blockDim.x) {
+    const int d = i % hd, h = (i / hd) % n_kv, pos = i / ((size_t)hd * n_kv);
+    kt[(size_t)h * head_stride + kv_k_index(pos, d, hd)] = k[i];
+    vt[(size_t)h * head_stride + kv_v_index(pos, d, hd)] = v[i];
+  }
+}
+
 }  // namespace
 
-template <typename T>
-void launch_attention(const T* q, const T* kcache, const T* vcache, size_t slot_stride, const AttnMeta& meta, T* out, bool out_tiled,
-                      int rows, int max_seq_rows, int n_q, int n_kv, int hd, hipStream_t st) {
-  dim3 grid((max_seq_rows + QT - 1) / QT, n_q, meta.n_seqs);
-  if (hd == 32) attention_kernel<T, 32><<<grid, 256, 0, st>>>(q, kcache, vcache, slot_stride, meta, out, out_tiled, n_q, n_kv);
-  else if (hd == 64) attention_kernel<T, 64><<<grid, 256, 0, st>>>(q, kcache, vcache, slot_stride, meta, out, out_tiled, n_q, n_kv);
-  else attention_kernel<T, 128><<<grid, 256, 0, st>>>(q, kcache, vcache, slot_stride, meta, out, out_tiled, n_q, n_kv);
+void launch_pack_kv(const bf16_t* k, const bf16_t* v, bf16_t* kt, bf16_t* vt, int T, int n_kv, int hd, size_t head_stride, hipStream_t st) {
+  pack_kv_kernel<<<256, 256, 0, st>>>(k, v, kt, vt, T, n_kv, hd, head_stride);
 }
-template void launch_attention<float>(const float*, const float*, const float*, size_t, const AttnMeta&, float*, bool, int, int, int, int, int, hipStream_t);
-template void launch_attention<bf16_t>(const bf16_t*, const bf16_t*, const bf16_t*, size_t, const AttnMeta&, bf16_t*, bool, int, int, int, int, int, hipStream_t);
+
+template <>
+void launch_attention<float>(const float* q, const float* kcache, const float* vcache, size_t slot_stride, size_t head_stride, const AttnMeta& meta,
+                             float* out, bool out_tiled, int rows, int max_seq_rows, int n_q, int n_kv, int hd, hipStream_t st) {
+  dim3 grid((max_seq_rows + QT - 1) / QT, n_q, meta.n_seqs);
+  if (hd == 32) attention_kernel<float, 32><<<grid, 256, 0, st>>>(q, kcache, vcache, slot_stride, meta, out, out_tiled, n_q, n_kv);
+  else if (hd == 64) attention_kernel<float, 64><<<grid, 256, 0, st>>>(q, kcache, vcache, slot_stride, meta, out, out_tiled, n_q, n_kv);
+  else attention_kernel<float, 128><<<grid, 256, 0, st>>>(q, kcache, vcache, slot_stride, meta, out, out_tiled, n_q, n_kv);
+}
+
+template <>
+void launch_attention<bf16_t>(const bf16_t* q, const bf16_t* kcache, const bf16_t* vcache, size_t slot_stride, size_t head_stride,
+                              const AttnMeta& meta, bf16_t* out, bool out_tiled, int rows, int max_seq_rows, int n_q, int n_kv, int hd,
+                              hipStream_t st) {
+  dim3 grid((max_seq_rows + 15) / 16, n_q, meta.n_seqs);
+  if (hd == 32) attention_mfma_kernel<32><<<grid, 256, 0, st>>>(q, kcache, vcache, slot_stride, head_stride, meta, out, out_tiled, n_q, n_kv);
+  else if (hd == 64) attention_mfma_kernel<64><<<grid, 256, 0, st>>>(q, kcache, vcache, slot_stride, head_stride, meta, out, out_tiled, n_q, n_kv);
+  else attention_mfma_kernel<128><<<grid, 256, 0, st>>>(q, kcache, vcache, slot_stride, head_stride, meta, out, out_tiled, n_q, n_kv);
+}

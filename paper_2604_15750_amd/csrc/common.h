@@ -28,6 +28,17 @@ __host__ __device__ inline size_t tile_index(int m, int k, int K) {
   return ((size_t)(m >> 4) * (size_t)(K >> 5) + (size_t)(k >> 5)) * 512 + (size_t)(((m & 15) + 16 * ((k & 31) >> 3)) * 8 + (k & 7));
 }
 
+// bf16 KV cache of one (slot, kv head): K in tiles of 16 positions x 32 dims (A operand of S^T = K Q^T), V in tiles of 16 dims x 32
+// positions (A operand of O^T = V^T P^T) whose 8-element lane slots hold positions {4g..4g+3, 16+4g..16+4g+3} of the 32-block: the order in
+// which the first product leaves the keys in a lane's registers.
+__host__ __device__ inline size_t kv_k_index(int pos, int d, int hd) {
+  return ((size_t)(pos >> 4) * (size_t)(hd >> 5) + (size_t)(d >> 5)) * 512 + (size_t)(((pos & 15) + 16 * ((d & 31) >> 3)) * 8 + (d & 7));
+}
+__host__ __device__ inline size_t kv_v_index(int pos, int d, int hd) {
+  const int p32 = pos & 31, r = p32 & 15, g = r >> 2, j = (r & 3) + 4 * (p32 >> 4);
+  return ((size_t)(pos >> 5) * (size_t)(hd >> 4) + (size_t)(d >> 4)) * 512 + (size_t)(((d & 15) + 16 * g) * 8 + j);
+}
+
 template <typename T> struct Act;
 template <> struct Act<float> {
   static __device__ inline size_t idx(int m, int k, int K) { return (size_t)m * K + k; }
@@ -116,11 +127,14 @@ void launch_silu_mul(const float* part, int splits, T* act, int rows, int ffn, h
 // rotary embedding of Q and K; Q -> q [rows, n_q*hd] row-major; K, V -> cache[slot][pos]
 template <typename T>
 void launch_rope_kv(const float* part, int splits, const RowTables& t, const SeqMeta& meta, T* q, T* kcache, T* vcache,
-                    size_t slot_stride, int rows, int n_q, int n_kv, int hd, hipStream_t st);
+                    size_t slot_stride, size_t head_stride, int rows, int n_q, int n_kv, int hd, hipStream_t st);
 // softmax(q k^T / sqrt(hd)) v over keys [0, n_keys) of the row's slot; q row-major, out in the activation layout [rows, n_q*hd]
+// (out_tiled) or row-major.  fp32 cache: row-major [pos][n_kv*hd] per slot (head_stride unused); bf16 cache: per (slot, kv head)
+// a region of head_stride elements in the fragment tiling below.
 template <typename T>
-void launch_attention(const T* q, const T* kcache, const T* vcache, size_t slot_stride, const AttnMeta& meta, T* out, bool out_tiled,
-                      int rows, int max_seq_rows, int n_q, int n_kv, int hd, hipStream_t st);
+void launch_attention(const T* q, const T* kcache, const T* vcache, size_t slot_stride, size_t head_stride, const AttnMeta& meta, T* out,
+                      bool out_tiled, int rows, int max_seq_rows, int n_q, int n_kv, int hd, hipStream_t st);
+void launch_pack_kv(const bf16_t* k, const bf16_t* v, bf16_t* kt, bf16_t* vt, int T, int n_kv, int hd, size_t head_stride, hipStream_t st);
 
 struct StatsOut {
   float *max_logit, *lse, *entropy, *kl, *conf;

@@ -68,6 +68,7 @@ struct dlm_state {
   const dlm_model* m;
   int max_seqs, max_seq_len, max_rows, max_rows_pad, max_lookahead;
   size_t slot_stride;   // elements per slot per layer in the KV cache
+  size_t head_stride;   // bf16: elements per (slot, kv head) region of the tiled cache
   size_t layer_stride;  // elements per layer
   DevBuf kcache, vcache, prev_logits, prev_lse;
   DevBuf h, x, x2, act, q, part, stats_ws;
@@ -179,7 +180,8 @@ extern "C" int dlm_state_create(const dlm_model* m, int max_seqs, int max_seq_le
   s->max_rows_pad = (max_rows + 15) / 16 * 16;
   const size_t es = elem_size(c.dtype);
   const int kvw = c.n_kv_heads * c.head_dim, qd = c.n_q_heads * c.head_dim, qkv = qd + 2 * kvw;
-  s->slot_stride = (size_t)max_seq_len * kvw;
+  s->head_stride = (size_t)((max_seq_len + 31) / 32 * 32) * c.head_dim;
+  s->slot_stride = c.dtype == DLM_BF16 ? s->head_stride * c.n_kv_heads : (size_t)max_seq_len * kvw;
   s->layer_stride = s->slot_stride * max_seqs;
   // split-K workspace: the largest [splits][rows][N] over the four per-layer GEMMs
   size_t pe = 0;
@@ -212,7 +214,10 @@ extern "C" int dlm_state_create(const dlm_model* m, int max_seqs, int max_seq_le
   A(s->prev_row, (size_t)max_rows * 8); A(s->save_row, (size_t)max_rows * 8);
   if (rc == DLM_OK) {
     // padding rows of the tiled activations are read by the matrix cores: keep them finite
+    // cache positions beyond a sequence's keys are multiplied by zero probabilities: keep them finite too
     hipError_t e = hipMemset(s->x.p, 0, (size_t)s->max_rows_pad * xw * es);
+    if (e == hipSuccess) e = hipMemset(s->kcache.p, 0, s->layer_stride * c.n_layers * es);
+    if (e == hipSuccess) e = hipMemset(s->vcache.p, 0, s->layer_stride * c.n_layers * es);
     if (e == hipSuccess) e = hipMemset(s->x2.p, 0, (size_t)s->max_rows_pad * xw * es);
     if (e == hipSuccess) e = hipMemset(s->act.p, 0, (size_t)s->max_rows_pad * c.d_ffn * es);
     if (e != hipSuccess) rc = dlm_fail(DLM_EHIP, "dlm_state_create: hipMemset: %s", hipGetErrorString(e));
@@ -306,9 +311,9 @@ int run_step(dlm_state* s, const dlm_step_desc* d, const SeqMeta& meta, const St
     T* vc = (T*)s->vcache.p + s->layer_stride * l;
     gemm<T>(s, x, m->wqkv[l].p, rows, qd + 2 * nkv * hd, dm, &sp, st);
     { ProfScope ps(pf, st, 3); pf.launches[3] += pf.on;
-      launch_rope_kv<T>(part, sp, t, meta, q, kc, vc, s->slot_stride, rows, nq, nkv, hd, st); }
+      launch_rope_kv<T>(part, sp, t, meta, q, kc, vc, s->slot_stride, s->head_stride, rows, nq, nkv, hd, st); }
     { ProfScope ps(pf, st, 1); pf.launches[1] += pf.on;
-      launch_attention<T>(q, kc, vc, s->slot_stride, am, x2, true, rows, max_seq_rows, nq, nkv, hd, st); }
+      launch_attention<T>(q, kc, vc, s->slot_stride, s->head_stride, am, x2, true, rows, max_seq_rows, nq, nkv, hd, st); }
     gemm<T>(s, x2, m->wo[l].p, rows, dm, qd, &sp, st);
     { ProfScope ps(pf, st, 3); pf.launches[3] += pf.on;
       launch_reduce_residual_norm<T>(part, sp, h, (const float*)m->norm2[l].p, c.rms_eps, x, rows, dm, st); }
@@ -508,7 +513,21 @@ extern "C" int dlm_attention(const void* q, const void* k, const void* v, void* 
   memset(&am, 0, sizeof am);
   am.n_seqs = 1; am.row_off[1] = A; am.n_keys[0] = T;
   hipStream_t st = (hipStream_t)stream;
-  if (dtype == DLM_BF16) launch_attention<bf16_t>((const bf16_t*)q, (const bf16_t*)k, (const bf16_t*)v, 0, am, (bf16_t*)out, false, A, A, n_q, n_kv, head_dim, st);
-  else launch_attention<float>((const float*)q, (const float*)k, (const float*)v, 0, am, (float*)out, false, A, A, n_q, n_kv, head_dim, st);
+  if (dtype == DLM_F32) {
+    launch_attention<float>((const float*)q, (const float*)k, (const float*)v, 0, 0, am, (float*)out, false, A, A, n_q, n_kv, head_dim, st);
+    return DLM_OK;
+  }
+  // bf16: re-tile K and V into the cache layout first (test helper: allocates and synchronises)
+  const size_t head_stride = (size_t)((T + 31) / 32 * 32) * head_dim, bytes = head_stride * n_kv * 2;
+  void* ws = nullptr;
+  if (hipMalloc(&ws, 2 * bytes) != hipSuccess) { (void)hipGetLastError(); return dlm_fail(DLM_ENOMEM, "dlm_attention: workspace allocation failed"); }
+  bf16_t* kt = (bf16_t*)ws;
+  bf16_t* vt = kt + head_stride * n_kv;
+  hipError_t e = hipMemsetAsync(ws, 0, 2 * bytes, st);
+  launch_pack_kv((const bf16_t*)k, (const bf16_t*)v, kt, vt, T, n_kv, head_dim, head_stride, st);
+  launch_attention<bf16_t>((const bf16_t*)q, kt, vt, 0, head_stride, am, (bf16_t*)out, false, A, A, n_q, n_kv, head_dim, st);
+  if (e == hipSuccess) e = hipStreamSynchronize(st);
+  (void)hipFree(ws);
+  if (e != hipSuccess) return dlm_fail(DLM_EHIP, "dlm_attention: %s", hipGetErrorString(e));
   return DLM_OK;
 }

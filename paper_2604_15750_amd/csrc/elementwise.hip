@@ -97,8 +97,8 @@ __global__ __launch_bounds__(256) void silu_mul_kernel(const float* __restrict__
 // grid (rows, n_q + 2*n_kv heads), hd/2 lanes: one rotary pair per lane
 template <typename T>
 __global__ void rope_kv_kernel(const float* __restrict__ part, int splits, size_t split_stride, RowTables t, SeqMeta meta,
-                               T* __restrict__ q, T* __restrict__ kcache, T* __restrict__ vcache, size_t slot_stride, int n_q,
-                               int n_kv, int hd) {
+                               T* __restrict__ q, T* __restrict__ kcache, T* __restrict__ vcache, size_t slot_stride,
+                               size_t head_stride, int n_q, int n_kv, int hd) {
   const int r = blockIdx.x, head = blockIdx.y, i = threadIdx.x, half = hd >> 1;
   const int width = (n_q + 2 * n_kv) * hd;
   const float* src = part + (size_t)r * width + (size_t)head * hd;
@@ -114,15 +114,29 @@ __global__ void rope_kv_kernel(const float* __restrict__ part, int splits, size_
     a = ra;
     b = rb;
   }
-  T* dst;
   if (head < n_q) {
-    dst = q + (size_t)r * n_q * hd + (size_t)head * hd;
-  } else {
-    const size_t row = (size_t)meta.slot[t.row_seq[r]] * slot_stride + (size_t)pos * n_kv * hd;
-    dst = (head < n_q + n_kv) ? kcache + row + (size_t)(head - n_q) * hd : vcache + row + (size_t)(head - n_q - n_kv) * hd;
+    T* dst = q + (size_t)r * n_q * hd + (size_t)head * hd;
+    dst[i] = from_f32<T>(a);
+    dst[i + half] = from_f32<T>(b);
+    return;
   }
-  dst[i] = from_f32<T>(a);
-  dst[i + half] = from_f32<T>(b);
+  const bool is_k = head < n_q + n_kv;
+  const int kvh = is_k ? head - n_q : head - n_q - n_kv;
+  T* base = (is_k ? kcache : vcache) + (size_t)meta.slot[t.row_seq[r]] * slot_stride;
+  if (sizeof(T) == 4) {  // fp32 cache: row-major [pos][n_kv*hd]
+    T* dst = base + (size_t)pos * n_kv * hd + (size_t)kvh * hd;
+    dst[i] = from_f32<T>(a);
+    dst[i + half] = from_f32<T>(b);
+  } else {               // bf16 cache: fragment tiles per kv head
+    T* dst = base + (size_t)kvh * head_stride;
+    if (is_k) {
+      dst[kv_k_index(pos, i, hd)] = from_f32<T>(a);
+      dst[kv_k_index(pos, i + half, hd)] = from_f32<T>(b);
+    } else {
+      dst[kv_v_index(pos, i, hd)] = from_f32<T>(a);
+      dst[kv_v_index(pos, i + half, hd)] = from_f32<T>(b);
+    }
+  }
 }
 
 }  // namespace
@@ -146,15 +160,16 @@ void launch_silu_mul(const float* part, int splits, T* act, int rows, int ffn, h
 }
 template <typename T>
 void launch_rope_kv(const float* part, int splits, const RowTables& t, const SeqMeta& meta, T* q, T* kcache, T* vcache,
-                    size_t slot_stride, int rows, int n_q, int n_kv, int hd, hipStream_t st) {
+                    size_t slot_stride, size_t head_stride, int rows, int n_q, int n_kv, int hd, hipStream_t st) {
   dim3 grid(rows, n_q + 2 * n_kv);
-  rope_kv_kernel<T><<<grid, hd / 2, 0, st>>>(part, splits, (size_t)rows * (n_q + 2 * n_kv) * hd, t, meta, q, kcache, vcache, slot_stride, n_q, n_kv, hd);
+  rope_kv_kernel<T><<<grid, hd / 2, 0, st>>>(part, splits, (size_t)rows * (n_q + 2 * n_kv) * hd, t, meta, q, kcache, vcache, slot_stride,
+                                             head_stride, n_q, n_kv, hd);
 }
 
 #define INST(T)                                                                                                                       \
   template void launch_embed_norm<T>(const T*, const int32_t*, const RowTables&, const float*, float, float*, T*, int, int, hipStream_t); \
   template void launch_reduce_residual_norm<T>(const float*, int, float*, const float*, float, T*, int, int, hipStream_t);             \
   template void launch_silu_mul<T>(const float*, int, T*, int, int, hipStream_t);                                                      \
-  template void launch_rope_kv<T>(const float*, int, const RowTables&, const SeqMeta&, T*, T*, T*, size_t, int, int, int, int, hipStream_t);
+  template void launch_rope_kv<T>(const float*, int, const RowTables&, const SeqMeta&, T*, T*, T*, size_t, size_t, int, int, int, int, hipStream_t);
 INST(float)
 INST(bf16_t)

@@ -52,6 +52,7 @@ class Decoder:
         self.phase = ["prefill"] * self.B
         self.nfe, self.blocks, self.steps = [0] * self.B, [[] for _ in range(self.B)], [[] for _ in range(self.B)]
         self.launches = 0
+        self.rows_log = []  # rows of every dlm_step launch
 
     def _plan(self, b):
         """(span_start, rows, commit, kl_first, kl_count, save_first, save_count) of sequence b's next pass."""
@@ -91,6 +92,7 @@ class Decoder:
         api.dlm_step(self.state, self.tokens, out, row_off, col(0), col(2), [b * self.T + plans[b][0] for b in group], slot=group,
                      kl_first=col(3), kl_count=col(4), save_first=col(5), save_count=col(6))
         self.launches += 1
+        self.rows_log.append(row_off[-1])
         for b in group:
             self.nfe[b] += 1
         # block-boundary decisions for the sequences that just finished a block (or the prompt)
