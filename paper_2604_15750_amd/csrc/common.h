@@ -112,22 +112,33 @@ void launch_pack_act(const bf16_t* x, bf16_t* out, int M, int K, hipStream_t st)
 // Y = X * W^T.  xt: fragment-tiled [Mpad, K]; wt: tiled weights.  Exactly one of out_f32 / out_bf16
 // is non-null: out_f32 [splits][M][N] partial sums (splits from gemm_bf16_splits), out_bf16 [M][N] (splits = 1).
 int gemm_bf16_splits(int M, int N, int K);
-void launch_gemm_bf16(const bf16_t* xt, const bf16_t* wt, float* out_f32, bf16_t* out_bf16, int M, int N, int K, int splits, hipStream_t st);
-void launch_gemm_f32(const float* x, const float* w, float* y, int M, int N, int K, hipStream_t st);
+// rs (optional): every output row m is multiplied by rsqrt(sum_c rs.ssq[m][c] * rs.inv_d + rs.eps).
+struct RowScale {
+  const float* ssq;
+  int nch;
+  float inv_d, eps;
+};
+void launch_gemm_bf16(const bf16_t* xt, const bf16_t* wt, float* out_f32, bf16_t* out_bf16, int M, int N, int K, int splits, RowScale rs,
+                      hipStream_t st);
+void launch_gemm_f32(const float* x, const float* w, float* y, int M, int N, int K, RowScale rs, hipStream_t st);
 
 void launch_prepare(const SeqMeta& meta, const StatsMeta& sm, RowTables t, int rows, int vocab, int head_dim, float theta, hipStream_t st);
+// RMSNorm in two halves: producers write x = h * gain and per-row sums of squares ssq [rows][norm_chunks(d)]; the consumer of the
+// following GEMM multiplies rsqrt(sum(ssq)/d + eps) back in (a per-row scalar commutes with the GEMM).
+int norm_chunks(int d);
 template <typename T>
-void launch_embed_norm(const T* embed, const int32_t* tokens, const RowTables& t, const float* gain, float eps, float* h, T* x, int rows, int d, hipStream_t st);
-// h += sum_s part[s]; x = rmsnorm(h) * gain   (x in the activation layout of T)
+void launch_embed_norm(const T* embed, const int32_t* tokens, const RowTables& t, const float* gain, float* h, T* x, float* ssq, int rows,
+                       int d, hipStream_t st);
+// h += sum_s part[s]; x = h * gain; ssq
 template <typename T>
-void launch_reduce_residual_norm(const float* part, int splits, float* h, const float* gain, float eps, T* x, int rows, int d, hipStream_t st);
-// act = silu(gate) * up from part [splits][rows][2*ffn]
+void launch_reduce_residual_norm(const float* part, int splits, float* h, const float* gain, T* x, float* ssq, int rows, int d, hipStream_t st);
+// act = silu(gate) * up from rinv * part [splits][rows][2*ffn]
 template <typename T>
-void launch_silu_mul(const float* part, int splits, T* act, int rows, int ffn, hipStream_t st);
-// rotary embedding of Q and K; Q -> q [rows, n_q*hd] row-major; K, V -> cache[slot][pos]
+void launch_silu_mul(const float* part, int splits, const float* ssq, int d, float eps, T* act, int rows, int ffn, hipStream_t st);
+// rinv * part -> rotary embedding of Q and K; Q -> q [rows, n_q*hd] row-major; K, V -> cache[slot][pos]
 template <typename T>
-void launch_rope_kv(const float* part, int splits, const RowTables& t, const SeqMeta& meta, T* q, T* kcache, T* vcache,
-                    size_t slot_stride, size_t head_stride, int rows, int n_q, int n_kv, int hd, hipStream_t st);
+void launch_rope_kv(const float* part, int splits, const float* ssq, int d, float eps, const RowTables& t, const SeqMeta& meta, T* q,
+                    T* kcache, T* vcache, size_t slot_stride, size_t head_stride, int rows, int n_q, int n_kv, int hd, hipStream_t st);
 // softmax(q k^T / sqrt(hd)) v over keys [0, n_keys) of the row's slot; q row-major, out in the activation layout [rows, n_q*hd]
 // (out_tiled) or row-major.  fp32 cache: row-major [pos][n_kv*hd] per slot (head_stride unused); bf16 cache: per (slot, kv head)
 // a region of head_stride elements in the fragment tiling below.

@@ -71,7 +71,7 @@ struct dlm_state {
   size_t head_stride;   // bf16: elements per (slot, kv head) region of the tiled cache
   size_t layer_stride;  // elements per layer
   DevBuf kcache, vcache, prev_logits, prev_lse;
-  DevBuf h, x, x2, act, q, part, stats_ws;
+  DevBuf h, x, x2, act, q, part, stats_ws, ssq;
   DevBuf row_seq, row_pos, row_tok, rope_cos, rope_sin, prev_row, save_row;
   std::vector<int> kv_len, prev_cur, prev_base, prev_count;
   size_t part_elems;
@@ -209,6 +209,7 @@ extern "C" int dlm_state_create(const dlm_model* m, int max_seqs, int max_seq_le
   A(s->q, (size_t)max_rows * qd * es);
   A(s->part, pe * 4);
   A(s->stats_ws, stats_workspace_bytes(max_rows));
+  A(s->ssq, (size_t)max_rows * norm_chunks(c.d_model) * 4);
   A(s->row_seq, (size_t)max_rows * 4); A(s->row_pos, (size_t)max_rows * 4); A(s->row_tok, (size_t)max_rows * 4);
   A(s->rope_cos, (size_t)max_rows * (c.head_dim / 2) * 4); A(s->rope_sin, (size_t)max_rows * (c.head_dim / 2) * 4);
   A(s->prev_row, (size_t)max_rows * 8); A(s->save_row, (size_t)max_rows * 8);
@@ -279,10 +280,10 @@ void gemm(dlm_state* s, const void* x, const void* w, int M, int N, int K, int* 
   s->prof.launches[0] += s->prof.on;
   if (sizeof(T) == 2) {
     int sp = gemm_bf16_splits(M, N, K);
-    launch_gemm_bf16((const bf16_t*)x, (const bf16_t*)w, (float*)s->part.p, nullptr, M, N, K, sp, st);
+    launch_gemm_bf16((const bf16_t*)x, (const bf16_t*)w, (float*)s->part.p, nullptr, M, N, K, sp, RowScale{nullptr, 0, 0.f, 0.f}, st);
     *splits_out = sp;
   } else {
-    launch_gemm_f32((const float*)x, (const float*)w, (float*)s->part.p, M, N, K, st);
+    launch_gemm_f32((const float*)x, (const float*)w, (float*)s->part.p, M, N, K, RowScale{nullptr, 0, 0.f, 0.f}, st);
     *splits_out = 1;
   }
 }
@@ -298,38 +299,40 @@ int run_step(dlm_state* s, const dlm_step_desc* d, const SeqMeta& meta, const St
   float* h = (float*)s->h.p;
   T *x = (T*)s->x.p, *x2 = (T*)s->x2.p, *act = (T*)s->act.p, *q = (T*)s->q.p;
   float* part = (float*)s->part.p;
+  float* ssq = (float*)s->ssq.p;
   Profile& pf = s->prof;
   int sp = 1;
   {
     ProfScope ps(pf, st, 3);
     pf.launches[3] += 2 * pf.on;
     launch_prepare(meta, sm, t, rows, c.vocab, hd, c.rope_theta, st);
-    launch_embed_norm<T>((const T*)m->embed.p, d->tokens, t, (const float*)m->norm1[0].p, c.rms_eps, h, x, rows, dm, st);
+    launch_embed_norm<T>((const T*)m->embed.p, d->tokens, t, (const float*)m->norm1[0].p, h, x, ssq, rows, dm, st);
   }
   for (int l = 0; l < c.n_layers; ++l) {
     T* kc = (T*)s->kcache.p + s->layer_stride * l;
     T* vc = (T*)s->vcache.p + s->layer_stride * l;
     gemm<T>(s, x, m->wqkv[l].p, rows, qd + 2 * nkv * hd, dm, &sp, st);
     { ProfScope ps(pf, st, 3); pf.launches[3] += pf.on;
-      launch_rope_kv<T>(part, sp, t, meta, q, kc, vc, s->slot_stride, s->head_stride, rows, nq, nkv, hd, st); }
+      launch_rope_kv<T>(part, sp, ssq, dm, c.rms_eps, t, meta, q, kc, vc, s->slot_stride, s->head_stride, rows, nq, nkv, hd, st); }
     { ProfScope ps(pf, st, 1); pf.launches[1] += pf.on;
       launch_attention<T>(q, kc, vc, s->slot_stride, s->head_stride, am, x2, true, rows, max_seq_rows, nq, nkv, hd, st); }
     gemm<T>(s, x2, m->wo[l].p, rows, dm, qd, &sp, st);
     { ProfScope ps(pf, st, 3); pf.launches[3] += pf.on;
-      launch_reduce_residual_norm<T>(part, sp, h, (const float*)m->norm2[l].p, c.rms_eps, x, rows, dm, st); }
+      launch_reduce_residual_norm<T>(part, sp, h, (const float*)m->norm2[l].p, x, ssq, rows, dm, st); }
     gemm<T>(s, x, m->w_gate_up[l].p, rows, 2 * ffn, dm, &sp, st);
     { ProfScope ps(pf, st, 3); pf.launches[3] += pf.on;
-      launch_silu_mul<T>(part, sp, act, rows, ffn, st); }
+      launch_silu_mul<T>(part, sp, ssq, dm, c.rms_eps, act, rows, ffn, st); }
     gemm<T>(s, act, m->w_down[l].p, rows, dm, ffn, &sp, st);
     { ProfScope ps(pf, st, 3); pf.launches[3] += pf.on;
       const float* g = l + 1 < c.n_layers ? (const float*)m->norm1[l + 1].p : (const float*)m->final_norm.p;
-      launch_reduce_residual_norm<T>(part, sp, h, g, c.rms_eps, x, rows, dm, st); }
+      launch_reduce_residual_norm<T>(part, sp, h, g, x, ssq, rows, dm, st); }
   }
   {
     ProfScope ps(pf, st, 0);
     pf.launches[0] += pf.on;
-    if (sizeof(T) == 2) launch_gemm_bf16((const bf16_t*)x, (const bf16_t*)m->lm_head.p, nullptr, (bf16_t*)d->logits, rows, c.vocab, dm, 1, st);
-    else launch_gemm_f32((const float*)x, (const float*)m->lm_head.p, (float*)d->logits, rows, c.vocab, dm, st);
+    const RowScale rs{ssq, norm_chunks(dm), 1.f / (float)dm, c.rms_eps};
+    if (sizeof(T) == 2) launch_gemm_bf16((const bf16_t*)x, (const bf16_t*)m->lm_head.p, nullptr, (bf16_t*)d->logits, rows, c.vocab, dm, 1, rs, st);
+    else launch_gemm_f32((const float*)x, (const float*)m->lm_head.p, (float*)d->logits, rows, c.vocab, dm, rs, st);
   }
   {
     ProfScope ps(pf, st, 2);
@@ -487,7 +490,7 @@ extern "C" int dlm_gemm_nt(const void* x, const void* w, void* y, int M, int N, 
   REQUIRE(dtype == DLM_F32 || dtype == DLM_BF16, DLM_EINVAL, "dlm_gemm_nt: dtype %d", dtype);
   REQUIRE(M >= 1 && N >= 1 && K >= 1, DLM_ESHAPE, "dlm_gemm_nt: non-positive dimension");
   hipStream_t st = (hipStream_t)stream;
-  if (dtype == DLM_F32) { launch_gemm_f32((const float*)x, (const float*)w, (float*)y, M, N, K, st); return DLM_OK; }
+  if (dtype == DLM_F32) { launch_gemm_f32((const float*)x, (const float*)w, (float*)y, M, N, K, RowScale{nullptr, 0, 0.f, 0.f}, st); return DLM_OK; }
   REQUIRE(N % 32 == 0 && K % 32 == 0, DLM_ESHAPE, "dlm_gemm_nt: bf16 needs N and K to be multiples of 32");
   const size_t mp = (size_t)(M + 15) / 16 * 16;
   void* ws = nullptr;
@@ -496,7 +499,7 @@ extern "C" int dlm_gemm_nt(const void* x, const void* w, void* y, int M, int N, 
   bf16_t* wt = xt + mp * K;
   launch_pack_act((const bf16_t*)x, xt, M, K, st);
   launch_pack_weight((const bf16_t*)w, wt, N, K, st);
-  launch_gemm_bf16(xt, wt, nullptr, (bf16_t*)y, M, N, K, 1, st);
+  launch_gemm_bf16(xt, wt, nullptr, (bf16_t*)y, M, N, K, 1, RowScale{nullptr, 0, 0.f, 0.f}, st);
   hipError_t e = hipStreamSynchronize(st);
   (void)hipFree(ws);
   if (e != hipSuccess) return dlm_fail(DLM_EHIP, "dlm_gemm_nt: %s", hipGetErrorString(e));

@@ -24,7 +24,7 @@ constexpr int KC = 4;  // k-tiles (of 32) per staged chunk
 template <int MT, int R, bool OUT_BF16>
 __global__ __launch_bounds__(TPB) void gemm_bf16_kernel(const bf16x8* __restrict__ xt, const bf16x8* __restrict__ wt,
                                                         float* __restrict__ out_f32, bf16_t* __restrict__ out_bf16, int M, int N, int K,
-                                                        int kt_per_split) {
+                                                        int kt_per_split, RowScale rs) {
   static_assert(R % 2 == 0, "row-tiles come in interleaved pairs");
   constexpr int XP = MT * KC / 4;  // 16-byte pieces of X each thread stages per chunk
   __shared__ bf16x8 xs[2][MT * KC * 64];
@@ -106,6 +106,17 @@ __global__ __launch_bounds__(TPB) void gemm_bf16_kernel(const bf16x8* __restrict
   // epilogue: lane holds, per (r, j), columns n0..n0+3 of row m
   if (!wave_active) return;
   const int g = lane >> 4, ml = lane & 15;
+  float sc[MT];
+#pragma unroll
+  for (int j = 0; j < MT; ++j) {
+    sc[j] = 1.f;
+    const int m = (mt0 + j) * 16 + ml;
+    if (rs.ssq && m < M) {
+      float ss = 0.f;
+      for (int c = 0; c < rs.nch; ++c) ss += rs.ssq[(size_t)m * rs.nch + c];
+      sc[j] = rsqrtf(ss * rs.inv_d + rs.eps);
+    }
+  }
 #pragma unroll
   for (int r = 0; r < R; ++r) {
     const int nt = (pair0 + (r >> 1)) * 2 + (r & 1);
@@ -115,6 +126,7 @@ __global__ __launch_bounds__(TPB) void gemm_bf16_kernel(const bf16x8* __restrict
     for (int j = 0; j < MT; ++j) {
       const int m = (mt0 + j) * 16 + ml;
       if (m >= M) continue;
+      acc[r][j] *= sc[j];
       if (OUT_BF16) {
         bf16x4 o = {(bf16_t)acc[r][j][0], (bf16_t)acc[r][j][1], (bf16_t)acc[r][j][2], (bf16_t)acc[r][j][3]};
         *(bf16x4*)(out_bf16 + (size_t)m * N + n0) = o;
@@ -157,13 +169,13 @@ __global__ void pack_act_kernel(const bf16x8* __restrict__ x, bf16x8* __restrict
 }
 
 template <int MT, int R>
-void launch_mt(const bf16_t* xt, const bf16_t* wt, float* out_f32, bf16_t* out_bf16, int M, int N, int K, int splits, int mblocks, hipStream_t st) {
+void launch_mt(const bf16_t* xt, const bf16_t* wt, float* out_f32, bf16_t* out_bf16, int M, int N, int K, int splits, int mblocks, RowScale rs, hipStream_t st) {
   const int KT = K >> 5;
   const int kps = ((KT + splits - 1) / splits + KC - 1) / KC * KC;
   const int groups = ((N >> 5) + 4 * (R / 2) - 1) / (4 * (R / 2));
   dim3 grid(groups, splits, mblocks);
-  if (out_bf16) gemm_bf16_kernel<MT, R, true><<<grid, TPB, 0, st>>>((const bf16x8*)xt, (const bf16x8*)wt, nullptr, out_bf16, M, N, K, kps);
-  else gemm_bf16_kernel<MT, R, false><<<grid, TPB, 0, st>>>((const bf16x8*)xt, (const bf16x8*)wt, out_f32, nullptr, M, N, K, kps);
+  if (out_bf16) gemm_bf16_kernel<MT, R, true><<<grid, TPB, 0, st>>>((const bf16x8*)xt, (const bf16x8*)wt, nullptr, out_bf16, M, N, K, kps, rs);
+  else gemm_bf16_kernel<MT, R, false><<<grid, TPB, 0, st>>>((const bf16x8*)xt, (const bf16x8*)wt, out_f32, nullptr, M, N, K, kps, rs);
 }
 
 }  // namespace
@@ -190,9 +202,10 @@ int gemm_bf16_splits(int M, int N, int K) {
   return (KT + kps - 1) / kps;
 }
 
-void launch_gemm_bf16(const bf16_t* xt, const bf16_t* wt, float* out_f32, bf16_t* out_bf16, int M, int N, int K, int splits, hipStream_t st) {
+void launch_gemm_bf16(const bf16_t* xt, const bf16_t* wt, float* out_f32, bf16_t* out_bf16, int M, int N, int K, int splits, RowScale rs,
+                      hipStream_t st) {
   const int mtiles = (M + 15) >> 4;
-#define GO(MT) launch_mt<MT, 2>(xt, wt, out_f32, out_bf16, M, N, K, splits, (mtiles + MT - 1) / MT, st)
+#define GO(MT) launch_mt<MT, 2>(xt, wt, out_f32, out_bf16, M, N, K, splits, (mtiles + MT - 1) / MT, rs, st)
   if (mtiles <= 1) GO(1);
   else if (mtiles <= 2) GO(2);
   else if (mtiles <= 3) GO(3);

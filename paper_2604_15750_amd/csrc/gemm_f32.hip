@@ -6,7 +6,7 @@ namespace {
 constexpr int BM = 64, BN = 64, BK = 16;
 
 __global__ __launch_bounds__(256) void gemm_f32_kernel(const float* __restrict__ x, const float* __restrict__ w, float* __restrict__ y,
-                                                       int M, int N, int K) {
+                                                       int M, int N, int K, RowScale rs) {
   __shared__ float xs[BK][BM + 1], ws[BK][BN + 1];
   const int tid = threadIdx.x, tx = tid & 15, ty = tid >> 4;
   const int m0 = blockIdx.y * BM, n0 = blockIdx.x * BN;
@@ -30,15 +30,24 @@ __global__ __launch_bounds__(256) void gemm_f32_kernel(const float* __restrict__
     }
     __syncthreads();
   }
-  for (int i = 0; i < 4; ++i)
-    for (int j = 0; j < 4; ++j) {
-      const int m = m0 + ty * 4 + i, n = n0 + tx * 4 + j;
-      if (m < M && n < N) y[(size_t)m * N + n] = acc[i][j];
+  for (int i = 0; i < 4; ++i) {
+    const int m = m0 + ty * 4 + i;
+    if (m >= M) continue;
+    float sc = 1.f;
+    if (rs.ssq) {
+      float ss = 0.f;
+      for (int c = 0; c < rs.nch; ++c) ss += rs.ssq[(size_t)m * rs.nch + c];
+      sc = rsqrtf(ss * rs.inv_d + rs.eps);
     }
+    for (int j = 0; j < 4; ++j) {
+      const int n = n0 + tx * 4 + j;
+      if (n < N) y[(size_t)m * N + n] = acc[i][j] * sc;
+    }
+  }
 }
 }  // namespace
 
-void launch_gemm_f32(const float* x, const float* w, float* y, int M, int N, int K, hipStream_t st) {
+void launch_gemm_f32(const float* x, const float* w, float* y, int M, int N, int K, RowScale rs, hipStream_t st) {
   dim3 grid((N + BN - 1) / BN, (M + BM - 1) / BM);
-  gemm_f32_kernel<<<grid, 256, 0, st>>>(x, w, y, M, N, K);
+  gemm_f32_kernel<<<grid, 256, 0, st>>>(x, w, y, M, N, K, rs);
 }

@@ -156,11 +156,14 @@ __global__ __launch_bounds__(TPB) void vocab_stats_kernel(const T* __restrict__ 
   }
 }
 
-__global__ void vocab_stats_merge_kernel(const Part* __restrict__ parts, int rows, int nchunks, int vocab, StatsRows sr, StatsOut o) {
-  int row = blockIdx.x * blockDim.x + threadIdx.x;
-  if (row >= rows) return;
-  Part r = parts[(size_t)row * nchunks];
-  for (int c = 1; c < nchunks; ++c) r = part_merge(r, parts[(size_t)row * nchunks + c]);
+// one wavefront per row: lane c holds the partial state of chunk c; fixed butterfly order
+__global__ __launch_bounds__(64) void vocab_stats_merge_kernel(const Part* __restrict__ parts, int rows, int nchunks, int vocab, StatsRows sr,
+                                                               StatsOut o) {
+  const int row = blockIdx.x, lane = threadIdx.x;
+  Part r = lane < nchunks ? parts[(size_t)row * nchunks + lane] : part_init();
+#pragma unroll
+  for (int ofs = 32; ofs > 0; ofs >>= 1) r = part_merge(r, part_shfl_xor(r, ofs));
+  if (lane != 0) return;
   const int64_t prow = sr.prev_row ? sr.prev_row[row] : (sr.prev_base ? (int64_t)row * vocab : -1);
   const int64_t srow = sr.save_row ? sr.save_row[row] : -1;
   float pl = 0.f;
@@ -193,7 +196,7 @@ void launch_vocab_stats(const T* logits, int rows, int vocab, int mask_id, const
   dim3 grid(nch, rows);
   if (vec) vocab_stats_kernel<T, true><<<grid, TPB, 0, st>>>(logits, vocab, mask_id, chunk, sr, o, (Part*)workspace);
   else vocab_stats_kernel<T, false><<<grid, TPB, 0, st>>>(logits, vocab, mask_id, chunk, sr, o, (Part*)workspace);
-  if (nch > 1) vocab_stats_merge_kernel<<<(rows + 63) / 64, 64, 0, st>>>((const Part*)workspace, rows, nch, vocab, sr, o);
+  if (nch > 1) vocab_stats_merge_kernel<<<rows, 64, 0, st>>>((const Part*)workspace, rows, nch, vocab, sr, o);
 }
 
 template void launch_vocab_stats<float>(const float*, int, int, int, const StatsRows&, const StatsOut&, void*, hipStream_t);
