@@ -105,21 +105,63 @@ struct RowTables {  // device arrays of one pass, [rows]
 };
 
 // ---- launchers (callers have validated shapes) -------------------------------------------------
-// bf16 weight tiling: W [N, K] row-major -> tiles of 16 rows x 32 k, pairs of row-tiles interleaved
-// along k: tile (nt, kt) at ((nt/2 * K/32 + kt) * 2 + nt%2) KiB.
-void launch_pack_weight(const bf16_t* w, bf16_t* out, int N, int K, hipStream_t st);
+// bf16 weight tiling: W [N, K] row-major -> 1 KiB fragments of 16 rows x 32 k, `pr` (1 or 2) row-tiles interleaved along k:
+// fragment (nt, kt) sits at ((nt/pr * K/32 + kt) * pr + nt%pr) KiB.  The rows may be permuted first so that the columns an
+// epilogue has to combine share one 16-column output tile (packed row n holds source row weight_source_row(n, ...)):
+//   PERM_ROTARY (param = head_dim): tile b of a head holds dims 8b..8b+7 and their rotary partners 8b+hd/2..8b+hd/2+7
+//   PERM_GATED  (param = d_ffn):    tile g holds gate rows 8g..8g+7 and the up rows 8g..8g+7
+enum { PERM_NONE = 0, PERM_ROTARY = 1, PERM_GATED = 2 };
+__host__ __device__ inline int weight_source_row(int n, int perm, int param) {
+  if (perm == PERM_ROTARY) {
+    const int head = n / param, w = n % param, c = w & 15;
+    return head * param + 8 * (w >> 4) + (c & 7) + (c >= 8 ? param / 2 : 0);
+  }
+  if (perm == PERM_GATED) {
+    const int c = n & 15, o = 8 * (n >> 4) + (c & 7);
+    return c < 8 ? o : param + o;
+  }
+  return n;
+}
+inline int weight_pack_rows(int N) { return N <= 8192 ? 1 : 2; }  // narrow matrices: one workgroup per single 16-column tile
+void launch_pack_weight(const bf16_t* w, bf16_t* out, int N, int K, int pr, int perm, int perm_param, hipStream_t st);
 void launch_pack_act(const bf16_t* x, bf16_t* out, int M, int K, hipStream_t st);  // row-major -> fragment tiles (rows padded to 16 with zeros)
-// Y = X * W^T.  xt: fragment-tiled [Mpad, K]; wt: tiled weights.  Exactly one of out_f32 / out_bf16
-// is non-null: out_f32 [splits][M][N] partial sums (splits from gemm_bf16_splits), out_bf16 [M][N] (splits = 1).
-int gemm_bf16_splits(int M, int N, int K);
+int gemm_bf16_splits(int M, int N, int K);        // K-splits of the tiled kernel (1 when the skinny kernel runs)
+int gemm_bf16_ssq_chunks(int M, int N);            // chunks per row of the sums of squares an EPI_RESID launch of this shape writes
+int gemm_bf16_counters(int max_rows, int max_n);  // ticket counters a state needs (zero-initialised, self-resetting)
 // rs (optional): every output row m is multiplied by rsqrt(sum_c rs.ssq[m][c] * rs.inv_d + rs.eps).
 struct RowScale {
   const float* ssq;
   int nch;
   float inv_d, eps;
 };
-void launch_gemm_bf16(const bf16_t* xt, const bf16_t* wt, float* out_f32, bf16_t* out_bf16, int M, int N, int K, int splits, RowScale rs,
-                      hipStream_t st);
+enum { EPI_DIRECT = 0, EPI_QKV = 1, EPI_SWIGLU = 2, EPI_RESID = 3, EPI_SUM = 4 };
+// What the bf16 GEMM does with a finished output tile (see gemm_bf16.hip).
+struct GemmEpi {
+  int kind;
+  float* part;        // [splits][M][N] fp32 partial tiles of the tiled kernel (all kinds but EPI_DIRECT)
+  int* counters;      // one ticket per (column group, row block)
+  RowScale rs;        // 1/rms of the GEMM's input rows (QKV, SWIGLU, DIRECT, SUM; ssq may be null)
+  // EPI_QKV (weights packed with PERM_ROTARY)
+  const int32_t *row_pos, *row_seq;
+  const float *rope_cos, *rope_sin;
+  int32_t slot[DLM_MAX_SEQS];
+  bf16_t *q, *kcache, *vcache;
+  size_t slot_stride, head_stride;
+  int n_q, n_kv, hd;
+  // EPI_SWIGLU (weights packed with PERM_GATED)
+  bf16_t* act;
+  int ffn;
+  // EPI_RESID: h += y; x = h * gain (fragment tiles); ssq_out[m][gemm_bf16_ssq_chunks(M, N)] = each column tile's share of sum h^2
+  float* h;
+  const float* gain;
+  bf16_t* x;
+  float* ssq_out;
+  // EPI_DIRECT (bf16) / EPI_SUM (either)
+  bf16_t* out_bf16;
+  float* out_f32;
+};
+// Y = X * W^T.  xt: fragment-tiled [Mpad, K]; wt: tiled weights [N, K] packed with `pr` interleaved row-tiles.
+void launch_gemm_bf16(const bf16_t* xt, const bf16_t* wt, int pr, int M, int N, int K, const GemmEpi& e, hipStream_t st);
 void launch_gemm_f32(const float* x, const float* w, float* y, int M, int N, int K, RowScale rs, hipStream_t st);
 
 void launch_prepare(const SeqMeta& meta, const StatsMeta& sm, RowTables t, int rows, int vocab, int head_dim, float theta, hipStream_t st);

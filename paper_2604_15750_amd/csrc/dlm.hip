@@ -71,7 +71,7 @@ struct dlm_state {
   size_t head_stride;   // bf16: elements per (slot, kv head) region of the tiled cache
   size_t layer_stride;  // elements per layer
   DevBuf kcache, vcache, prev_logits, prev_lse;
-  DevBuf h, x, x2, act, q, part, stats_ws, ssq;
+  DevBuf h, x, x2, act, q, part, stats_ws, ssq, counters;
   DevBuf row_seq, row_pos, row_tok, rope_cos, rope_sin, prev_row, save_row;
   std::vector<int> kv_len, prev_cur, prev_base, prev_count;
   size_t part_elems;
@@ -110,10 +110,10 @@ int copy_gain(DevBuf& dst, const void* src, int n, int dtype, hipStream_t st) {
   return DLM_OK;
 }
 
-int copy_matrix(DevBuf& dst, const void* src, int N, int K, int dtype, hipStream_t st) {
+int copy_matrix(DevBuf& dst, const void* src, int N, int K, int dtype, hipStream_t st, int perm = PERM_NONE, int perm_param = 0) {
   int rc = dst.alloc((size_t)N * K * elem_size(dtype));
   if (rc) return rc;
-  if (dtype == DLM_BF16) launch_pack_weight((const bf16_t*)src, (bf16_t*)dst.p, N, K, st);
+  if (dtype == DLM_BF16) launch_pack_weight((const bf16_t*)src, (bf16_t*)dst.p, N, K, weight_pack_rows(N), perm, perm_param, st);
   else DLM_HIP(hipMemcpyAsync(dst.p, src, (size_t)N * K * 4, hipMemcpyDeviceToDevice, st));
   return DLM_OK;
 }
@@ -132,9 +132,10 @@ extern "C" int dlm_model_create(const dlm_config* cfg, const dlm_weights* w, voi
   REQUIRE(cfg->n_q_heads % cfg->n_kv_heads == 0, DLM_ESHAPE, "dlm_model_create: n_q_heads %% n_kv_heads != 0");
   REQUIRE(cfg->mask_id >= 0 && cfg->mask_id < cfg->vocab, DLM_EINVAL, "dlm_model_create: mask_id out of range");
   REQUIRE(cfg->d_model % 4 == 0 && cfg->d_ffn % 4 == 0, DLM_ESHAPE, "dlm_model_create: d_model and d_ffn must be multiples of 4");
-  if (cfg->dtype == DLM_BF16)
-    REQUIRE(mult32(cfg->d_model) && mult32(cfg->d_ffn) && mult32(cfg->vocab) && mult32(cfg->n_q_heads * cfg->head_dim),
-            DLM_ESHAPE, "dlm_model_create: bf16 needs d_model, d_ffn, vocab, n_q*head_dim to be multiples of 32");
+  if (cfg->dtype == DLM_BF16)  // whole 128-column output tiles (64 + 64 for the gated FFN); the LM head may end on a 32-column group
+    REQUIRE(cfg->d_model % 128 == 0 && cfg->d_ffn % 64 == 0 && mult32(cfg->vocab) && (cfg->n_q_heads * cfg->head_dim) % 128 == 0 &&
+                (cfg->n_kv_heads * cfg->head_dim) % 128 == 0,
+            DLM_ESHAPE, "dlm_model_create: bf16 needs d_model, n_q*head_dim, n_kv*head_dim %% 128 == 0, d_ffn %% 64 == 0, vocab %% 32 == 0");
   REQUIRE(w->embed && w->wqkv && w->wo && w->w_gate_up && w->w_down && w->norm1 && w->norm2 && w->final_norm && w->lm_head,
           DLM_EINVAL, "dlm_model_create: null weight pointer");
   for (int l = 0; l < cfg->n_layers; ++l)
@@ -156,8 +157,8 @@ extern "C" int dlm_model_create(const dlm_config* cfg, const dlm_weights* w, voi
   if (rc == DLM_OK) step(copy_gain(m->final_norm, w->final_norm, d, dt, st));
   if (rc == DLM_OK) step(copy_matrix(m->lm_head, w->lm_head, cfg->vocab, d, dt, st));
   for (int l = 0; l < L && rc == DLM_OK; ++l) {
-    step(copy_matrix(m->wqkv[l], w->wqkv[l], qkv, d, dt, st)) && step(copy_matrix(m->wo[l], w->wo[l], d, qd, dt, st)) &&
-        step(copy_matrix(m->w_gate_up[l], w->w_gate_up[l], 2 * cfg->d_ffn, d, dt, st)) &&
+    step(copy_matrix(m->wqkv[l], w->wqkv[l], qkv, d, dt, st, PERM_ROTARY, cfg->head_dim)) && step(copy_matrix(m->wo[l], w->wo[l], d, qd, dt, st)) &&
+        step(copy_matrix(m->w_gate_up[l], w->w_gate_up[l], 2 * cfg->d_ffn, d, dt, st, PERM_GATED, cfg->d_ffn)) &&
         step(copy_matrix(m->w_down[l], w->w_down[l], d, cfg->d_ffn, dt, st)) && step(copy_gain(m->norm1[l], w->norm1[l], d, dt, st)) &&
         step(copy_gain(m->norm2[l], w->norm2[l], d, dt, st));
   }
@@ -209,7 +210,12 @@ extern "C" int dlm_state_create(const dlm_model* m, int max_seqs, int max_seq_le
   A(s->q, (size_t)max_rows * qd * es);
   A(s->part, pe * 4);
   A(s->stats_ws, stats_workspace_bytes(max_rows));
-  A(s->ssq, (size_t)max_rows * norm_chunks(c.d_model) * 4);
+  const int ssq_chunks = c.dtype == DLM_BF16 ? c.d_model / 16 : norm_chunks(c.d_model);
+  A(s->ssq, (size_t)max_rows * ssq_chunks * 4);
+  int n_counters = 1;
+  if (c.dtype == DLM_BF16)
+    for (auto& sh : shapes) { int k = gemm_bf16_counters(max_rows, sh[0]); if (k > n_counters) n_counters = k; }
+  A(s->counters, (size_t)n_counters * 4);
   A(s->row_seq, (size_t)max_rows * 4); A(s->row_pos, (size_t)max_rows * 4); A(s->row_tok, (size_t)max_rows * 4);
   A(s->rope_cos, (size_t)max_rows * (c.head_dim / 2) * 4); A(s->rope_sin, (size_t)max_rows * (c.head_dim / 2) * 4);
   A(s->prev_row, (size_t)max_rows * 8); A(s->save_row, (size_t)max_rows * 8);
@@ -221,6 +227,7 @@ extern "C" int dlm_state_create(const dlm_model* m, int max_seqs, int max_seq_le
     if (e == hipSuccess) e = hipMemset(s->vcache.p, 0, s->layer_stride * c.n_layers * es);
     if (e == hipSuccess) e = hipMemset(s->x2.p, 0, (size_t)s->max_rows_pad * xw * es);
     if (e == hipSuccess) e = hipMemset(s->act.p, 0, (size_t)s->max_rows_pad * c.d_ffn * es);
+    if (e == hipSuccess) e = hipMemset(s->counters.p, 0, (size_t)n_counters * 4);
     if (e != hipSuccess) rc = dlm_fail(DLM_EHIP, "dlm_state_create: hipMemset: %s", hipGetErrorString(e));
   }
   if (rc != DLM_OK) { delete s; return rc; }
@@ -274,23 +281,10 @@ extern "C" int dlm_profile_read(dlm_state* s, int n, double* ms_out, int64_t* la
 // ---- dlm_step ------------------------------------------------------------------------------------
 namespace {
 
-template <typename T>
-void gemm(dlm_state* s, const void* x, const void* w, int M, int N, int K, int* splits_out, hipStream_t st) {
-  ProfScope ps(s->prof, st, 0);
-  s->prof.launches[0] += s->prof.on;
-  if (sizeof(T) == 2) {
-    int sp = gemm_bf16_splits(M, N, K);
-    launch_gemm_bf16((const bf16_t*)x, (const bf16_t*)w, (float*)s->part.p, nullptr, M, N, K, sp, RowScale{nullptr, 0, 0.f, 0.f}, st);
-    *splits_out = sp;
-  } else {
-    launch_gemm_f32((const float*)x, (const float*)w, (float*)s->part.p, M, N, K, RowScale{nullptr, 0, 0.f, 0.f}, st);
-    *splits_out = 1;
-  }
-}
-
-template <typename T>
-int run_step(dlm_state* s, const dlm_step_desc* d, const SeqMeta& meta, const StatsMeta& sm, const AttnMeta& am, int rows, int max_seq_rows,
-             hipStream_t st) {
+// fp32 model: plain GEMMs with the row-wise glue in kernels of their own
+int run_step_f32(dlm_state* s, const dlm_step_desc* d, const SeqMeta& meta, const StatsMeta& sm, const AttnMeta& am, int rows, int max_seq_rows,
+                 hipStream_t st) {
+  typedef float T;
   const dlm_model* m = s->m;
   const dlm_config& c = m->cfg;
   const int dm = c.d_model, hd = c.head_dim, nq = c.n_q_heads, nkv = c.n_kv_heads, qd = nq * hd, ffn = c.d_ffn;
@@ -301,7 +295,12 @@ int run_step(dlm_state* s, const dlm_step_desc* d, const SeqMeta& meta, const St
   float* part = (float*)s->part.p;
   float* ssq = (float*)s->ssq.p;
   Profile& pf = s->prof;
-  int sp = 1;
+  const RowScale none{nullptr, 0, 0.f, 0.f};
+  auto gemm = [&](const float* a, const void* w, int N, int K) {
+    ProfScope ps(pf, st, 0);
+    pf.launches[0] += pf.on;
+    launch_gemm_f32(a, (const float*)w, part, rows, N, K, none, st);
+  };
   {
     ProfScope ps(pf, st, 3);
     pf.launches[3] += 2 * pf.on;
@@ -311,28 +310,110 @@ int run_step(dlm_state* s, const dlm_step_desc* d, const SeqMeta& meta, const St
   for (int l = 0; l < c.n_layers; ++l) {
     T* kc = (T*)s->kcache.p + s->layer_stride * l;
     T* vc = (T*)s->vcache.p + s->layer_stride * l;
-    gemm<T>(s, x, m->wqkv[l].p, rows, qd + 2 * nkv * hd, dm, &sp, st);
+    gemm(x, m->wqkv[l].p, qd + 2 * nkv * hd, dm);
     { ProfScope ps(pf, st, 3); pf.launches[3] += pf.on;
-      launch_rope_kv<T>(part, sp, ssq, dm, c.rms_eps, t, meta, q, kc, vc, s->slot_stride, s->head_stride, rows, nq, nkv, hd, st); }
+      launch_rope_kv<T>(part, 1, ssq, dm, c.rms_eps, t, meta, q, kc, vc, s->slot_stride, s->head_stride, rows, nq, nkv, hd, st); }
     { ProfScope ps(pf, st, 1); pf.launches[1] += pf.on;
       launch_attention<T>(q, kc, vc, s->slot_stride, s->head_stride, am, x2, true, rows, max_seq_rows, nq, nkv, hd, st); }
-    gemm<T>(s, x2, m->wo[l].p, rows, dm, qd, &sp, st);
+    gemm(x2, m->wo[l].p, dm, qd);
     { ProfScope ps(pf, st, 3); pf.launches[3] += pf.on;
-      launch_reduce_residual_norm<T>(part, sp, h, (const float*)m->norm2[l].p, x, ssq, rows, dm, st); }
-    gemm<T>(s, x, m->w_gate_up[l].p, rows, 2 * ffn, dm, &sp, st);
+      launch_reduce_residual_norm<T>(part, 1, h, (const float*)m->norm2[l].p, x, ssq, rows, dm, st); }
+    gemm(x, m->w_gate_up[l].p, 2 * ffn, dm);
     { ProfScope ps(pf, st, 3); pf.launches[3] += pf.on;
-      launch_silu_mul<T>(part, sp, ssq, dm, c.rms_eps, act, rows, ffn, st); }
-    gemm<T>(s, act, m->w_down[l].p, rows, dm, ffn, &sp, st);
+      launch_silu_mul<T>(part, 1, ssq, dm, c.rms_eps, act, rows, ffn, st); }
+    gemm(act, m->w_down[l].p, dm, ffn);
     { ProfScope ps(pf, st, 3); pf.launches[3] += pf.on;
       const float* g = l + 1 < c.n_layers ? (const float*)m->norm1[l + 1].p : (const float*)m->final_norm.p;
-      launch_reduce_residual_norm<T>(part, sp, h, g, x, ssq, rows, dm, st); }
+      launch_reduce_residual_norm<T>(part, 1, h, g, x, ssq, rows, dm, st); }
   }
   {
     ProfScope ps(pf, st, 0);
     pf.launches[0] += pf.on;
     const RowScale rs{ssq, norm_chunks(dm), 1.f / (float)dm, c.rms_eps};
-    if (sizeof(T) == 2) launch_gemm_bf16((const bf16_t*)x, (const bf16_t*)m->lm_head.p, nullptr, (bf16_t*)d->logits, rows, c.vocab, dm, 1, rs, st);
-    else launch_gemm_f32((const float*)x, (const float*)m->lm_head.p, (float*)d->logits, rows, c.vocab, dm, rs, st);
+    launch_gemm_f32((const float*)x, (const float*)m->lm_head.p, (float*)d->logits, rows, c.vocab, dm, rs, st);
+  }
+  {
+    ProfScope ps(pf, st, 2);
+    pf.launches[2] += pf.on;
+    StatsRows sr{t.prev_row, t.save_row, s->prev_logits.p, s->prev_logits.p, (const float*)s->prev_lse.p, (float*)s->prev_lse.p};
+    StatsOut so{d->max_logit, d->lse, d->entropy, d->kl, d->conf, d->argmax};
+    launch_vocab_stats<T>((const T*)d->logits, rows, c.vocab, c.mask_id, sr, so, s->stats_ws.p, st);
+  }
+  return DLM_OK;
+}
+
+// bf16 models: five launches per layer; every row-wise step between two GEMMs runs in the producing GEMM's epilogue
+int run_step_bf16(dlm_state* s, const dlm_step_desc* d, const SeqMeta& meta, const StatsMeta& sm, const AttnMeta& am, int rows,
+                  int max_seq_rows, hipStream_t st) {
+  typedef bf16_t T;
+  const dlm_model* m = s->m;
+  const dlm_config& c = m->cfg;
+  const int dm = c.d_model, hd = c.head_dim, nq = c.n_q_heads, nkv = c.n_kv_heads, qd = nq * hd, ffn = c.d_ffn;
+  RowTables t{(int32_t*)s->row_seq.p, (int32_t*)s->row_pos.p, (int32_t*)s->row_tok.p, (float*)s->rope_cos.p, (float*)s->rope_sin.p,
+              (int64_t*)s->prev_row.p, (int64_t*)s->save_row.p};
+  float* h = (float*)s->h.p;
+  T *x = (T*)s->x.p, *x2 = (T*)s->x2.p, *act = (T*)s->act.p, *q = (T*)s->q.p;
+  float* ssq = (float*)s->ssq.p;
+  Profile& pf = s->prof;
+  GemmEpi base;
+  memset(&base, 0, sizeof base);
+  base.part = (float*)s->part.p;
+  base.counters = (int*)s->counters.p;
+  auto gemm = [&](const T* a, const void* w, int N, int K, const GemmEpi& e) {
+    ProfScope ps(pf, st, 0);
+    pf.launches[0] += pf.on;
+    launch_gemm_bf16(a, (const T*)w, weight_pack_rows(N), rows, N, K, e, st);
+  };
+  {
+    ProfScope ps(pf, st, 3);
+    pf.launches[3] += 2 * pf.on;
+    launch_prepare(meta, sm, t, rows, c.vocab, hd, c.rope_theta, st);
+    launch_embed_norm<T>((const T*)m->embed.p, d->tokens, t, (const float*)m->norm1[0].p, h, x, ssq, rows, dm, st);
+  }
+  int nch = norm_chunks(dm);  // chunks of the row sums of squares the next consumer reads: the embedding's, then the epilogue's
+  for (int l = 0; l < c.n_layers; ++l) {
+    T* kc = (T*)s->kcache.p + s->layer_stride * l;
+    T* vc = (T*)s->vcache.p + s->layer_stride * l;
+    {
+      GemmEpi e = base;
+      e.kind = EPI_QKV;
+      e.rs = RowScale{ssq, nch, 1.f / (float)dm, c.rms_eps};
+      e.row_pos = t.row_pos; e.row_seq = t.row_seq; e.rope_cos = t.rope_cos; e.rope_sin = t.rope_sin;
+      for (int b = 0; b < meta.n_seqs; ++b) e.slot[b] = meta.slot[b];
+      e.q = q; e.kcache = kc; e.vcache = vc; e.slot_stride = s->slot_stride; e.head_stride = s->head_stride;
+      e.n_q = nq; e.n_kv = nkv; e.hd = hd;
+      gemm(x, m->wqkv[l].p, qd + 2 * nkv * hd, dm, e);
+    }
+    { ProfScope ps(pf, st, 1); pf.launches[1] += pf.on;
+      launch_attention<T>(q, kc, vc, s->slot_stride, s->head_stride, am, x2, true, rows, max_seq_rows, nq, nkv, hd, st); }
+    {
+      GemmEpi e = base;
+      e.kind = EPI_RESID;
+      e.h = h; e.gain = (const float*)m->norm2[l].p; e.x = x; e.ssq_out = ssq;
+      gemm(x2, m->wo[l].p, dm, qd, e);
+      nch = gemm_bf16_ssq_chunks(rows, dm);
+    }
+    {
+      GemmEpi e = base;
+      e.kind = EPI_SWIGLU;
+      e.rs = RowScale{ssq, nch, 1.f / (float)dm, c.rms_eps};
+      e.act = act; e.ffn = ffn;
+      gemm(x, m->w_gate_up[l].p, 2 * ffn, dm, e);
+    }
+    {
+      GemmEpi e = base;
+      e.kind = EPI_RESID;
+      e.h = h; e.gain = l + 1 < c.n_layers ? (const float*)m->norm1[l + 1].p : (const float*)m->final_norm.p;
+      e.x = x; e.ssq_out = ssq;
+      gemm(act, m->w_down[l].p, dm, ffn, e);
+    }
+  }
+  {
+    GemmEpi e = base;
+    e.kind = EPI_DIRECT;
+    e.rs = RowScale{ssq, nch, 1.f / (float)dm, c.rms_eps};
+    e.out_bf16 = (T*)d->logits;
+    gemm(x, m->lm_head.p, c.vocab, dm, e);
   }
   {
     ProfScope ps(pf, st, 2);
@@ -400,8 +481,8 @@ extern "C" int dlm_step(dlm_state* s, const dlm_step_desc* d, void* stream) {
   }
   const int rows = d->row_offsets[n];
   hipStream_t st = (hipStream_t)stream;
-  int rc = c.dtype == DLM_BF16 ? run_step<bf16_t>(s, d, meta, sm, am, rows, max_seq_rows, st)
-                               : run_step<float>(s, d, meta, sm, am, rows, max_seq_rows, st);
+  int rc = c.dtype == DLM_BF16 ? run_step_bf16(s, d, meta, sm, am, rows, max_seq_rows, st)
+                               : run_step_f32(s, d, meta, sm, am, rows, max_seq_rows, st);
   if (rc != DLM_OK) return rc;
   for (int b = 0; b < n; ++b) {  // host bookkeeping: commit the prefix, flip the retained-logit buffers
     const int slot = meta.slot[b];
@@ -493,14 +574,28 @@ extern "C" int dlm_gemm_nt(const void* x, const void* w, void* y, int M, int N, 
   if (dtype == DLM_F32) { launch_gemm_f32((const float*)x, (const float*)w, (float*)y, M, N, K, RowScale{nullptr, 0, 0.f, 0.f}, st); return DLM_OK; }
   REQUIRE(N % 32 == 0 && K % 32 == 0, DLM_ESHAPE, "dlm_gemm_nt: bf16 needs N and K to be multiples of 32");
   const size_t mp = (size_t)(M + 15) / 16 * 16;
+  const int n_counters = gemm_bf16_counters(M, N);
+  const size_t tiled_bytes = ((mp * K + (size_t)N * K) * 2 + 15) / 16 * 16;
+  const size_t part_bytes = (size_t)gemm_bf16_splits(M, N, K) * M * N * 4;
   void* ws = nullptr;
-  if (hipMalloc(&ws, (mp * K + (size_t)N * K) * 2) != hipSuccess) { (void)hipGetLastError(); return dlm_fail(DLM_ENOMEM, "dlm_gemm_nt: workspace allocation failed"); }
+  if (hipMalloc(&ws, tiled_bytes + part_bytes + (size_t)n_counters * 4) != hipSuccess) { (void)hipGetLastError(); return dlm_fail(DLM_ENOMEM, "dlm_gemm_nt: workspace allocation failed"); }
   bf16_t* xt = (bf16_t*)ws;
   bf16_t* wt = xt + mp * K;
+  float* part = (float*)((char*)ws + tiled_bytes);
   launch_pack_act((const bf16_t*)x, xt, M, K, st);
-  launch_pack_weight((const bf16_t*)w, wt, N, K, st);
-  launch_gemm_bf16(xt, wt, nullptr, (bf16_t*)y, M, N, K, 1, RowScale{nullptr, 0, 0.f, 0.f}, st);
-  hipError_t e = hipStreamSynchronize(st);
+  launch_pack_weight((const bf16_t*)w, wt, N, K, weight_pack_rows(N), PERM_NONE, 0, st);
+  const int splits = gemm_bf16_splits(M, N, K);
+  GemmEpi ge;
+  memset(&ge, 0, sizeof ge);
+  ge.out_bf16 = (bf16_t*)y;
+  hipError_t e = hipSuccess;
+  // partial tiles and ticket counters (used when the tiled kernel splits K) follow the tiled operands in the scratch
+  ge.kind = EPI_SUM;
+  ge.part = part;
+  ge.counters = (int*)(part + (size_t)splits * M * N);
+  e = hipMemsetAsync(ge.counters, 0, (size_t)n_counters * 4, st);
+  launch_gemm_bf16(xt, wt, weight_pack_rows(N), M, N, K, ge, st);
+  if (e == hipSuccess) e = hipStreamSynchronize(st);
   (void)hipFree(ws);
   if (e != hipSuccess) return dlm_fail(DLM_EHIP, "dlm_gemm_nt: %s", hipGetErrorString(e));
   return DLM_OK;
