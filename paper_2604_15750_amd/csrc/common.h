@@ -122,12 +122,15 @@ __host__ __device__ inline int weight_source_row(int n, int perm, int param) {
   }
   return n;
 }
-inline int weight_pack_rows(int N) { return N <= 8192 ? 1 : 2; }  // narrow matrices: one workgroup per single 16-column tile
-void launch_pack_weight(const bf16_t* w, bf16_t* out, int N, int K, int pr, int perm, int perm_param, hipStream_t st);
+inline int weight_pack_rows(int N) { return N <= 8192 ? 1 : 2; }  // narrow matrices: one run per 16-column tile
+void launch_pack_weight(const bf16_t* w, bf16_t* out, int N, int K, int perm, int perm_param, hipStream_t st);
 void launch_pack_act(const bf16_t* x, bf16_t* out, int M, int K, hipStream_t st);  // row-major -> fragment tiles (rows padded to 16 with zeros)
-int gemm_bf16_splits(int M, int N, int K);        // K-splits of the tiled kernel (1 when the skinny kernel runs)
+int gemm_bf16_splits(int M, int N, int K);         // partial tiles [splits][M][N] the launch of this shape needs in GemmEpi::part (1: none)
 int gemm_bf16_ssq_chunks(int M, int N);            // chunks per row of the sums of squares an EPI_RESID launch of this shape writes
-int gemm_bf16_counters(int max_rows, int max_n);  // ticket counters a state needs (zero-initialised, self-resetting)
+int gemm_tiled_counters(int max_rows, int max_n);  // ticket counters a state needs (zero-initialised, self-resetting)
+int gemm_tiled_splits(int M, int N, int K);
+int gemm_tiled_ssq_chunks(int M, int N);
+void gemm_tiled_set_target(int wgs);               // tuning: workgroups the K split aims at
 // rs (optional): every output row m is multiplied by rsqrt(sum_c rs.ssq[m][c] * rs.inv_d + rs.eps).
 struct RowScale {
   const float* ssq;
@@ -138,8 +141,8 @@ enum { EPI_DIRECT = 0, EPI_QKV = 1, EPI_SWIGLU = 2, EPI_RESID = 3, EPI_SUM = 4 }
 // What the bf16 GEMM does with a finished output tile (see gemm_bf16.hip).
 struct GemmEpi {
   int kind;
-  float* part;        // [splits][M][N] fp32 partial tiles of the tiled kernel (all kinds but EPI_DIRECT)
-  int* counters;      // one ticket per (column group, row block)
+  float* part;        // [gemm_bf16_splits][M][N] fp32 partial tiles of the tiled kernel when it splits K
+  int* counters;      // gemm_tiled_counters tickets, one per (column group, row block)
   RowScale rs;        // 1/rms of the GEMM's input rows (QKV, SWIGLU, DIRECT, SUM; ssq may be null)
   // EPI_QKV (weights packed with PERM_ROTARY)
   const int32_t *row_pos, *row_seq;
@@ -160,8 +163,11 @@ struct GemmEpi {
   bf16_t* out_bf16;
   float* out_f32;
 };
-// Y = X * W^T.  xt: fragment-tiled [Mpad, K]; wt: tiled weights [N, K] packed with `pr` interleaved row-tiles.
-void launch_gemm_bf16(const bf16_t* xt, const bf16_t* wt, int pr, int M, int N, int K, const GemmEpi& e, hipStream_t st);
+// Y = X * W^T.  xt: fragment-tiled [Mpad, K]; wt: weights [N, K] as packed by launch_pack_weight.
+void launch_gemm_bf16(const bf16_t* xt, const bf16_t* wt, int M, int N, int K, const GemmEpi& e, hipStream_t st);
+#define GEMM_SKINNY_MAX_ROWS 64
+void launch_gemm_skinny(const bf16_t* xt, const bf16_t* wt, int pr, int M, int N, int K, const GemmEpi& e, hipStream_t st);  // M <= GEMM_SKINNY_MAX_ROWS
+void launch_gemm_tiled(const bf16_t* xt, const bf16_t* wt, int M, int N, int K, const GemmEpi& e, hipStream_t st);
 void launch_gemm_f32(const float* x, const float* w, float* y, int M, int N, int K, RowScale rs, hipStream_t st);
 
 void launch_prepare(const SeqMeta& meta, const StatsMeta& sm, RowTables t, int rows, int vocab, int head_dim, float theta, hipStream_t st);

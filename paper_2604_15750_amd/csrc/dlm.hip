@@ -113,7 +113,7 @@ int copy_gain(DevBuf& dst, const void* src, int n, int dtype, hipStream_t st) {
 int copy_matrix(DevBuf& dst, const void* src, int N, int K, int dtype, hipStream_t st, int perm = PERM_NONE, int perm_param = 0) {
   int rc = dst.alloc((size_t)N * K * elem_size(dtype));
   if (rc) return rc;
-  if (dtype == DLM_BF16) launch_pack_weight((const bf16_t*)src, (bf16_t*)dst.p, N, K, weight_pack_rows(N), perm, perm_param, st);
+  if (dtype == DLM_BF16) launch_pack_weight((const bf16_t*)src, (bf16_t*)dst.p, N, K, perm, perm_param, st);
   else DLM_HIP(hipMemcpyAsync(dst.p, src, (size_t)N * K * 4, hipMemcpyDeviceToDevice, st));
   return DLM_OK;
 }
@@ -133,9 +133,9 @@ extern "C" int dlm_model_create(const dlm_config* cfg, const dlm_weights* w, voi
   REQUIRE(cfg->mask_id >= 0 && cfg->mask_id < cfg->vocab, DLM_EINVAL, "dlm_model_create: mask_id out of range");
   REQUIRE(cfg->d_model % 4 == 0 && cfg->d_ffn % 4 == 0, DLM_ESHAPE, "dlm_model_create: d_model and d_ffn must be multiples of 4");
   if (cfg->dtype == DLM_BF16)  // whole 128-column output tiles (64 + 64 for the gated FFN); the LM head may end on a 32-column group
-    REQUIRE(cfg->d_model % 128 == 0 && cfg->d_ffn % 64 == 0 && mult32(cfg->vocab) && (cfg->n_q_heads * cfg->head_dim) % 128 == 0 &&
+    REQUIRE(cfg->d_model % 256 == 0 && cfg->d_ffn % 64 == 0 && mult32(cfg->vocab) && (cfg->n_q_heads * cfg->head_dim) % 128 == 0 &&
                 (cfg->n_kv_heads * cfg->head_dim) % 128 == 0,
-            DLM_ESHAPE, "dlm_model_create: bf16 needs d_model, n_q*head_dim, n_kv*head_dim %% 128 == 0, d_ffn %% 64 == 0, vocab %% 32 == 0");
+            DLM_ESHAPE, "dlm_model_create: bf16 needs d_model %% 256 == 0, n_q*head_dim and n_kv*head_dim %% 128 == 0, d_ffn %% 64 == 0, vocab %% 32 == 0");
   REQUIRE(w->embed && w->wqkv && w->wo && w->w_gate_up && w->w_down && w->norm1 && w->norm2 && w->final_norm && w->lm_head,
           DLM_EINVAL, "dlm_model_create: null weight pointer");
   for (int l = 0; l < cfg->n_layers; ++l)
@@ -190,7 +190,10 @@ extern "C" int dlm_state_create(const dlm_model* m, int max_seqs, int max_seq_le
   for (auto& sh : shapes) {
     int maxsp = 1;
     if (c.dtype == DLM_BF16)
-      for (int rows = 1; rows <= max_rows; rows = rows < 16 ? 16 : rows + 16) { int sp = gemm_bf16_splits(rows, sh[0], sh[1]); if (sp > maxsp) maxsp = sp; }
+      for (int mt = 1; mt <= (max_rows + 15) / 16; ++mt) {  // the split count depends on the rows only through their 16-row tiles
+        const int sp = gemm_bf16_splits(mt * 16 < max_rows ? mt * 16 : max_rows, sh[0], sh[1]);
+        if (sp > maxsp) maxsp = sp;
+      }
     size_t e = (size_t)maxsp * max_rows * sh[0];
     if (e > pe) pe = e;
   }
@@ -214,7 +217,7 @@ extern "C" int dlm_state_create(const dlm_model* m, int max_seqs, int max_seq_le
   A(s->ssq, (size_t)max_rows * ssq_chunks * 4);
   int n_counters = 1;
   if (c.dtype == DLM_BF16)
-    for (auto& sh : shapes) { int k = gemm_bf16_counters(max_rows, sh[0]); if (k > n_counters) n_counters = k; }
+    for (auto& sh : shapes) { int k = gemm_tiled_counters(max_rows, sh[0]); if (k > n_counters) n_counters = k; }
   A(s->counters, (size_t)n_counters * 4);
   A(s->row_seq, (size_t)max_rows * 4); A(s->row_pos, (size_t)max_rows * 4); A(s->row_tok, (size_t)max_rows * 4);
   A(s->rope_cos, (size_t)max_rows * (c.head_dim / 2) * 4); A(s->rope_sin, (size_t)max_rows * (c.head_dim / 2) * 4);
@@ -359,10 +362,17 @@ int run_step_bf16(dlm_state* s, const dlm_step_desc* d, const SeqMeta& meta, con
   memset(&base, 0, sizeof base);
   base.part = (float*)s->part.p;
   base.counters = (int*)s->counters.p;
+  // every layer GEMM of this pass must fit the partial-tile workspace the state was created with
+  {
+    const int shapes[4][2] = {{qd + 2 * nkv * hd, dm}, {dm, qd}, {2 * ffn, dm}, {dm, ffn}};
+    for (auto& sh : shapes)
+      if ((size_t)gemm_bf16_splits(rows, sh[0], sh[1]) * rows * sh[0] > s->part_elems)
+        return dlm_fail(DLM_ECAPACITY, "dlm_step: split-K workspace too small for %d rows x %d columns", rows, sh[0]);
+  }
   auto gemm = [&](const T* a, const void* w, int N, int K, const GemmEpi& e) {
     ProfScope ps(pf, st, 0);
     pf.launches[0] += pf.on;
-    launch_gemm_bf16(a, (const T*)w, weight_pack_rows(N), rows, N, K, e, st);
+    launch_gemm_bf16(a, (const T*)w, rows, N, K, e, st);
   };
   {
     ProfScope ps(pf, st, 3);
@@ -574,7 +584,7 @@ extern "C" int dlm_gemm_nt(const void* x, const void* w, void* y, int M, int N, 
   if (dtype == DLM_F32) { launch_gemm_f32((const float*)x, (const float*)w, (float*)y, M, N, K, RowScale{nullptr, 0, 0.f, 0.f}, st); return DLM_OK; }
   REQUIRE(N % 32 == 0 && K % 32 == 0, DLM_ESHAPE, "dlm_gemm_nt: bf16 needs N and K to be multiples of 32");
   const size_t mp = (size_t)(M + 15) / 16 * 16;
-  const int n_counters = gemm_bf16_counters(M, N);
+  const int n_counters = gemm_tiled_counters(M, N);
   const size_t tiled_bytes = ((mp * K + (size_t)N * K) * 2 + 15) / 16 * 16;
   const size_t part_bytes = (size_t)gemm_bf16_splits(M, N, K) * M * N * 4;
   void* ws = nullptr;
@@ -583,7 +593,7 @@ extern "C" int dlm_gemm_nt(const void* x, const void* w, void* y, int M, int N, 
   bf16_t* wt = xt + mp * K;
   float* part = (float*)((char*)ws + tiled_bytes);
   launch_pack_act((const bf16_t*)x, xt, M, K, st);
-  launch_pack_weight((const bf16_t*)w, wt, N, K, weight_pack_rows(N), PERM_NONE, 0, st);
+  launch_pack_weight((const bf16_t*)w, wt, N, K, PERM_NONE, 0, st);
   const int splits = gemm_bf16_splits(M, N, K);
   GemmEpi ge;
   memset(&ge, 0, sizeof ge);
@@ -594,7 +604,7 @@ extern "C" int dlm_gemm_nt(const void* x, const void* w, void* y, int M, int N, 
   ge.part = part;
   ge.counters = (int*)(part + (size_t)splits * M * N);
   e = hipMemsetAsync(ge.counters, 0, (size_t)n_counters * 4, st);
-  launch_gemm_bf16(xt, wt, weight_pack_rows(N), M, N, K, ge, st);
+  launch_gemm_bf16(xt, wt, M, N, K, ge, st);
   if (e == hipSuccess) e = hipStreamSynchronize(st);
   (void)hipFree(ws);
   if (e != hipSuccess) return dlm_fail(DLM_EHIP, "dlm_gemm_nt: %s", hipGetErrorString(e));

@@ -1,0 +1,105 @@
+// Epilogues of the bf16 GEMM kernels, on finished values in the accumulator layout of
+// v_mfma_f32_16x16x32_bf16 (transposed product): in a 16 x 16 output tile, lane ml + 16 g holds
+// columns 4g .. 4g+3 of row ml.
+#pragma once
+#include "common.h"
+
+__device__ inline bf16x4 to_bf16x4(f32x4 v) { return bf16x4{(bf16_t)v[0], (bf16_t)v[1], (bf16_t)v[2], (bf16_t)v[3]}; }
+
+// 1/rms of rows [m_lo, m_lo + rows) from the producer's partial sums of squares into s_rinv, by the whole workgroup of NT
+// threads: sixteen lanes per row, each adding every sixteenth chunk, then a fixed butterfly (deterministic).
+template <int NT>
+__device__ inline void block_rinv(const RowScale& rs, int m_lo, int rows, float* s_rinv) {
+  const int sub = threadIdx.x & 15;
+  for (int row = threadIdx.x >> 4; row < rows; row += NT / 16) {
+    float ss = 0.f;
+    if (rs.ssq)
+      for (int c = sub; c < rs.nch; c += 16) ss += rs.ssq[(size_t)(m_lo + row) * rs.nch + c];
+#pragma unroll
+    for (int o = 8; o > 0; o >>= 1) ss += __shfl_xor(ss, o, 64);
+    if (sub == 0) s_rinv[row] = rs.ssq ? rsqrtf(ss * rs.inv_d + rs.eps) : 1.f;
+  }
+}
+
+// Rotary pair group: a = packed columns nc+4gp .. +3 of a 16-column tile starting at packed column nc,
+// b = the same + 8; they are dims i .. i+3 and i+half .. i+half+3 of one head (weights packed with PERM_ROTARY).
+__device__ inline void finish_qkv(const GemmEpi& e, int m, int nc, int gp, f32x4 a, f32x4 b) {
+  const int hd = e.hd, half = hd >> 1;
+  const int head = nc / hd, i = 8 * ((nc % hd) >> 4) + 4 * gp;
+  if (head < e.n_q + e.n_kv) {
+    const f32x4 c = *(const f32x4*)(e.rope_cos + (size_t)m * half + i), sn = *(const f32x4*)(e.rope_sin + (size_t)m * half + i);
+    const f32x4 ra = a * c - b * sn, rb = b * c + a * sn;
+    a = ra;
+    b = rb;
+  }
+  const bf16x4 ab = to_bf16x4(a), bb = to_bf16x4(b);
+  if (head < e.n_q) {
+    bf16_t* dst = e.q + (size_t)m * e.n_q * hd + (size_t)head * hd;
+    *(bf16x4*)(dst + i) = ab;
+    *(bf16x4*)(dst + i + half) = bb;
+    return;
+  }
+  const bool is_k = head < e.n_q + e.n_kv;
+  const int kvh = is_k ? head - e.n_q : head - e.n_q - e.n_kv;
+  const int pos = e.row_pos[m];
+  bf16_t* dst = (is_k ? e.kcache : e.vcache) + (size_t)e.slot[e.row_seq[m]] * e.slot_stride + (size_t)kvh * e.head_stride;
+  if (is_k) {  // four consecutive dims share a lane slot of the K tiling
+    *(bf16x4*)(dst + kv_k_index(pos, i, hd)) = ab;
+    *(bf16x4*)(dst + kv_k_index(pos, i + half, hd)) = bb;
+  } else {
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+      dst[kv_v_index(pos, i + j, hd)] = ab[j];
+      dst[kv_v_index(pos, i + half + j, hd)] = bb[j];
+    }
+  }
+}
+
+// gate = packed columns nc+4gp .. +3, up = the same + 8: output columns 8 (nc/16) + 4gp .. +3 (weights packed with PERM_GATED)
+__device__ inline void finish_swiglu(const GemmEpi& e, int m, int nc, int gp, f32x4 g, f32x4 u) {
+  bf16x4 o;
+#pragma unroll
+  for (int t = 0; t < 4; ++t) o[t] = (bf16_t)(g[t] / (1.f + __expf(-g[t])) * u[t]);
+  *(bf16x4*)(e.act + tile_index(m, 8 * (nc >> 4) + 4 * gp, e.ffn)) = o;
+}
+
+// residual add and next norm's x for columns n .. n+3 of row m; returns the four columns' share of sum h^2
+__device__ inline float finish_resid(const GemmEpi& e, int m, int n, int N, f32x4 y) {
+  const size_t o = (size_t)m * N + n;
+  const f32x4 v = *(const f32x4*)(e.h + o) + y;
+  *(f32x4*)(e.h + o) = v;
+  const f32x4 g = *(const f32x4*)(e.gain + n);
+  *(bf16x4*)(e.x + tile_index(m, n, N)) = to_bf16x4(v * g);
+  return v[0] * v[0] + v[1] * v[1] + v[2] * v[2] + v[3] * v[3];
+}
+
+__device__ inline void finish_sum(const GemmEpi& e, int m, int n, int N, f32x4 v) {
+  const size_t o = (size_t)m * N + n;
+  if (e.out_bf16) *(bf16x4*)(e.out_bf16 + o) = to_bf16x4(v);
+  else *(f32x4*)(e.out_f32 + o) = v;
+}
+
+// One 16 x 16 tile starting at packed column nc: v = this lane's four finished columns of row m, rinv = 1/rms of the input row.
+// Called by all 64 lanes of a wavefront together (it exchanges values between lanes).  EPI_RESID returns the tile's share of
+// sum h^2 of row m (in every lane of the row), the others 0.
+template <int EPI>
+__device__ inline float finish_frag(const GemmEpi& e, int M, int N, int m, int nc, int g, f32x4 v, float rinv) {
+  if (EPI == EPI_QKV || EPI == EPI_SWIGLU) {
+    f32x4 b;  // the partner group, columns + 8, sits 32 lanes up
+#pragma unroll
+    for (int i = 0; i < 4; ++i) b[i] = __shfl_xor(v[i], 32, 64);
+    if (g < 2 && m < M) {
+      if (EPI == EPI_QKV) finish_qkv(e, m, nc, g, v * rinv, b * rinv);
+      else finish_swiglu(e, m, nc, g, v * rinv, b * rinv);
+    }
+    return 0.f;
+  }
+  if (EPI == EPI_RESID) {
+    float ss = m < M ? finish_resid(e, m, nc + 4 * g, N, v) : 0.f;
+    ss += __shfl_xor(ss, 16, 64);
+    ss += __shfl_xor(ss, 32, 64);
+    return ss;
+  }
+  if (m < M) finish_sum(e, m, nc + 4 * g, N, v * rinv);
+  return 0.f;
+}

@@ -1,0 +1,107 @@
+// Skinny bf16 GEMM (M <= 64 rows): Y[M,N] = X[M,K] * W[N,K]^T, fp32 accumulation, epilogue fused.
+//
+// One workgroup per 16- or 32-column output tile over the whole of K.  Its wavefronts split K among
+// themselves; each keeps 8 KiB of W fragments (and the matching X fragments) in flight, HBM ->
+// registers, and multiplies them on the matrix cores; the accumulators are added through LDS in
+// wavefront order (deterministic).  No workgroup waits for another: no workspace, no counter, no
+// serial tail.  With 256 .. 768 workgroups all resident at once, HBM stays busy from the first load
+// to the last.
+#include "gemm_epilogue.h"
+
+namespace {
+
+// grid.x = N / (16 R) workgroups of NWV wavefronts; wavefront w multiplies k-tiles [w*per, (w+1)*per) of the
+// workgroup's R column tiles against all MT row tiles, D k-tiles per batch, two batches of registers.
+template <int MT, int R, int NWV, int D, int EPI>
+__global__ __launch_bounds__(NWV * 64) void gemm_skinny_kernel(const bf16x8* __restrict__ xt, const bf16x8* __restrict__ wt, int M, int N,
+                                                               int K, GemmEpi e) {
+  __shared__ f32x4 red[NWV][R * MT][64];
+  __shared__ float s_rinv[MT * 16];
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int KT = K >> 5, MTILES = (M + 15) >> 4;
+  const int per = (KT + NWV - 1) / NWV;
+  const int t_begin = wave * per, t_end = min(KT, t_begin + per);
+  const bf16x8 zero8 = {0, 0, 0, 0, 0, 0, 0, 0};
+  const bf16x8* wbase = wt + (size_t)blockIdx.x * KT * R * 64 + lane;  // the workgroup's R tiles are one interleaved run
+
+  f32x4 acc[R][MT];
+#pragma unroll
+  for (int r = 0; r < R; ++r)
+#pragma unroll
+    for (int j = 0; j < MT; ++j) acc[r][j] = f32x4{0.f, 0.f, 0.f, 0.f};
+  bf16x8 wreg[2][D][R], xreg[2][D][MT];
+
+  auto load = [&](int buf, int tb) {
+#pragma unroll
+    for (int i = 0; i < D; ++i) {
+      const int t = tb + i;
+      const bool ok = t < t_end;
+#pragma unroll
+      for (int r = 0; r < R; ++r) wreg[buf][i][r] = ok ? wbase[((size_t)t * R + r) * 64] : zero8;
+#pragma unroll
+      for (int j = 0; j < MT; ++j) xreg[buf][i][j] = (ok && j < MTILES) ? xt[((size_t)j * KT + t) * 64 + lane] : zero8;
+    }
+  };
+  auto compute = [&](int buf) {
+#pragma unroll
+    for (int i = 0; i < D; ++i)
+#pragma unroll
+      for (int j = 0; j < MT; ++j)
+#pragma unroll
+        for (int r = 0; r < R; ++r) acc[r][j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(wreg[buf][i][r], xreg[buf][i][j], acc[r][j], 0, 0, 0);
+  };
+
+  load(0, t_begin);
+  // 1/rms of the input rows, needed only by the epilogue: fetched while the first batch is in flight
+  if (EPI != EPI_RESID) block_rinv<NWV * 64>(e.rs, 0, min(M, MT * 16), s_rinv);
+  for (int tb = t_begin; tb < t_end; tb += 2 * D) {
+    load(1, tb + D);
+    compute(0);
+    load(0, tb + 2 * D);
+    compute(1);
+  }
+
+#pragma unroll
+  for (int r = 0; r < R; ++r)
+#pragma unroll
+    for (int j = 0; j < MT; ++j) red[wave][r * MT + j][lane] = acc[r][j];
+  __syncthreads();
+
+  const int g = lane >> 4, ml = lane & 15;
+  for (int rj = wave; rj < R * MT; rj += NWV) {  // one wavefront finishes one 16 x 16 tile
+    const int r = rj / MT, j = rj % MT;
+    const int m = j * 16 + ml;
+    const int nt = blockIdx.x * R + r;
+    f32x4 v = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+    for (int w = 0; w < NWV; ++w) v += red[w][rj][lane];
+    const float ss = finish_frag<EPI>(e, M, N, m, nt * 16, g, v, EPI == EPI_RESID ? 1.f : s_rinv[j * 16 + ml]);
+    if (EPI == EPI_RESID && g == 0 && m < M) e.ssq_out[(size_t)m * (N >> 4) + nt] = ss;
+  }
+}
+
+// batch depth: 8 KiB of W in flight per wavefront for up to 32 rows, half of that beyond (the X fragments take the registers)
+template <int MT, int EPI>
+void launch_skinny(const bf16_t* xt, const bf16_t* wt, int pr, int M, int N, int K, const GemmEpi& e, hipStream_t st) {
+  if (pr == 1) gemm_skinny_kernel<MT, 1, 8, (MT <= 2 ? 8 : 4), EPI><<<N / 16, 512, 0, st>>>((const bf16x8*)xt, (const bf16x8*)wt, M, N, K, e);
+  else gemm_skinny_kernel<MT, 2, 4, (MT <= 2 ? 4 : 2), EPI><<<N / 32, 256, 0, st>>>((const bf16x8*)xt, (const bf16x8*)wt, M, N, K, e);
+}
+
+template <int EPI>
+void launch_epi(const bf16_t* xt, const bf16_t* wt, int pr, int M, int N, int K, const GemmEpi& e, hipStream_t st) {
+  if (M <= 16) launch_skinny<1, EPI>(xt, wt, pr, M, N, K, e, st);
+  else if (M <= 32) launch_skinny<2, EPI>(xt, wt, pr, M, N, K, e, st);
+  else if (M <= 48) launch_skinny<3, EPI>(xt, wt, pr, M, N, K, e, st);
+  else launch_skinny<4, EPI>(xt, wt, pr, M, N, K, e, st);
+}
+
+}  // namespace
+
+void launch_gemm_skinny(const bf16_t* xt, const bf16_t* wt, int pr, int M, int N, int K, const GemmEpi& e, hipStream_t st) {
+  switch (e.kind) {
+    case EPI_QKV: launch_epi<EPI_QKV>(xt, wt, pr, M, N, K, e, st); break;
+    case EPI_SWIGLU: launch_epi<EPI_SWIGLU>(xt, wt, pr, M, N, K, e, st); break;
+    case EPI_RESID: launch_epi<EPI_RESID>(xt, wt, pr, M, N, K, e, st); break;
+    default: launch_epi<EPI_SUM>(xt, wt, pr, M, N, K, e, st); break;
+  }
+}
