@@ -89,6 +89,8 @@ class Decoder:
         for b in group:
             row_off.append(row_off[-1] + plans[b][1])
         col = lambda i: [plans[b][i] for b in group]
+        if trace is not None:  # the tokens this pass reads, before the selection below rewrites some of them
+            self._fed = [self.tokens[b, plans[b][0]: plans[b][0] + plans[b][1]].cpu().numpy() for b in group]
         api.dlm_step(self.state, self.tokens, out, row_off, col(0), col(2), [b * self.T + plans[b][0] for b in group], slot=group,
                      kl_first=col(3), kl_count=col(4), save_first=col(5), save_count=col(6))
         self.launches += 1
@@ -136,7 +138,8 @@ class Decoder:
             for i, b in enumerate(group):
                 sp, rws = plans[b][0], plans[b][1]
                 trace.append(dict(op="pass", seq=b, kind=self.phase[b] if self.phase[b] != "prefill" else "prefill", span_start=sp,
-                                  rows=rws, commit_len=plans[b][2], logits=out.logits[row_off[i]: row_off[i] + rws].cpu()))
+                                  rows=rws, commit_len=plans[b][2], tokens=self._fed[i],
+                                  logits=out.logits[row_off[i]: row_off[i] + rws].cpu()))
                 trace.append(dict(op="select", seq=b, F=self.F[b], L=self.L[b],
                                   selected=self.sel[row_start[i]: row_start[i] + blen[i]].cpu().numpy().astype(bool)))
         for i, b in enumerate(group):
