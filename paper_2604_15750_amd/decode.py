@@ -37,6 +37,7 @@ class Decoder:
         self.sel = torch.zeros(self.max_rows, dtype=torch.uint8, device=device)
         self.nsel = torch.zeros(batch, dtype=torch.int32, device=device)
         self.L_dev = torch.zeros(batch, dtype=torch.int32, device=device)
+        self.time_steps = False  # bracket every dlm_step launch with events on the launch stream (measurement only)
 
     def load(self, prompts):
         """prompts: int array [B, P]; generation slots are filled with the mask id."""
@@ -53,6 +54,7 @@ class Decoder:
         self.nfe, self.blocks, self.steps = [0] * self.B, [[] for _ in range(self.B)], [[] for _ in range(self.B)]
         self.launches = 0
         self.rows_log = []  # rows of every dlm_step launch
+        self.step_events = []  # (rows, start, end) events around every dlm_step launch when time_steps is set
 
     def _plan(self, b):
         """(span_start, rows, commit, kl_first, kl_count, save_first, save_count) of sequence b's next pass."""
@@ -91,8 +93,14 @@ class Decoder:
         col = lambda i: [plans[b][i] for b in group]
         if trace is not None:  # the tokens this pass reads, before the selection below rewrites some of them
             self._fed = [self.tokens[b, plans[b][0]: plans[b][0] + plans[b][1]].cpu().numpy() for b in group]
+        if self.time_steps:
+            ev = (torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True))
+            ev[0].record()
         api.dlm_step(self.state, self.tokens, out, row_off, col(0), col(2), [b * self.T + plans[b][0] for b in group], slot=group,
                      kl_first=col(3), kl_count=col(4), save_first=col(5), save_count=col(6))
+        if self.time_steps:
+            ev[1].record()
+            self.step_events.append((row_off[-1], ev[0], ev[1]))
         self.launches += 1
         self.rows_log.append(row_off[-1])
         for b in group:
