@@ -206,11 +206,14 @@ int dlm_gemm_nt(const void* x, const void* w, void* y, int M, int N, int K, int 
 int dlm_attention(const void* q, const void* k, const void* v, void* out, int A, int T, int n_q, int n_kv,
                   int head_dim, int dtype, void* stream);
 
-/* Per-kernel-class timing of dlm_step: when enabled, every class of kernel launched by dlm_step is
- * bracketed by HIP events on the caller's stream.  dlm_profile_read synchronises those events and
- * returns, per class c < n, the accumulated milliseconds and launch count since the last reset.
- * Classes: 0 gemm, 1 attention, 2 vocab statistics, 3 other. */
-int dlm_profile_enable(dlm_state* s, int on);
+/* Per-kernel-class timing of dlm_step: the launches of every class whose bit is set in class_mask
+ * are bracketed by HIP events on the caller's stream (0 switches the timing off; events cost queue
+ * time, so bracket few classes when a class's own duration matters).  dlm_profile_read synchronises
+ * those events and returns, per class c < n, the accumulated milliseconds and launch count since the
+ * last reset.  Classes: 0 QKV GEMM, 1 O GEMM, 2 gate/up GEMM, 3 down GEMM, 4 LM-head GEMM,
+ * 5 attention, 6 vocabulary statistics, 7 other (row tables, embedding, and for fp32 models the
+ * row-wise glue). */
+int dlm_profile_enable(dlm_state* s, unsigned class_mask);
 int dlm_profile_read(dlm_state* s, int n, double* ms_out, int64_t* launches_out, int reset);
 
 #ifdef __cplusplus

@@ -86,7 +86,7 @@ def lib():
                                      [C.c_size_t, C.c_void_p]
         L.dlm_gemm_nt.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_int, C.c_int, C.c_int, C.c_int, C.c_void_p]
         L.dlm_attention.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p] + [C.c_int] * 6 + [C.c_void_p]
-        L.dlm_profile_enable.argtypes = [C.c_void_p, C.c_int]
+        L.dlm_profile_enable.argtypes = [C.c_void_p, C.c_uint]
         L.dlm_profile_read.argtypes = [C.c_void_p, C.c_int, C.POINTER(C.c_double), C.POINTER(C.c_int64), C.c_int]
         _lib = L
     return _lib
@@ -155,15 +155,25 @@ class State:
     def kv_len(self, slot):
         return _check(lib().dlm_state_kv_len(self.handle, slot))
 
-    def profile_enable(self, on):
-        _check(lib().dlm_profile_enable(self.handle, int(on)))
+    PROFILE_CLASSES = ("gemm_qkv", "gemm_o", "gemm_gate_up", "gemm_down", "gemm_lm_head", "attention", "vocab_stats", "other")
+
+    def profile_enable(self, classes):
+        """classes: True (all), False (none) or an iterable of names from PROFILE_CLASSES."""
+        if classes is True:
+            mask = (1 << len(self.PROFILE_CLASSES)) - 1
+        elif not classes:
+            mask = 0
+        else:
+            mask = sum(1 << self.PROFILE_CLASSES.index(c) for c in classes)
+        _check(lib().dlm_profile_enable(self.handle, mask))
 
     def profile_read(self, reset=True):
-        ms = (C.c_double * 4)()
-        n = (C.c_int64 * 4)()
-        _check(lib().dlm_profile_read(self.handle, 4, ms, n, int(reset)))
-        names = ("gemm", "attention", "vocab_stats", "other")
-        return {k: (ms[i], n[i]) for i, k in enumerate(names)}
+        """{class name: (milliseconds, launches)} since the last reset."""
+        k = len(self.PROFILE_CLASSES)
+        ms = (C.c_double * k)()
+        n = (C.c_int64 * k)()
+        _check(lib().dlm_profile_read(self.handle, k, ms, n, int(reset)))
+        return {name: (ms[i], n[i]) for i, name in enumerate(self.PROFILE_CLASSES)}
 
     def close(self):
         if self.handle:

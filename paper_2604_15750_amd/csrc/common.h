@@ -98,6 +98,7 @@ struct RowTables {  // device arrays of one pass, [rows]
   int32_t* row_seq;   // packed sequence index of the row
   int32_t* row_pos;   // absolute position
   int32_t* row_tok;   // index of the row's token in the caller's token array
+  int32_t* row_slot;  // KV-cache slot of the row's sequence
   float* rope_cos;    // [rows, hd/2]
   float* rope_sin;
   int64_t* prev_row;  // element offset of the row's retained p^prev logits, or -1
@@ -122,7 +123,7 @@ __host__ __device__ inline int weight_source_row(int n, int perm, int param) {
   }
   return n;
 }
-inline int weight_pack_rows(int N) { return N <= 8192 ? 1 : 2; }  // narrow matrices: one run per 16-column tile
+__host__ __device__ inline int weight_pack_rows(int N) { return N <= 8192 ? 1 : 2; }  // narrow matrices: one run per 16-column tile
 void launch_pack_weight(const bf16_t* w, bf16_t* out, int N, int K, int perm, int perm_param, hipStream_t st);
 void launch_pack_act(const bf16_t* x, bf16_t* out, int M, int K, hipStream_t st);  // row-major -> fragment tiles (rows padded to 16 with zeros)
 int gemm_bf16_splits(int M, int N, int K);         // partial tiles [splits][M][N] the launch of this shape needs in GemmEpi::part (1: none)
@@ -145,9 +146,8 @@ struct GemmEpi {
   int* counters;      // gemm_tiled_counters tickets, one per (column group, row block)
   RowScale rs;        // 1/rms of the GEMM's input rows (QKV, SWIGLU, DIRECT, SUM; ssq may be null)
   // EPI_QKV (weights packed with PERM_ROTARY)
-  const int32_t *row_pos, *row_seq;
+  const int32_t *row_pos, *row_slot;
   const float *rope_cos, *rope_sin;
-  int32_t slot[DLM_MAX_SEQS];
   bf16_t *q, *kcache, *vcache;
   size_t slot_stride, head_stride;
   int n_q, n_kv, hd;

@@ -54,11 +54,12 @@ struct dlm_model {
   std::vector<DevBuf> wqkv, wo, w_gate_up, w_down, norm1, norm2;
 };
 
+enum { PC_QKV = 0, PC_O = 1, PC_GATE_UP = 2, PC_DOWN = 3, PC_LM_HEAD = 4, PC_ATTENTION = 5, PC_STATS = 6, PC_OTHER = 7 };
 struct Profile {
-  bool on = false;
-  static constexpr int NC = 4;
-  double ms[NC] = {0, 0, 0, 0};
-  int64_t launches[NC] = {0, 0, 0, 0};
+  unsigned mask = 0;  // classes whose launches are bracketed by events
+  static constexpr int NC = 8;
+  double ms[NC] = {};
+  int64_t launches[NC] = {};
   struct Span { hipEvent_t a, b; int cls; };
   std::vector<Span> pending;
   std::vector<std::pair<hipEvent_t, hipEvent_t>> pool;
@@ -72,7 +73,7 @@ struct dlm_state {
   size_t layer_stride;  // elements per layer
   DevBuf kcache, vcache, prev_logits, prev_lse;
   DevBuf h, x, x2, act, q, part, stats_ws, ssq, counters;
-  DevBuf row_seq, row_pos, row_tok, rope_cos, rope_sin, prev_row, save_row;
+  DevBuf row_seq, row_pos, row_tok, row_slot, rope_cos, rope_sin, prev_row, save_row;
   std::vector<int> kv_len, prev_cur, prev_base, prev_count;
   size_t part_elems;
   Profile prof;
@@ -81,15 +82,16 @@ struct dlm_state {
 namespace {
 
 struct ProfScope {  // brackets the launches of one kernel class with events when profiling is on
-  Profile& p; hipStream_t st; int cls; hipEvent_t a = nullptr, b = nullptr;
-  ProfScope(Profile& p_, hipStream_t st_, int cls_) : p(p_), st(st_), cls(cls_) {
-    if (!p.on) return;
+  Profile& p; hipStream_t st; int cls; bool on; hipEvent_t a = nullptr, b = nullptr;
+  ProfScope(Profile& p_, hipStream_t st_, int cls_, int n_launches = 1) : p(p_), st(st_), cls(cls_), on((p_.mask >> cls_) & 1u) {
+    if (!on) return;
+    p.launches[cls] += n_launches;
     if (p.pool.empty()) { (void)hipEventCreate(&a); (void)hipEventCreate(&b); }
     else { a = p.pool.back().first; b = p.pool.back().second; p.pool.pop_back(); }
     (void)hipEventRecord(a, st);
   }
   ~ProfScope() {
-    if (!p.on) return;
+    if (!on) return;
     (void)hipEventRecord(b, st);
     p.pending.push_back({a, b, cls});
   }
@@ -219,7 +221,7 @@ extern "C" int dlm_state_create(const dlm_model* m, int max_seqs, int max_seq_le
   if (c.dtype == DLM_BF16)
     for (auto& sh : shapes) { int k = gemm_tiled_counters(max_rows, sh[0]); if (k > n_counters) n_counters = k; }
   A(s->counters, (size_t)n_counters * 4);
-  A(s->row_seq, (size_t)max_rows * 4); A(s->row_pos, (size_t)max_rows * 4); A(s->row_tok, (size_t)max_rows * 4);
+  A(s->row_seq, (size_t)max_rows * 4); A(s->row_pos, (size_t)max_rows * 4); A(s->row_tok, (size_t)max_rows * 4); A(s->row_slot, (size_t)max_rows * 4);
   A(s->rope_cos, (size_t)max_rows * (c.head_dim / 2) * 4); A(s->rope_sin, (size_t)max_rows * (c.head_dim / 2) * 4);
   A(s->prev_row, (size_t)max_rows * 8); A(s->save_row, (size_t)max_rows * 8);
   if (rc == DLM_OK) {
@@ -259,9 +261,9 @@ extern "C" int dlm_state_kv_len(const dlm_state* s, int slot) {
   return s->kv_len[slot];
 }
 
-extern "C" int dlm_profile_enable(dlm_state* s, int on) {
+extern "C" int dlm_profile_enable(dlm_state* s, unsigned class_mask) {
   REQUIRE(s, DLM_EINVAL, "dlm_profile_enable: null state");
-  s->prof.on = on != 0;
+  s->prof.mask = class_mask & ((1u << Profile::NC) - 1);
   return DLM_OK;
 }
 
@@ -291,7 +293,7 @@ int run_step_f32(dlm_state* s, const dlm_step_desc* d, const SeqMeta& meta, cons
   const dlm_model* m = s->m;
   const dlm_config& c = m->cfg;
   const int dm = c.d_model, hd = c.head_dim, nq = c.n_q_heads, nkv = c.n_kv_heads, qd = nq * hd, ffn = c.d_ffn;
-  RowTables t{(int32_t*)s->row_seq.p, (int32_t*)s->row_pos.p, (int32_t*)s->row_tok.p, (float*)s->rope_cos.p, (float*)s->rope_sin.p,
+  RowTables t{(int32_t*)s->row_seq.p, (int32_t*)s->row_pos.p, (int32_t*)s->row_tok.p, (int32_t*)s->row_slot.p, (float*)s->rope_cos.p, (float*)s->rope_sin.p,
               (int64_t*)s->prev_row.p, (int64_t*)s->save_row.p};
   float* h = (float*)s->h.p;
   T *x = (T*)s->x.p, *x2 = (T*)s->x2.p, *act = (T*)s->act.p, *q = (T*)s->q.p;
@@ -299,45 +301,41 @@ int run_step_f32(dlm_state* s, const dlm_step_desc* d, const SeqMeta& meta, cons
   float* ssq = (float*)s->ssq.p;
   Profile& pf = s->prof;
   const RowScale none{nullptr, 0, 0.f, 0.f};
-  auto gemm = [&](const float* a, const void* w, int N, int K) {
-    ProfScope ps(pf, st, 0);
-    pf.launches[0] += pf.on;
+  auto gemm = [&](int cls, const float* a, const void* w, int N, int K) {
+    ProfScope ps(pf, st, cls);
     launch_gemm_f32(a, (const float*)w, part, rows, N, K, none, st);
   };
   {
-    ProfScope ps(pf, st, 3);
-    pf.launches[3] += 2 * pf.on;
+    ProfScope ps(pf, st, PC_OTHER, 2);
     launch_prepare(meta, sm, t, rows, c.vocab, hd, c.rope_theta, st);
     launch_embed_norm<T>((const T*)m->embed.p, d->tokens, t, (const float*)m->norm1[0].p, h, x, ssq, rows, dm, st);
   }
   for (int l = 0; l < c.n_layers; ++l) {
     T* kc = (T*)s->kcache.p + s->layer_stride * l;
     T* vc = (T*)s->vcache.p + s->layer_stride * l;
-    gemm(x, m->wqkv[l].p, qd + 2 * nkv * hd, dm);
-    { ProfScope ps(pf, st, 3); pf.launches[3] += pf.on;
+    gemm(PC_QKV, x, m->wqkv[l].p, qd + 2 * nkv * hd, dm);
+    { ProfScope ps(pf, st, PC_OTHER);
       launch_rope_kv<T>(part, 1, ssq, dm, c.rms_eps, t, meta, q, kc, vc, s->slot_stride, s->head_stride, rows, nq, nkv, hd, st); }
-    { ProfScope ps(pf, st, 1); pf.launches[1] += pf.on;
+    { ProfScope ps(pf, st, PC_ATTENTION);
       launch_attention<T>(q, kc, vc, s->slot_stride, s->head_stride, am, x2, true, rows, max_seq_rows, nq, nkv, hd, st); }
-    gemm(x2, m->wo[l].p, dm, qd);
-    { ProfScope ps(pf, st, 3); pf.launches[3] += pf.on;
+    gemm(PC_O, x2, m->wo[l].p, dm, qd);
+    { ProfScope ps(pf, st, PC_OTHER);
       launch_reduce_residual_norm<T>(part, 1, h, (const float*)m->norm2[l].p, x, ssq, rows, dm, st); }
-    gemm(x, m->w_gate_up[l].p, 2 * ffn, dm);
-    { ProfScope ps(pf, st, 3); pf.launches[3] += pf.on;
+    gemm(PC_GATE_UP, x, m->w_gate_up[l].p, 2 * ffn, dm);
+    { ProfScope ps(pf, st, PC_OTHER);
       launch_silu_mul<T>(part, 1, ssq, dm, c.rms_eps, act, rows, ffn, st); }
-    gemm(act, m->w_down[l].p, dm, ffn);
-    { ProfScope ps(pf, st, 3); pf.launches[3] += pf.on;
+    gemm(PC_DOWN, act, m->w_down[l].p, dm, ffn);
+    { ProfScope ps(pf, st, PC_OTHER);
       const float* g = l + 1 < c.n_layers ? (const float*)m->norm1[l + 1].p : (const float*)m->final_norm.p;
       launch_reduce_residual_norm<T>(part, 1, h, g, x, ssq, rows, dm, st); }
   }
   {
-    ProfScope ps(pf, st, 0);
-    pf.launches[0] += pf.on;
+    ProfScope ps(pf, st, PC_LM_HEAD);
     const RowScale rs{ssq, norm_chunks(dm), 1.f / (float)dm, c.rms_eps};
     launch_gemm_f32((const float*)x, (const float*)m->lm_head.p, (float*)d->logits, rows, c.vocab, dm, rs, st);
   }
   {
-    ProfScope ps(pf, st, 2);
-    pf.launches[2] += pf.on;
+    ProfScope ps(pf, st, PC_STATS);
     StatsRows sr{t.prev_row, t.save_row, s->prev_logits.p, s->prev_logits.p, (const float*)s->prev_lse.p, (float*)s->prev_lse.p};
     StatsOut so{d->max_logit, d->lse, d->entropy, d->kl, d->conf, d->argmax};
     launch_vocab_stats<T>((const T*)d->logits, rows, c.vocab, c.mask_id, sr, so, s->stats_ws.p, st);
@@ -352,7 +350,7 @@ int run_step_bf16(dlm_state* s, const dlm_step_desc* d, const SeqMeta& meta, con
   const dlm_model* m = s->m;
   const dlm_config& c = m->cfg;
   const int dm = c.d_model, hd = c.head_dim, nq = c.n_q_heads, nkv = c.n_kv_heads, qd = nq * hd, ffn = c.d_ffn;
-  RowTables t{(int32_t*)s->row_seq.p, (int32_t*)s->row_pos.p, (int32_t*)s->row_tok.p, (float*)s->rope_cos.p, (float*)s->rope_sin.p,
+  RowTables t{(int32_t*)s->row_seq.p, (int32_t*)s->row_pos.p, (int32_t*)s->row_tok.p, (int32_t*)s->row_slot.p, (float*)s->rope_cos.p, (float*)s->rope_sin.p,
               (int64_t*)s->prev_row.p, (int64_t*)s->save_row.p};
   float* h = (float*)s->h.p;
   T *x = (T*)s->x.p, *x2 = (T*)s->x2.p, *act = (T*)s->act.p, *q = (T*)s->q.p;
@@ -369,14 +367,12 @@ int run_step_bf16(dlm_state* s, const dlm_step_desc* d, const SeqMeta& meta, con
       if ((size_t)gemm_bf16_splits(rows, sh[0], sh[1]) * rows * sh[0] > s->part_elems)
         return dlm_fail(DLM_ECAPACITY, "dlm_step: split-K workspace too small for %d rows x %d columns", rows, sh[0]);
   }
-  auto gemm = [&](const T* a, const void* w, int N, int K, const GemmEpi& e) {
-    ProfScope ps(pf, st, 0);
-    pf.launches[0] += pf.on;
+  auto gemm = [&](int cls, const T* a, const void* w, int N, int K, const GemmEpi& e) {
+    ProfScope ps(pf, st, cls);
     launch_gemm_bf16(a, (const T*)w, rows, N, K, e, st);
   };
   {
-    ProfScope ps(pf, st, 3);
-    pf.launches[3] += 2 * pf.on;
+    ProfScope ps(pf, st, PC_OTHER, 2);
     launch_prepare(meta, sm, t, rows, c.vocab, hd, c.rope_theta, st);
     launch_embed_norm<T>((const T*)m->embed.p, d->tokens, t, (const float*)m->norm1[0].p, h, x, ssq, rows, dm, st);
   }
@@ -388,19 +384,18 @@ int run_step_bf16(dlm_state* s, const dlm_step_desc* d, const SeqMeta& meta, con
       GemmEpi e = base;
       e.kind = EPI_QKV;
       e.rs = RowScale{ssq, nch, 1.f / (float)dm, c.rms_eps};
-      e.row_pos = t.row_pos; e.row_seq = t.row_seq; e.rope_cos = t.rope_cos; e.rope_sin = t.rope_sin;
-      for (int b = 0; b < meta.n_seqs; ++b) e.slot[b] = meta.slot[b];
+      e.row_pos = t.row_pos; e.row_slot = t.row_slot; e.rope_cos = t.rope_cos; e.rope_sin = t.rope_sin;
       e.q = q; e.kcache = kc; e.vcache = vc; e.slot_stride = s->slot_stride; e.head_stride = s->head_stride;
       e.n_q = nq; e.n_kv = nkv; e.hd = hd;
-      gemm(x, m->wqkv[l].p, qd + 2 * nkv * hd, dm, e);
+      gemm(PC_QKV, x, m->wqkv[l].p, qd + 2 * nkv * hd, dm, e);
     }
-    { ProfScope ps(pf, st, 1); pf.launches[1] += pf.on;
+    { ProfScope ps(pf, st, PC_ATTENTION);
       launch_attention<T>(q, kc, vc, s->slot_stride, s->head_stride, am, x2, true, rows, max_seq_rows, nq, nkv, hd, st); }
     {
       GemmEpi e = base;
       e.kind = EPI_RESID;
       e.h = h; e.gain = (const float*)m->norm2[l].p; e.x = x; e.ssq_out = ssq;
-      gemm(x2, m->wo[l].p, dm, qd, e);
+      gemm(PC_O, x2, m->wo[l].p, dm, qd, e);
       nch = gemm_bf16_ssq_chunks(rows, dm);
     }
     {
@@ -408,14 +403,14 @@ int run_step_bf16(dlm_state* s, const dlm_step_desc* d, const SeqMeta& meta, con
       e.kind = EPI_SWIGLU;
       e.rs = RowScale{ssq, nch, 1.f / (float)dm, c.rms_eps};
       e.act = act; e.ffn = ffn;
-      gemm(x, m->w_gate_up[l].p, 2 * ffn, dm, e);
+      gemm(PC_GATE_UP, x, m->w_gate_up[l].p, 2 * ffn, dm, e);
     }
     {
       GemmEpi e = base;
       e.kind = EPI_RESID;
       e.h = h; e.gain = l + 1 < c.n_layers ? (const float*)m->norm1[l + 1].p : (const float*)m->final_norm.p;
       e.x = x; e.ssq_out = ssq;
-      gemm(act, m->w_down[l].p, dm, ffn, e);
+      gemm(PC_DOWN, act, m->w_down[l].p, dm, ffn, e);
     }
   }
   {
@@ -423,11 +418,10 @@ int run_step_bf16(dlm_state* s, const dlm_step_desc* d, const SeqMeta& meta, con
     e.kind = EPI_DIRECT;
     e.rs = RowScale{ssq, nch, 1.f / (float)dm, c.rms_eps};
     e.out_bf16 = (T*)d->logits;
-    gemm(x, m->lm_head.p, c.vocab, dm, e);
+    gemm(PC_LM_HEAD, x, m->lm_head.p, c.vocab, dm, e);
   }
   {
-    ProfScope ps(pf, st, 2);
-    pf.launches[2] += pf.on;
+    ProfScope ps(pf, st, PC_STATS);
     StatsRows sr{t.prev_row, t.save_row, s->prev_logits.p, s->prev_logits.p, (const float*)s->prev_lse.p, (float*)s->prev_lse.p};
     StatsOut so{d->max_logit, d->lse, d->entropy, d->kl, d->conf, d->argmax};
     launch_vocab_stats<T>((const T*)d->logits, rows, c.vocab, c.mask_id, sr, so, s->stats_ws.p, st);

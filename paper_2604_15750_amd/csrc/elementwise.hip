@@ -16,6 +16,7 @@ __global__ void prepare_kernel(SeqMeta meta, StatsMeta sm, RowTables t, int rows
     t.row_seq[r] = b;
     t.row_pos[r] = pos;
     t.row_tok[r] = meta.tok_start[b] + rel;
+    t.row_slot[r] = meta.slot[b];
     const int kr = rel - sm.kl_first[b];
     t.prev_row[r] = (kr >= 0 && kr < sm.kl_count[b]) ? sm.prev_off[b] + (int64_t)kr * vocab : -1;
     const int sr = rel - sm.save_first[b];

@@ -54,6 +54,7 @@ class Decoder:
         self.nfe, self.blocks, self.steps = [0] * self.B, [[] for _ in range(self.B)], [[] for _ in range(self.B)]
         self.launches = 0
         self.rows_log = []  # rows of every dlm_step launch
+        self.pass_log = []  # per launch: (rows of each packed sequence, cached prefix length of each)
         self.step_events = []  # (rows, start, end) events around every dlm_step launch when time_steps is set
 
     def _plan(self, b):
@@ -103,6 +104,7 @@ class Decoder:
             self.step_events.append((row_off[-1], ev[0], ev[1]))
         self.launches += 1
         self.rows_log.append(row_off[-1])
+        self.pass_log.append(([plans[b][1] for b in group], [plans[b][0] for b in group]))
         for b in group:
             self.nfe[b] += 1
         # block-boundary decisions for the sequences that just finished a block (or the prompt)

@@ -37,6 +37,10 @@ WORKLOADS = {
 # hyper-parameters of Sec. 5.1 of the paper (L_max comes with the workload)
 PAPER_PARAMS = dict(l_min=8, lam=1.2, smooth_radius=1, norm_mode=0, rule=0,
                     tau_low=0.8, tau_high=0.95, gamma=-16.0, mode=0)
+# A random-init model never reaches those confidences (it commits one token per pass).  This second set puts the thresholds
+# inside the confidence range such a model does reach at the benchmark vocabularies, so that every branch of the selection
+# rule runs and passes commit several tokens.
+SCALED_THRESHOLDS = dict(lam=0.9, tau_low=0.04, tau_high=0.25, gamma=-36.0)
 
 
 def with_depth(cfg, n_layers):

@@ -23,7 +23,7 @@ pytestmark = pytest.mark.gpu
 
 # thresholds that let CAP-Decoding take several tokens per pass on random-init weights (their confidences are a few
 # per cent to a few tens of per cent); lambda below 1 so that blocks grow beyond L_min
-SCALED = dict(inputs.PAPER_PARAMS, lam=0.9, tau_low=0.04, tau_high=0.25, gamma=-36.0)
+SCALED = dict(inputs.PAPER_PARAMS, **inputs.SCALED_THRESHOLDS)
 
 
 def _twin(name, layers=2):
