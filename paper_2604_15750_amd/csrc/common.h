@@ -168,6 +168,9 @@ void launch_gemm_bf16(const bf16_t* xt, const bf16_t* wt, int M, int N, int K, c
 #define GEMM_SKINNY_MAX_ROWS 64
 void launch_gemm_skinny(const bf16_t* xt, const bf16_t* wt, int pr, int M, int N, int K, const GemmEpi& e, hipStream_t st);  // M <= GEMM_SKINNY_MAX_ROWS
 void launch_gemm_tiled(const bf16_t* xt, const bf16_t* wt, int M, int N, int K, const GemmEpi& e, hipStream_t st);
+#define GEMM_MACRO_MIN_ROWS_NARROW 256  // more rows than this: the macro-tile kernel whatever the width
+int gemm_macro_ssq_chunks(int M, int N);
+void launch_gemm_macro(const bf16_t* xt, const bf16_t* wt, int M, int N, int K, const GemmEpi& e, hipStream_t st);
 void launch_gemm_f32(const float* x, const float* w, float* y, int M, int N, int K, RowScale rs, hipStream_t st);
 
 void launch_prepare(const SeqMeta& meta, const StatsMeta& sm, RowTables t, int rows, int vocab, int head_dim, float theta, hipStream_t st);

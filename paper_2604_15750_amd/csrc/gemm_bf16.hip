@@ -8,7 +8,8 @@
 //   * activations live in the same fragment tiling (B operand), written that way by their producer;
 //   * the product is computed transposed (W fragment = A operand), so a lane ends up with four
 //     consecutive output columns of one row.
-// gemm_skinny.hip serves M <= 64, gemm_tiled.hip everything else and the LM head; the layer's
+// gemm_skinny.hip serves M <= 64 (except the LM head), gemm_macro.hip (both operands through LDS, large output tiles:
+// bound by the matrix cores, not by W) wide passes, gemm_tiled.hip what lies between; the layer's
 // row-wise glue runs in their epilogues (gemm_epilogue.h):
 //   QKV     1/rms of the input row, rotary embedding, Q row-major, K and V into the tiled KV cache
 //   SWIGLU  1/rms, silu(gate) * up into the fragment tiling of the down projection
@@ -53,6 +54,10 @@ __global__ void pack_act_kernel(const bf16x8* __restrict__ x, bf16x8* __restrict
 }
 
 bool use_skinny(int M, int N, int kind) { return kind != EPI_DIRECT && M <= GEMM_SKINNY_MAX_ROWS && N % (16 * weight_pack_rows(N)) == 0; }
+// The macro-tile kernel has no K split: it needs enough output tiles of its own.  Wide matrices (QKV, gate/up, LM head) have
+// them from 65 rows on; the narrow ones (O, down: 32 column tiles of 128) only beyond 256 rows, below that the tiled
+// kernel's K split keeps more of the chip busy.
+bool use_macro(int M, int N) { return M > GEMM_MACRO_MIN_ROWS_NARROW || (M > GEMM_SKINNY_MAX_ROWS && N > 8192); }
 
 }  // namespace
 
@@ -63,10 +68,13 @@ void launch_pack_act(const bf16_t* x, bf16_t* out, int M, int K, hipStream_t st)
   pack_act_kernel<<<512, 256, 0, st>>>((const bf16x8*)x, (bf16x8*)out, M, K);
 }
 
-int gemm_bf16_splits(int M, int N, int K) { return use_skinny(M, N, EPI_SUM) ? 1 : gemm_tiled_splits(M, N, K); }
-int gemm_bf16_ssq_chunks(int M, int N) { return use_skinny(M, N, EPI_RESID) ? N >> 4 : gemm_tiled_ssq_chunks(M, N); }
+int gemm_bf16_splits(int M, int N, int K) { return use_skinny(M, N, EPI_SUM) || use_macro(M, N) ? 1 : gemm_tiled_splits(M, N, K); }
+int gemm_bf16_ssq_chunks(int M, int N) {
+  return use_skinny(M, N, EPI_RESID) ? N >> 4 : use_macro(M, N) ? gemm_macro_ssq_chunks(M, N) : gemm_tiled_ssq_chunks(M, N);
+}
 
 void launch_gemm_bf16(const bf16_t* xt, const bf16_t* wt, int M, int N, int K, const GemmEpi& e, hipStream_t st) {
   if (use_skinny(M, N, e.kind)) launch_gemm_skinny(xt, wt, weight_pack_rows(N), M, N, K, e, st);
+  else if (use_macro(M, N)) launch_gemm_macro(xt, wt, M, N, K, e, st);
   else launch_gemm_tiled(xt, wt, M, N, K, e, st);
 }

@@ -1,0 +1,220 @@
+// Macro-tile bf16 GEMM for wide passes (M > 256 rows: batched decoding, prefill): Y[M,N] = X[M,K] * W[N,K]^T,
+// fp32 accumulation, epilogue fused.
+//
+// Beyond a few hundred rows the GEMMs leave the weight-streaming regime and are bound by the matrix
+// cores and by how often operands are re-read.  A workgroup of four wavefronts (2 x 2) owns a tile of
+// 32 WM rows x 32 WN columns (128 x 256 or 128 x 128; the kernel is written for any WM, WN, but with
+// 256 x 256 the compiler no longer keeps 256 accumulators and two operand sets in registers without
+// spilling inside the loop) and walks K one k-tile (32) at a time:
+//   * both operands are already stored as 1 KiB matrix-core fragments (16 rows x 32 k), so a stage of
+//     the pipeline is just 2 WM + 2 WN fragments copied HBM/L2 -> LDS by direct-to-LDS loads (no
+//     registers, no LDS writes): 5 to 8 stages of 16 .. 24 KiB rotate through up to 128 KiB of LDS;
+//   * a wavefront owns WM x WN fragments of the output (fp32 accumulators, up to 256 registers), reads
+//     its WM + WN operand fragments of the NEXT k-tile from LDS into a second register set while the
+//     matrix cores work on the current one (WM WN products per WM + WN fragment reads);
+//   * the accumulators reach the epilogue through LDS, half of a wavefront's column tiles at a time;
+//   * one barrier per k-tile; the waits on the direct-to-LDS loads are counted by hand (every stage is
+//     the same number of loads per wavefront; indices past the end are clamped, so the count never
+//     varies).
+// Workgroups that share columns (and so W) get ids congruent mod 8: they run on the same XCD and find
+// W in its L2 after the first reader; X is shared by every column block through the L2s and the
+// memory-side cache.  The product is computed transposed (W fragment = A operand) like the other
+// kernels, so the epilogues of gemm_epilogue.h apply unchanged.
+#include "gemm_epilogue.h"
+
+namespace {
+
+constexpr int TPB = 256;
+
+#define GLOBAL_PTR(p) ((const void __attribute__((address_space(1)))*)(p))
+#define LDS_PTR(p) ((void __attribute__((address_space(3)))*)(p))
+
+template <int WM, int WN>
+struct MacroShape {
+  static constexpr int AF = 2 * WM, BF = 2 * WN;  // X (row) and W (column) fragments of a stage
+  static constexpr int NFR = AF + BF;
+  static constexpr int LPS = NFR / 4;              // direct-to-LDS loads per wavefront and stage
+  static constexpr int STAGE = NFR * 1024;
+  static constexpr int S = 131072 / STAGE > 8 ? 8 : 131072 / STAGE;  // stages: at most 128 KiB
+  static constexpr int LDS_BYTES = S * STAGE + AF * 16 * 4 * 3;      // + 1/rms of the rows, two partial sums of squares per row
+};
+
+template <int WM, int WN, int PR, int EPI>
+__global__ __launch_bounds__(TPB) void gemm_macro_kernel(const bf16x8* __restrict__ xt, const bf16x8* __restrict__ wt, int M, int N, int K,
+                                                         int nblocks, int mblocks, GemmEpi e) {
+  typedef MacroShape<WM, WN> SH;
+  constexpr int AF = SH::AF, BF = SH::BF, LPS = SH::LPS, STAGE = SH::STAGE, S = SH::S;
+  static_assert(AF % 4 == 0 && BF % 4 == 0 && S >= 4 && (S - 2) * LPS < 64, "pipeline shape");
+  extern __shared__ __align__(16) unsigned char lds[];
+  float* s_rinv = (float*)(lds + S * STAGE);  // [AF * 16]
+  float* s_ssq = s_rinv + AF * 16;            // [2][AF * 16]
+
+  // workgroup id -> (column block, row block): ids congruent mod 8 share an XCD
+  const int q = blockIdx.x >> 3;
+  const int rb = q % mblocks;
+  const int cb = (q / mblocks) * 8 + (blockIdx.x & 7);
+  if (cb >= nblocks) return;
+
+  const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int wm = wave >> 1, wn = wave & 1;
+  const int KT = K >> 5, MTILES = (M + 15) >> 4, NT = N >> 4;
+  const int mt0 = rb * AF, nt0 = cb * BF;
+
+  // stage kt % S <- k-tile kt: fragment f (f < AF: X row tile mt0 + f, else W column tile nt0 + f - AF) is moved by wavefront f % 4
+  auto issue = [&](int kt) {
+    const int t = min(kt, KT - 1);
+    unsigned char* base = lds + (kt % S) * STAGE;
+#pragma unroll
+    for (int i = 0; i < LPS; ++i) {
+      const int f = i * 4 + wave;
+      const bf16x8* src;
+      if (i < AF / 4) {
+        const int mt = min(mt0 + f, MTILES - 1);
+        src = xt + ((size_t)mt * KT + t) * 64 + lane;
+      } else {
+        const int nt = min(nt0 + f - AF, NT - 1);
+        src = PR == 2 ? wt + (((size_t)(nt >> 1) * KT + t) * 2 + (nt & 1)) * 64 + lane : wt + ((size_t)nt * KT + t) * 64 + lane;
+      }
+      __builtin_amdgcn_global_load_lds(GLOBAL_PTR(src), LDS_PTR(base + f * 1024), 16, 0, 0);
+    }
+  };
+
+  f32x4 acc[WN][WM];
+#pragma unroll
+  for (int j = 0; j < WN; ++j)
+#pragma unroll
+    for (int i = 0; i < WM; ++i) acc[j][i] = f32x4{0.f, 0.f, 0.f, 0.f};
+  bf16x8 xf[2][WM], wf[2][WN];
+  auto read_frags = [&](int buf, int kt) {
+    const bf16x8* st = (const bf16x8*)(lds + (kt % S) * STAGE) + lane;
+#pragma unroll
+    for (int i = 0; i < WM; ++i) xf[buf][i] = st[(wm * WM + i) * 64];
+#pragma unroll
+    for (int j = 0; j < WN; ++j) wf[buf][j] = st[(AF + wn * WN + j) * 64];
+  };
+  auto multiply = [&](int buf) {
+#pragma unroll
+    for (int j = 0; j < WN; ++j)
+#pragma unroll
+      for (int i = 0; i < WM; ++i) acc[j][i] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(wf[buf][j], xf[buf][i], acc[j][i], 0, 0, 0);
+  };
+
+#pragma unroll
+  for (int s = 0; s < S - 1; ++s) issue(s);
+  asm volatile("s_waitcnt vmcnt(%0)" ::"n"((S - 2) * LPS) : "memory");  // stage 0 has landed (this wavefront's share)
+  __builtin_amdgcn_s_barrier();
+  asm volatile("" ::: "memory");
+  read_frags(0, 0);
+  // iteration kt: registers kt & 1 hold stage kt; stages kt + 1 .. kt + S - 2 are in flight
+  auto step = [&](int buf, int kt) {
+    asm volatile("s_waitcnt vmcnt(%0)" ::"n"((S - 3) * LPS) : "memory");  // stage kt + 1 has landed
+    __builtin_amdgcn_s_barrier();  // ... for every wavefront, and every wavefront has finished with the buffer of stage kt - 1
+    asm volatile("" ::: "memory");
+    issue(kt + S - 1);
+    read_frags(buf ^ 1, kt + 1);
+    multiply(buf);
+  };
+  for (int kt = 0; kt < KT; kt += 2) {
+    step(0, kt);
+    if (kt + 1 < KT) step(1, kt + 1);
+  }
+  asm volatile("s_waitcnt vmcnt(0)" ::: "memory");  // the surplus loads of the last stages: LDS must be quiet before it is reused
+
+  // ---- epilogue
+  const int g = lane >> 4, ml = lane & 15;
+  const int m_lo = mt0 * 16;
+  if (EPI != EPI_RESID) block_rinv<TPB>(e.rs, m_lo, max(0, min(M, m_lo + AF * 16) - m_lo), s_rinv);
+  __syncthreads();
+  // The accumulators leave the registers through LDS (each wavefront its own region, half of its column tiles at a time), so
+  // that the epilogue runs as a loop over fragments instead of 64 unrolled copies with every accumulator live.
+  constexpr int HJ = WN / 2;
+  f32x4* mine = (f32x4*)lds + wave * (HJ * WM * 64) + lane;
+  float ssq[WM];
+#pragma unroll
+  for (int i = 0; i < WM; ++i) ssq[i] = 0.f;
+#pragma unroll
+  for (int h = 0; h < 2; ++h) {
+#pragma unroll
+    for (int jj = 0; jj < HJ; ++jj)
+#pragma unroll
+      for (int i = 0; i < WM; ++i) mine[(jj * WM + i) * 64] = acc[h * HJ + jj][i];
+#pragma unroll
+    for (int i = 0; i < WM; ++i) {
+      const int rl = (wm * WM + i) * 16 + ml;
+      const float rinv = EPI == EPI_RESID ? 1.f : s_rinv[rl];
+#pragma unroll 1
+      for (int jj = 0; jj < HJ; ++jj) {
+        const int nt = nt0 + wn * WN + h * HJ + jj;
+        if (nt >= NT) break;  // uniform in the wavefront
+        ssq[i] += finish_frag<EPI>(e, M, N, m_lo + rl, nt * 16, g, mine[(jj * WM + i) * 64], rinv);
+      }
+    }
+  }
+  if (EPI == EPI_RESID) {  // the workgroup's share of sum h^2 per row: its two column halves in order
+    if (g == 0)
+#pragma unroll
+      for (int i = 0; i < WM; ++i) s_ssq[wn * AF * 16 + (wm * WM + i) * 16 + ml] = ssq[i];
+    __syncthreads();
+    const int m = m_lo + tid;
+    if (tid < AF * 16 && m < M) e.ssq_out[(size_t)m * nblocks + cb] = s_ssq[tid] + s_ssq[AF * 16 + tid];
+  }
+}
+
+struct MacroPlan {
+  int wm, wn, nblocks, mblocks;
+};
+
+// the tile with the least estimated time: rounds of workgroups over the chip x products per workgroup, the smaller tiles
+// charged for their heavier LDS traffic
+MacroPlan macro_plan(int M, int N) {
+  const int cand[2][2] = {{4, 8}, {4, 4}};
+  const double penalty[2] = {1.0, 1.25};
+  MacroPlan best{4, 8, 1, 1};
+  double best_cost = 1e300;
+  for (int c = 0; c < 2; ++c) {
+    const int bm = 32 * cand[c][0], bn = 32 * cand[c][1];
+    const int mb = (M + bm - 1) / bm, nb = (N + bn - 1) / bn;
+    const int rounds = (mb * nb + 255) / 256;
+    const double cost = (double)rounds * bm * bn * penalty[c];
+    if (cost < best_cost) { best_cost = cost; best = MacroPlan{cand[c][0], cand[c][1], nb, mb}; }
+  }
+  return best;
+}
+
+template <int WM, int WN, int PR, int EPI>
+void launch_one(const bf16_t* xt, const bf16_t* wt, int M, int N, int K, const MacroPlan& p, const GemmEpi& e, hipStream_t st) {
+  typedef MacroShape<WM, WN> SH;
+  static bool configured = false;  // raise the dynamic LDS limit of this instantiation once
+  if (!configured) {
+    (void)hipFuncSetAttribute((const void*)gemm_macro_kernel<WM, WN, PR, EPI>, hipFuncAttributeMaxDynamicSharedMemorySize, SH::LDS_BYTES);
+    configured = true;
+  }
+  const int grid = (p.nblocks + 7) / 8 * 8 * p.mblocks;
+  gemm_macro_kernel<WM, WN, PR, EPI><<<grid, TPB, SH::LDS_BYTES, st>>>((const bf16x8*)xt, (const bf16x8*)wt, M, N, K, p.nblocks, p.mblocks, e);
+}
+
+template <int PR, int EPI>
+void launch_shape(const bf16_t* xt, const bf16_t* wt, int M, int N, int K, const MacroPlan& p, const GemmEpi& e, hipStream_t st) {
+  if (p.wn == 8) launch_one<4, 8, PR, EPI>(xt, wt, M, N, K, p, e, st);
+  else launch_one<4, 4, PR, EPI>(xt, wt, M, N, K, p, e, st);
+}
+
+template <int EPI>
+void launch_epi(const bf16_t* xt, const bf16_t* wt, int M, int N, int K, const MacroPlan& p, const GemmEpi& e, hipStream_t st) {
+  if (weight_pack_rows(N) == 2) launch_shape<2, EPI>(xt, wt, M, N, K, p, e, st);
+  else launch_shape<1, EPI>(xt, wt, M, N, K, p, e, st);
+}
+
+}  // namespace
+
+int gemm_macro_ssq_chunks(int M, int N) { return macro_plan(M, N).nblocks; }
+
+void launch_gemm_macro(const bf16_t* xt, const bf16_t* wt, int M, int N, int K, const GemmEpi& e, hipStream_t st) {
+  const MacroPlan p = macro_plan(M, N);
+  switch (e.kind) {
+    case EPI_QKV: launch_epi<EPI_QKV>(xt, wt, M, N, K, p, e, st); break;
+    case EPI_SWIGLU: launch_epi<EPI_SWIGLU>(xt, wt, M, N, K, p, e, st); break;
+    case EPI_RESID: launch_epi<EPI_RESID>(xt, wt, M, N, K, p, e, st); break;
+    default: launch_epi<EPI_SUM>(xt, wt, M, N, K, p, e, st); break;
+  }
+}

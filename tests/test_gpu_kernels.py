@@ -29,7 +29,9 @@ def _rowtol(ref, rel, floor=0.0):
 
 # ---- GEMM ----------------------------------------------------------------------------------------
 @pytest.mark.parametrize("M,N,K", [(1, 32, 32), (7, 64, 96), (16, 128, 128), (64, 4096, 4096), (100, 160, 4096 + 64),
-                                   (192, 1024, 1536), (300, 96, 512), (33, 12288, 256), (64, 256, 12288)])
+                                   (192, 1024, 1536), (300, 96, 512), (33, 12288, 256), (64, 256, 12288),
+                                   # more than 256 rows: the macro-tile kernel (ragged rows, column tails, both weight packings, short K)
+                                   (257, 4096, 4096), (513, 8224, 1024), (700, 160, 4096 + 64), (1100, 640, 64), (384, 12288, 32)])
 def test_gemm_bf16(device, M, N, K):
     g = torch.Generator(device="cpu").manual_seed(M * 7 + N + K)
     x = torch.randn(M, K, generator=g).to(torch.bfloat16).to(device)
