@@ -75,6 +75,39 @@ def traffic_from_profile(workload):
         return None
 
 
+def micro_vocab_stats(args):
+    """The vocabulary-statistics kernel alone at a batched-pass shape (HBM-bound: the logits are read once, plus the retained
+    p^prev logits on KL rows).  Buffers rotate over more than the 256 MB memory-side cache.  Prints one JSON line."""
+    import torch
+    from paper_2604_15750_amd import api, inputs
+
+    dev = torch.device("cuda:0")
+    V = inputs.WORKLOADS[args.workload][0]["vocab"]
+    rows, with_prev = args.rows, bool(args.prev)
+    nb = max(2, min(8, int(1.2e9 // (rows * V * 2))))
+    mk = lambda: torch.randn(rows, V, device=dev, dtype=torch.float32).mul_(4).to(torch.bfloat16)
+    zs = [mk() for _ in range(nb)]
+    ps = [mk() for _ in range(nb)] if with_prev else None
+    ws = torch.empty(api.lib().dlm_vocab_stats_workspace(rows), dtype=torch.uint8, device=dev)
+    run = lambda i: api.dlm_vocab_stats(zs[i % nb], V - 1, prev=ps[i % nb] if ps else None, workspace=ws)
+    for i in range(args.warmup + 2):
+        run(i)
+    torch.cuda.synchronize()
+    a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    iters = max(args.steps, 1) * 10
+    a.record()
+    for i in range(iters):
+        run(i)
+    b.record()
+    torch.cuda.synchronize()
+    us = a.elapsed_time(b) * 1e3 / iters
+    by = rows * V * 2 * (2 if with_prev else 1)
+    gbs = by / (us * 1e-6) / 1e9
+    print(json.dumps({"micro": "vocab_stats", "rows": rows, "vocab": V, "kl_rows": with_prev, "launches": iters, "avg_launch_us": us,
+                      "bytes_per_launch": by,
+                      "roofline": {"bound": "hbm", "achieved": gbs, "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": gbs / HBM_PEAK_GBS}}))
+
+
 def cpu_baseline(cfg, W_host, prompt, prm, sample_layers):
     """The oracle, as it stands, on a bounded sample: prefill + the first in-block pass of the same
     workload through the first `sample_layers` layers and the LM head; the in-block pass time is
@@ -128,12 +161,19 @@ def main():
     ap.add_argument("--thresholds", default="paper", choices=["paper", "scaled"],
                     help="paper: the defaults of Sec. 5.1; scaled: thresholds placed inside the confidence range of a random-init model, "
                          "so that CAP-Decoding commits several tokens per pass")
+    ap.add_argument("--micro", default="", choices=["", "vocab_stats"], help="time one kernel alone instead of the decode")
+    ap.add_argument("--rows", type=int, default=3072, help="--micro: rows of the pass (3072 = 16 sequences x 192 rows, the widest batched pass)")
+    ap.add_argument("--prev", type=int, default=1, help="--micro vocab_stats: 1 = every row is a KL row (reads the retained logits too)")
     ap.add_argument("--copy-calibration", action="store_true",
-                    help="also copy a 1 GiB tensor three times (a kernel of known HBM traffic, to scale rocprofv3's FETCH_SIZE / WRITE_SIZE)")
+                    help="also run out = in + 1 over 1 GiB three times (a kernel of known HBM traffic, to scale rocprofv3's FETCH_SIZE / WRITE_SIZE)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on one GPU only (every box has one); --gpus must be 1", file=sys.stderr)
         sys.exit(2)
+
+    if args.micro == "vocab_stats":
+        micro_vocab_stats(args)
+        return
 
     import torch
     from paper_2604_15750_amd import api, inputs
@@ -204,6 +244,21 @@ def main():
     roof["kernel"] = "gemm_skinny_kernel / gemm_tiled_kernel with the SwiGLU epilogue (gate/up GEMM, every launch of one decode)"
     roof["traffic"] = traffic_from_profile(args.workload)
     others = {cls: class_roofline(cls, *prof[cls]) for cls in GEMM_CLASSES}
+    # attention against the HBM time of its K/V reads (cached prefix + the span's own rows, every layer); vocabulary statistics
+    # against one read of the logits (plus the retained logits on KL rows)
+    kvw = cfg["n_kv_heads"] * cfg["head_dim"]
+    att_bytes = cfg["n_layers"] * sum(2 * (kv + r) * kvw * 2 for rows_l, kv_l in dec.pass_log for r, kv in zip(rows_l, kv_l))
+    att_flops = cfg["n_layers"] * sum(4 * r * (kv + r) * cfg["n_q_heads"] * cfg["head_dim"] for rows_l, kv_l in dec.pass_log for r, kv in zip(rows_l, kv_l))
+    att_ms, att_n = prof["attention"]
+    others["attention"] = {"bound": "hbm", "achieved": att_bytes / (att_ms * 1e-3) / 1e9, "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                           "frac": att_bytes / (att_ms * 1e-3) / 1e9 / HBM_PEAK_GBS, "avg_launch_us": att_ms * 1e3 / max(att_n, 1), "launches": att_n,
+                           "bytes_per_launch": att_bytes / max(att_n, 1), "mfma_tflops": att_flops / (att_ms * 1e-3) / 1e12}
+    vs_ms, vs_n = prof["vocab_stats"]
+    vs_bytes = sum(rows_hist) * cfg["vocab"] * 2 + dec.kl_rows * cfg["vocab"] * 2
+    others["vocab_stats"] = {"bound": "hbm", "achieved": vs_bytes / (vs_ms * 1e-3) / 1e9, "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                             "frac": vs_bytes / (vs_ms * 1e-3) / 1e9 / HBM_PEAK_GBS, "avg_launch_us": vs_ms * 1e3 / max(vs_n, 1), "launches": vs_n,
+                             "bytes_per_launch": vs_bytes / max(vs_n, 1),
+                             "note": "narrow passes: launch-bound, and the logits were just written (cache hits); see --micro vocab_stats for the batched shape"}
     # the whole decode against the sum of its passes' roofline floors
     floor_ms = sum(pass_floor_us(cfg, rows_l, kv_l) for rows_l, kv_l in dec.pass_log) * 1e-3
     out = {
@@ -223,10 +278,10 @@ def main():
         "setup_s": t_setup,
     }
     if args.copy_calibration:
-        src = torch.empty(1 << 30, dtype=torch.uint8, device=dev).fill_(1)
+        src = torch.ones(1 << 28, dtype=torch.int32, device=dev)  # 1 GiB
         dst = torch.empty_like(src)
         for _ in range(3):
-            dst.copy_(src)
+            torch.add(src, 1, out=dst)  # an elementwise kernel (CUDAFunctor_add) that reads 1 GiB and writes 1 GiB
         torch.cuda.synchronize()
     if not args.no_cpu:
         out["cpu_baseline"] = cpu_baseline(cfg, W_host, prompts[0], prm, min(args.cpu_layers, cfg["n_layers"]))

@@ -35,14 +35,27 @@ __device__ inline void st_f32x4(float* p, f32x4 v) {
 }
 
 // 1/rms of rows [m_lo, m_lo + rows) from the producer's partial sums of squares into s_rinv, by the whole workgroup of NT
-// threads: sixteen lanes per row, each adding every sixteenth chunk, then a fixed butterfly (deterministic).
+// threads: sixteen lanes per row, each adding every sixteenth chunk in ascending order, then a fixed butterfly
+// (deterministic).  A lane's sixteen loads of a block of 256 chunks are issued together and waited for once: one trip to
+// memory per block instead of one per chunk.
 template <int NT>
 __device__ inline void block_rinv(const RowScale& rs, int m_lo, int rows, float* s_rinv) {
   const int sub = threadIdx.x & 15;
   for (int row = threadIdx.x >> 4; row < rows; row += NT / 16) {
     float ss = 0.f;
-    if (rs.ssq)
-      for (int c = sub; c < rs.nch; c += 16) ss += rs.ssq[(size_t)(m_lo + row) * rs.nch + c];
+    if (rs.ssq) {
+      const float* src = rs.ssq + (size_t)(m_lo + row) * rs.nch;
+      for (int c0 = 0; c0 < rs.nch; c0 += 256) {
+        float v[16];
+#pragma unroll
+        for (int k = 0; k < 16; ++k) {
+          const int c = c0 + sub + 16 * k;
+          v[k] = c < rs.nch ? src[c] : 0.f;
+        }
+#pragma unroll
+        for (int k = 0; k < 16; ++k) ss += v[k];
+      }
+    }
 #pragma unroll
     for (int o = 8; o > 0; o >>= 1) ss += __shfl_xor(ss, o, 64);
     if (sub == 0) s_rinv[row] = rs.ssq ? rsqrtf(ss * rs.inv_d + rs.eps) : 1.f;
