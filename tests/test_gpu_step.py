@@ -40,7 +40,7 @@ def _f32(prm):
     return out
 
 
-def replay(cfg, W_dev, prompt, N, prm, device, logit_tol, max_passes=None):
+def replay(cfg, W_dev, prompt, N, prm, device, logit_tol, max_passes=None, stats_out=None):
     prm = _f32(prm)
     P, END, lmax, mask = len(prompt), len(prompt) + N, prm["l_max"], cfg["mask_id"]
     Wn = inputs.weights_to_numpy(W_dev)
@@ -57,7 +57,7 @@ def replay(cfg, W_dev, prompt, N, prm, device, logit_tol, max_passes=None):
     mg = torch.zeros(1, dtype=torch.float32, device=device)
     L_dev = torch.zeros(1, dtype=torch.int32, device=device)
     prev = None  # (base position, GPU logits fp64) retained by the previous prefill / boundary pass
-    worst = 0.0
+    worst = rms = 0.0
     n_pass = n_bnd = n_sel = 0
     last = None
     for rec in trace:
@@ -81,6 +81,10 @@ def replay(cfg, W_dev, prompt, N, prm, device, logit_tol, max_passes=None):
             scale = np.maximum(np.abs(ref).max(-1, keepdims=True), SIGMA_LOGIT)
             err = (np.abs(z - ref) / scale).max()
             worst = max(worst, err)
+            rms = max(rms, float((np.sqrt(np.mean((z - ref) ** 2, -1)) / np.sqrt(np.mean(ref ** 2, -1))).max()))
+            if stats_out is not None:
+                stats_out.append(dict(kind=rec["kind"], rows=rows, worst=float(err), rms=rms,
+                                      p999=float(np.quantile(np.abs(z - ref) / scale, 0.999)), frac_over=float((np.abs(z - ref) / scale > logit_tol).mean())))
             assert err <= logit_tol, (rec["kind"], s0, rows, err)
             st = o_stats.vocab_stats(z, mask)
             got = {k: getattr(out, k)[:rows].cpu().numpy() for k in ("max_logit", "lse", "entropy", "conf", "argmax", "kl")}
@@ -136,7 +140,7 @@ def replay(cfg, W_dev, prompt, N, prm, device, logit_tol, max_passes=None):
             n_sel += 1
     state.close()
     model.close()
-    return dict(worst=worst, passes=n_pass, boundaries=n_bnd, selects=n_sel, trace=trace)
+    return dict(worst=worst, rms=rms, passes=n_pass, boundaries=n_bnd, selects=n_sel, trace=trace)
 
 
 TINY_SETS = {
