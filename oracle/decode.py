@@ -25,6 +25,11 @@ cache (parity with the authors' behaviour is unpinned):
                      first L rows double as the new block's first denoising step.
 
 NFE counts forward passes (Sec. 5.1, metrics).
+
+prm["fixed_block"] = B > 0 replaces DepGA-Block by the fixed block size of the comparison methods of
+Sec. 5.1 (vanilla and confidence-threshold decoding with block size 16 / 32 / 64; CAP-Decoding alone
+with block size 32): every block has min(B, remaining) positions and the boundary pass only commits
+the finished block and gives the next block's first denoising step.
 """
 import numpy as np
 
@@ -50,6 +55,7 @@ def decode_full(cfg, W, prompt, n_gen, prm, trace=None, max_passes=None):
     cache = KVCache(cfg)
     nfe, blocks, steps = 0, [], []
     l_min, l_max = prm["l_min"], prm["l_max"]
+    fixed = int(prm.get("fixed_block", 0))
 
     class _Stop(Exception):
         pass
@@ -70,7 +76,10 @@ def decode_full(cfg, W, prompt, n_gen, prm, trace=None, max_passes=None):
         z = run_pass("prefill", 0, P + Lk, P)
         prev_base, prev_z = P, z[P:]
         F = P
-        L, _, _ = block_boundary(np.zeros(min(l_max, N)), np.zeros(min(l_max, N)), prm["lam"], l_min, cold_start=True)
+        if fixed:
+            L = min(fixed, N)
+        else:
+            L, _, _ = block_boundary(np.zeros(min(l_max, N)), np.zeros(min(l_max, N)), prm["lam"], l_min, cold_start=True)
         zb = prev_z[:L]
         while True:
             blocks.append(L)
@@ -97,13 +106,16 @@ def decode_full(cfg, W, prompt, n_gen, prm, trace=None, max_passes=None):
             Wn = min(l_max, R)
             z = run_pass("boundary", F, L + Lk, L)
             look = z[L:]
-            off = F + L - prev_base
-            st = vocab_stats(look[:Wn], mask, z_prev=prev_z[off : off + Wn])
-            Lnext, S, mrg = block_boundary(
-                st["kl"], st["entropy"], prm["lam"], l_min, prm["smooth_radius"], prm["norm_mode"], prm["rule"]
-            )
-            if trace is not None:
-                trace.append(dict(op="boundary", F=F + L, W=Wn, kl=st["kl"], entropy=st["entropy"], L=Lnext, S=S, margin=mrg))
+            if fixed:
+                Lnext = min(fixed, R)
+            else:
+                off = F + L - prev_base
+                st = vocab_stats(look[:Wn], mask, z_prev=prev_z[off : off + Wn])
+                Lnext, S, mrg = block_boundary(
+                    st["kl"], st["entropy"], prm["lam"], l_min, prm["smooth_radius"], prm["norm_mode"], prm["rule"]
+                )
+                if trace is not None:
+                    trace.append(dict(op="boundary", F=F + L, W=Wn, kl=st["kl"], entropy=st["entropy"], L=Lnext, S=S, margin=mrg))
             prev_base, prev_z = F + L, look
             F, L = F + L, Lnext
             zb = look[:L]

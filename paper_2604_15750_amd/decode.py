@@ -23,11 +23,15 @@ from . import api
 
 class Decoder:
     def __init__(self, model, batch, prompt_len, gen_len, prm, device, max_rows=None):
-        """prm: dict(l_min, l_max, lam, smooth_radius, norm_mode, rule, tau_low, tau_high, gamma, mode)."""
+        """prm: dict(l_min, l_max, lam, smooth_radius, norm_mode, rule, tau_low, tau_high, gamma, mode[, fixed_block]).
+
+        fixed_block = B > 0: every block has min(B, remaining) positions instead of the DepGA-Block length (the fixed block
+        sizes of the comparison methods of Sec. 5.1); the boundary pass then compares and retains nothing."""
         self.model, self.cfg, self.prm, self.device = model, model.cfg, dict(prm), device
         self.B, self.P, self.N = batch, prompt_len, gen_len
         self.T = prompt_len + gen_len
         lmax = prm["l_max"]
+        self.fixed = int(prm.get("fixed_block", 0))
         self.look = min(2 * lmax, gen_len)
         steady = batch * (lmax + self.look)
         self.max_rows = max_rows or max(prompt_len + self.look, steady)
@@ -62,12 +66,14 @@ class Decoder:
         """(span_start, rows, commit, kl_first, kl_count, save_first, save_count) of sequence b's next pass."""
         END, lmax = self.T, self.prm["l_max"]
         if self.phase[b] == "prefill":
-            return 0, self.P + self.look, self.P, 0, 0, self.P, self.look
+            return 0, self.P + self.look, self.P, 0, 0, self.P, (0 if self.fixed else self.look)
         F, L = self.F[b], self.L[b]
         if self.phase[b] == "inblock":
             return F, L, 0, 0, 0, 0, 0
         R = END - (F + L)
         Lk, W = min(2 * lmax, R), min(lmax, R)
+        if self.fixed:
+            return F, L + Lk, L, L, 0, L, 0
         return F, L + Lk, L, L, W, L, Lk
 
     def iterate(self, trace=None):
@@ -111,7 +117,13 @@ class Decoder:
             self.nfe[b] += 1
         # block-boundary decisions for the sequences that just finished a block (or the prompt)
         bnd = [i for i, b in enumerate(group) if self.phase[b] != "inblock"]
-        if bnd:
+        if bnd and self.fixed:
+            for i in bnd:
+                b = group[i]
+                self.F[b] += self.L[b]
+                self.L[b] = self.left[b] = min(self.fixed, self.T - self.F[b])
+                self.blocks[b].append(self.L[b])
+        elif bnd:
             starts, lens, cold = [], [], []
             for i in bnd:
                 b = group[i]

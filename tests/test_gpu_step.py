@@ -184,7 +184,7 @@ def _free_run_matches(cfg, W_dev, prompts, N, prm, device, exact):
     for b in range(len(prompts)):
         y = got["tokens"][b]
         assert (y[: prompts.shape[1]] == prompts[b]).all() and not (y == mask).any()
-        assert sum(got["blocks"][b]) == N and got["blocks"][b][0] == min(prm["l_min"], N)
+        assert sum(got["blocks"][b]) == N and got["blocks"][b][0] == min(prm.get("fixed_block") or prm["l_min"], N)
         assert sum(got["steps"][b]) == N and min(got["steps"][b]) >= 1
         if exact:
             ref = o_decode.decode_full(cfg, Wn, prompts[b], N, prm)
@@ -200,6 +200,16 @@ def test_tiny_f32_free_run_equals_oracle(device, name):
     cfg = inputs.TINY
     W = _weights(cfg, 0, device)
     _free_run_matches(cfg, W, inputs.make_prompts(cfg, 1, 64), 64, TINY_SETS[name], device, exact=True)
+
+
+@pytest.mark.parametrize("block,mode", [(16, 2), (32, 1), (24, 0)])
+def test_tiny_f32_fixed_block_rules_equal_oracle(device, block, mode):
+    """The comparison methods of Sec. 5.1 (fixed block size; vanilla, confidence-threshold or CAP selection) decode exactly
+    as the oracle does."""
+    cfg = inputs.TINY
+    W = _weights(cfg, 0, device)
+    prm = dict(inputs.PAPER_PARAMS, l_max=32, fixed_block=block, mode=mode, tau_low=0.05, tau_high=0.2, gamma=-14.0)
+    _free_run_matches(cfg, W, inputs.make_prompts(cfg, 1, 64), 64, prm, device, exact=True)
 
 
 def test_tiny_f32_ragged_batch(device):

@@ -50,3 +50,23 @@ def test_decode_invariants(tiny, name):
     assert (again["tokens"] == y).all() and again["nfe"] == r["nfe"]
     if name != "paper":
         assert max(r["steps"]) > 1 and len(set(r["blocks"][:-1])) > 1, (r["blocks"], r["steps"])  # both decisions are exercised
+
+
+@pytest.mark.parametrize("block,mode", [(16, 2), (32, 1), (24, 0)])
+def test_fixed_block_comparison_rules(tiny, block, mode):
+    """The comparison methods of Sec. 5.1: fixed block size with vanilla (top-1), confidence-threshold or CAP selection.
+    Vanilla decoding takes exactly one token per pass: NFE = N (the paper's NFE 256 at generation length 256)."""
+    cfg, W, prompt = tiny
+    prm = dict(inputs.PAPER_PARAMS, l_max=32, fixed_block=block, mode=mode, tau_low=0.05, tau_high=0.2, gamma=-14.0)
+    N, mask = 64, cfg["mask_id"]
+    trace = []
+    r = decode_full(cfg, W, prompt, N, prm, trace)
+    assert not (r["tokens"] == mask).any() and sum(r["steps"]) == N
+    assert r["blocks"] == [block] * (N // block) + ([N % block] if N % block else [])
+    assert not any(t["op"] == "boundary" for t in trace)  # no DepGA-Block decision is taken
+    if mode == 2:
+        assert r["nfe"] == N and set(r["steps"]) == {1}
+    else:
+        assert r["nfe"] < N and max(r["steps"]) > 1
+        vanilla = decode_full(cfg, W, prompt, N, dict(prm, mode=2))
+        assert r["nfe"] < vanilla["nfe"]
