@@ -4,7 +4,7 @@
 //
 // fp32 kernel (head_dim 32/64/128, row-major cache [pos][n_kv*hd]): one workgroup per (16-query
 // tile, head, sequence); keys are streamed in tiles through LDS with an online softmax in fp32.
-#include "common.h"
+#include "attention_core.h"
 
 namespace {
 
@@ -96,137 +96,21 @@ __global__ __launch_bounds__(256) void attention_kernel(const T* __restrict__ q,
   }
 }
 
-// ---- bf16 kernel on the matrix cores --------------------------------------------------------------
-// The bf16 KV cache is kept per (slot, kv head) in matrix-core fragment tiles (kv_k_index /
-// kv_v_index), so a wavefront fetches a K operand (16 keys x 32 dims) or a V^T operand
-// (16 dims x 32 keys) as 64 consecutive 16-byte pieces.  One workgroup per (16-query tile, head,
-// sequence); its NWV wavefronts take every NWV-th block of 32 keys with their own online-softmax
-// state and are merged through LDS.  The K and V fragments of a wavefront's next block are in flight
-// while the current one is multiplied.  S^T = K Q^T puts 8 keys of one query in each lane (the lane's
-// query is lane%16 in both S^T and O^T), so the probabilities feed the second product straight
-// from registers: the V tiling stores keys in the order the first product emits them.
-// A decode pass has few (query tile, head) pairs, so it runs 8 wavefronts per workgroup to shorten
-// each wavefront's chain of dependent loads; wide passes (prefill, batches) run 4.
+// ---- bf16 kernel on the matrix cores (attention_core.h) ----------------------------------------------
+// One workgroup per (16-query tile, head, sequence).  A decode pass has few (query tile, head) pairs, so it runs 8
+// wavefronts per workgroup to shorten each wavefront's chain of dependent loads; wide passes (prefill, batches) run 4.
 template <int HD, int NWV>
 __global__ __launch_bounds__(NWV * 64) void attention_mfma_kernel(const bf16_t* __restrict__ q, const bf16_t* __restrict__ kcache,
                                                                   const bf16_t* __restrict__ vcache, size_t slot_stride, size_t head_stride,
                                                                   AttnMeta meta, bf16_t* __restrict__ out, bool out_tiled, int n_q, int n_kv) {
-  constexpr int KS = HD / 32, DT = HD / 16;
-  __shared__ float sm[NWV][16], sl[NWV][16];
-  __shared__ float so[NWV][HD][17];
-
+  __shared__ AttnLds<HD, NWV> L;
   const int b = blockIdx.z, head = blockIdx.y;
   const int row0 = meta.row_off[b] + blockIdx.x * 16;
   const int row_end = meta.row_off[b + 1];
   if (row0 >= row_end) return;
-  const int n_keys = meta.n_keys[b];
   const int kvh = head / (n_q / n_kv);
-  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, g = lane >> 4, c = lane & 15;
-  const float scale = rsqrtf((float)HD);
-  const bf16x8 zero8 = {0, 0, 0, 0, 0, 0, 0, 0};
-
-  bf16x8 qf[KS];
-  {
-    const int r = row0 + c;
-#pragma unroll
-    for (int t = 0; t < KS; ++t)
-      qf[t] = r < row_end ? *(const bf16x8*)(q + (size_t)r * n_q * HD + (size_t)head * HD + 32 * t + 8 * g) : zero8;
-  }
-  const bf16x8* kt = (const bf16x8*)(kcache + (size_t)meta.slot[b] * slot_stride + (size_t)kvh * head_stride) + lane;
-  const bf16x8* vt = (const bf16x8*)(vcache + (size_t)meta.slot[b] * slot_stride + (size_t)kvh * head_stride) + lane;
-
-  float m = NEG_BIG, l = 0.f;
-  f32x4 o[DT];
-#pragma unroll
-  for (int dt = 0; dt < DT; ++dt) o[dt] = f32x4{0.f, 0.f, 0.f, 0.f};
-
-  const int nblk = (n_keys + 31) >> 5;
-  bf16x8 kf[2][2 * KS], vf[2][DT];
-  auto load = [&](int buf, int blk) {  // blk may lie beyond the keys: nothing is fetched then
-    const bool ok = blk < nblk;
-#pragma unroll
-    for (int t = 0; t < 2 * KS; ++t) kf[buf][t] = ok ? kt[((size_t)blk * 2 * KS + t) * 64] : zero8;
-#pragma unroll
-    for (int dt = 0; dt < DT; ++dt) vf[buf][dt] = ok ? vt[((size_t)blk * DT + dt) * 64] : zero8;
-  };
-  auto step = [&](int buf, int blk) {
-    f32x4 s0 = {0.f, 0.f, 0.f, 0.f}, s1 = {0.f, 0.f, 0.f, 0.f};
-#pragma unroll
-    for (int t = 0; t < KS; ++t) {
-      s0 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(kf[buf][t], qf[t], s0, 0, 0, 0);
-      s1 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(kf[buf][KS + t], qf[t], s1, 0, 0, 0);
-    }
-    // lane holds, for query c, keys blk*32 + 4g + i (s0) and + 16 (s1)
-    const int key0 = blk * 32 + 4 * g;
-    float sv[8];
-    bool ok[8];
-#pragma unroll
-    for (int i = 0; i < 4; ++i) {
-      ok[i] = key0 + i < n_keys;
-      ok[4 + i] = key0 + 16 + i < n_keys;
-      sv[i] = ok[i] ? s0[i] * scale : NEG_BIG;
-      sv[4 + i] = ok[4 + i] ? s1[i] * scale : NEG_BIG;
-    }
-    float mx = sv[0];
-#pragma unroll
-    for (int i = 1; i < 8; ++i) mx = fmaxf(mx, sv[i]);
-    mx = fmaxf(mx, __shfl_xor(mx, 16, 64));
-    mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
-    const float mn = fmaxf(m, mx);
-    const float corr = __expf(m - mn);
-    float pv[8], ps = 0.f;
-#pragma unroll
-    for (int i = 0; i < 8; ++i) {
-      pv[i] = ok[i] ? __expf(sv[i] - mn) : 0.f;
-      ps += pv[i];
-    }
-    ps += __shfl_xor(ps, 16, 64);
-    ps += __shfl_xor(ps, 32, 64);
-    l = l * corr + ps;
-    m = mn;
-    const bf16x8 pb = {(bf16_t)pv[0], (bf16_t)pv[1], (bf16_t)pv[2], (bf16_t)pv[3], (bf16_t)pv[4], (bf16_t)pv[5], (bf16_t)pv[6], (bf16_t)pv[7]};
-#pragma unroll
-    for (int dt = 0; dt < DT; ++dt) {
-      o[dt] *= corr;
-      o[dt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(vf[buf][dt], pb, o[dt], 0, 0, 0);
-    }
-  };
-  load(0, wave);
-  for (int blk = wave; blk < nblk; blk += 2 * NWV) {
-    load(1, blk + NWV);
-    step(0, blk);
-    load(0, blk + 2 * NWV);
-    if (blk + NWV < nblk) step(1, blk + NWV);
-  }
-  // merge the wavefronts
-  if (g == 0) { sm[wave][c] = m; sl[wave][c] = l; }
-#pragma unroll
-  for (int dt = 0; dt < DT; ++dt)
-#pragma unroll
-    for (int i = 0; i < 4; ++i) so[wave][16 * dt + 4 * g + i][c] = o[dt][i];
-  __syncthreads();
-  constexpr int CH = HD * 16 / (NWV * 64);  // each thread finishes CH consecutive dims of one query
-  const int qi = tid & 15, d0 = (tid >> 4) * CH;
-  float M = sm[0][qi];
-#pragma unroll
-  for (int wv = 1; wv < NWV; ++wv) M = fmaxf(M, sm[wv][qi]);
-  float w[NWV], Lsum = 0.f;
-#pragma unroll
-  for (int wv = 0; wv < NWV; ++wv) { w[wv] = __expf(sm[wv][qi] - M); Lsum += w[wv] * sl[wv][qi]; }
-  const int r = row0 + qi;
-  if (r < row_end) {
-    const int width = n_q * HD;
-#pragma unroll
-    for (int j = 0; j < CH; ++j) {
-      const int d = d0 + j;
-      float acc = 0.f;
-#pragma unroll
-      for (int wv = 0; wv < NWV; ++wv) acc += w[wv] * so[wv][d][qi];
-      const int col = head * HD + d;
-      const size_t idx = out_tiled ? tile_index(r, col, width) : (size_t)r * width + col;
-      out[idx] = (bf16_t)(acc / Lsum);
-    }
-  }
+  const size_t region = (size_t)meta.slot[b] * slot_stride + (size_t)kvh * head_stride;
+  attention_tile<HD, NWV>(q, kcache + region, vcache + region, row0, row_end, meta.n_keys[b], head, n_q, out, out_tiled, L);
 }
 
 // K [T, n_kv, hd] and V row-major -> the tiled cache layout of one slot (test helper for dlm_attention)

@@ -6,34 +6,6 @@
 
 __device__ inline bf16x4 to_bf16x4(f32x4 v) { return bf16x4{(bf16_t)v[0], (bf16_t)v[1], (bf16_t)v[2], (bf16_t)v[3]}; }
 
-// Stores of an epilogue.  COH = false: ordinary stores (the consumer is a later kernel).  COH = true: written through to
-// device scope, for consumers in the same kernel that may run on another XCD (each XCD has an L2 of its own).
-template <bool COH>
-__device__ inline void st_bf16x4(bf16_t* p, bf16x4 v) {
-  if (COH) __hip_atomic_store((uint64_t*)p, __builtin_bit_cast(uint64_t, v), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-  else *(bf16x4*)p = v;
-}
-template <bool COH>
-__device__ inline void st_bf16(bf16_t* p, bf16_t v) {
-  if (COH) __hip_atomic_store((unsigned short*)p, __builtin_bit_cast(unsigned short, v), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-  else *p = v;
-}
-template <bool COH>
-__device__ inline void st_f32(float* p, float v) {
-  if (COH) __hip_atomic_store(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-  else *p = v;
-}
-template <bool COH>
-__device__ inline void st_f32x4(float* p, f32x4 v) {
-  if (COH) {
-    typedef float f32x2 __attribute__((ext_vector_type(2)));
-    __hip_atomic_store((uint64_t*)p, __builtin_bit_cast(uint64_t, f32x2{v[0], v[1]}), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-    __hip_atomic_store((uint64_t*)p + 1, __builtin_bit_cast(uint64_t, f32x2{v[2], v[3]}), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-  } else {
-    *(f32x4*)p = v;
-  }
-}
-
 // 1/rms of rows [m_lo, m_lo + rows) from the producer's partial sums of squares into s_rinv, by the whole workgroup of NT
 // threads: sixteen lanes per row, each adding every sixteenth chunk in ascending order, then a fixed butterfly
 // (deterministic).  A lane's sixteen loads of a block of 256 chunks are issued together and waited for once: one trip to
@@ -64,7 +36,6 @@ __device__ inline void block_rinv(const RowScale& rs, int m_lo, int rows, float*
 
 // Rotary pair group: a = packed columns nc+4gp .. +3 of a 16-column tile starting at packed column nc,
 // b = the same + 8; they are dims i .. i+3 and i+half .. i+half+3 of one head (weights packed with PERM_ROTARY).
-template <bool COH>
 __device__ inline void finish_qkv(const GemmEpi& e, int m, int nc, int gp, f32x4 a, f32x4 b) {
   const int hd = e.hd, half = hd >> 1;
   const int head = nc / hd, i = 8 * ((nc % hd) >> 4) + 4 * gp;
@@ -77,8 +48,8 @@ __device__ inline void finish_qkv(const GemmEpi& e, int m, int nc, int gp, f32x4
   const bf16x4 ab = to_bf16x4(a), bb = to_bf16x4(b);
   if (head < e.n_q) {
     bf16_t* dst = e.q + (size_t)m * e.n_q * hd + (size_t)head * hd;
-    st_bf16x4<COH>(dst + i, ab);
-    st_bf16x4<COH>(dst + i + half, bb);
+    *(bf16x4*)(dst + i) = ab;
+    *(bf16x4*)(dst + i + half) = bb;
     return;
   }
   const bool is_k = head < e.n_q + e.n_kv;
@@ -86,34 +57,32 @@ __device__ inline void finish_qkv(const GemmEpi& e, int m, int nc, int gp, f32x4
   const int pos = e.row_pos[m];
   bf16_t* dst = (is_k ? e.kcache : e.vcache) + (size_t)e.row_slot[m] * e.slot_stride + (size_t)kvh * e.head_stride;
   if (is_k) {  // four consecutive dims share a lane slot of the K tiling
-    st_bf16x4<COH>(dst + kv_k_index(pos, i, hd), ab);
-    st_bf16x4<COH>(dst + kv_k_index(pos, i + half, hd), bb);
+    *(bf16x4*)(dst + kv_k_index(pos, i, hd)) = ab;
+    *(bf16x4*)(dst + kv_k_index(pos, i + half, hd)) = bb;
   } else {
 #pragma unroll
     for (int j = 0; j < 4; ++j) {
-      st_bf16<COH>(dst + kv_v_index(pos, i + j, hd), ab[j]);
-      st_bf16<COH>(dst + kv_v_index(pos, i + half + j, hd), bb[j]);
+      dst[kv_v_index(pos, i + j, hd)] = ab[j];
+      dst[kv_v_index(pos, i + half + j, hd)] = bb[j];
     }
   }
 }
 
 // gate = packed columns nc+4gp .. +3, up = the same + 8: output columns 8 (nc/16) + 4gp .. +3 (weights packed with PERM_GATED)
-template <bool COH>
 __device__ inline void finish_swiglu(const GemmEpi& e, int m, int nc, int gp, f32x4 g, f32x4 u) {
   bf16x4 o;
 #pragma unroll
   for (int t = 0; t < 4; ++t) o[t] = (bf16_t)(g[t] / (1.f + __expf(-g[t])) * u[t]);
-  st_bf16x4<COH>(e.act + tile_index(m, 8 * (nc >> 4) + 4 * gp, e.ffn), o);
+  *(bf16x4*)(e.act + tile_index(m, 8 * (nc >> 4) + 4 * gp, e.ffn)) = o;
 }
 
 // residual add and next norm's x for columns n .. n+3 of row m; returns the four columns' share of sum h^2
-template <bool COH>
 __device__ inline float finish_resid(const GemmEpi& e, int m, int n, int N, f32x4 y) {
   const size_t o = (size_t)m * N + n;
   const f32x4 v = *(const f32x4*)(e.h + o) + y;
-  st_f32x4<COH>(e.h + o, v);
+  *(f32x4*)(e.h + o) = v;
   const f32x4 g = *(const f32x4*)(e.gain + n);
-  st_bf16x4<COH>(e.x + tile_index(m, n, N), to_bf16x4(v * g));
+  *(bf16x4*)(e.x + tile_index(m, n, N)) = to_bf16x4(v * g);
   return v[0] * v[0] + v[1] * v[1] + v[2] * v[2] + v[3] * v[3];
 }
 
@@ -126,20 +95,20 @@ __device__ inline void finish_sum(const GemmEpi& e, int m, int n, int N, f32x4 v
 // One 16 x 16 tile starting at packed column nc: v = this lane's four finished columns of row m, rinv = 1/rms of the input row.
 // Called by all 64 lanes of a wavefront together (it exchanges values between lanes).  EPI_RESID returns the tile's share of
 // sum h^2 of row m (in every lane of the row), the others 0.
-template <int EPI, bool COH = false>
+template <int EPI>
 __device__ inline float finish_frag(const GemmEpi& e, int M, int N, int m, int nc, int g, f32x4 v, float rinv) {
   if (EPI == EPI_QKV || EPI == EPI_SWIGLU) {
     f32x4 b;  // the partner group, columns + 8, sits 32 lanes up
 #pragma unroll
     for (int i = 0; i < 4; ++i) b[i] = __shfl_xor(v[i], 32, 64);
     if (g < 2 && m < M) {
-      if (EPI == EPI_QKV) finish_qkv<COH>(e, m, nc, g, v * rinv, b * rinv);
-      else finish_swiglu<COH>(e, m, nc, g, v * rinv, b * rinv);
+      if (EPI == EPI_QKV) finish_qkv(e, m, nc, g, v * rinv, b * rinv);
+      else finish_swiglu(e, m, nc, g, v * rinv, b * rinv);
     }
     return 0.f;
   }
   if (EPI == EPI_RESID) {
-    float ss = m < M ? finish_resid<COH>(e, m, nc + 4 * g, N, v) : 0.f;
+    float ss = m < M ? finish_resid(e, m, nc + 4 * g, N, v) : 0.f;
     ss += __shfl_xor(ss, 16, 64);
     ss += __shfl_xor(ss, 32, 64);
     return ss;

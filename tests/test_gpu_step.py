@@ -172,6 +172,24 @@ def test_mid_bf16_gqa_replay(device, name):
     print(name, "worst relative logit error", r["worst"], "passes", r["passes"])
 
 
+# many heads (48 query heads over 12 kv heads of 128 dims: 9216 QKV columns, so the QKV weights take the interleaved-pair
+# packing of the wide matrices) on a narrow model
+WIDE_HEADS = inputs.model_config(2, 256, 48, 12, 128, 512, 2048, "bf16")
+
+
+@pytest.mark.parametrize("l_max", [12, 24])
+def test_wide_heads_bf16_gqa_replay(device, l_max):
+    """Grouped-query attention with groups of four, blocks of one and of two query tiles, QKV weights in the wide packing;
+    every pass against the oracle."""
+    W = _weights(WIDE_HEADS, 7, device)
+    prompt = inputs.make_prompts(WIDE_HEADS, 1, 70, seed=7)[0]
+    prm = dict(TINY_SETS["scaled"], l_max=l_max, l_min=4)
+    r = replay(WIDE_HEADS, W, prompt, 60, prm, device, logit_tol=2e-2)
+    kinds = [t["kind"] for t in r["trace"] if t["op"] == "pass"]
+    assert kinds.count("inblock") >= 5 and kinds.count("boundary") >= 2
+    print("worst relative logit error", r["worst"], "passes", r["passes"])
+
+
 def _free_run_matches(cfg, W_dev, prompts, N, prm, device, exact):
     prm = _f32(prm)
     Wn = inputs.weights_to_numpy(W_dev)
