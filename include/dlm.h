@@ -91,6 +91,10 @@ int dlm_state_kv_len(const dlm_state* s, int slot);
  * Each row attends (bidirectionally) to the slot's cached prefix [0, kv_len) and to all rows of
  * its own span; span_start[b] must equal the slot's kv_len.  After the pass the first
  * commit_len[b] rows join the cache (Sec. 5.2: prefix KV cached per decoded block).
+ * suffix_len[b] > 0 (dual cache, Sec. 5.3): the rows also attend to the suffix_len[b] positions right
+ * after the span, with the keys and values an earlier pass over those positions left in the cache
+ * (every pass writes the K and V of all its rows at their positions; only the committed ones count
+ * as prefix).  They are not recomputed.
  *
  * Statistics (Sec. 4.2, 4.3; natural log; the mask token's probability is forced to 0 first;
  * argmax ties go to the lowest token id) are written for every row:
@@ -103,7 +107,7 @@ int dlm_state_kv_len(const dlm_state* s, int slot);
  *
  * Errors (nothing is launched): DLM_EINVAL (null pointer, n_seqs < 1, offsets not increasing, slot
  * out of range or repeated, span_start != kv_len, commit/kl/save ranges outside the span, a kl row
- * with no retained p^prev), DLM_ECAPACITY (rows > max_rows, span beyond max_seq_len, save_count >
+ * with no retained p^prev, a suffix beyond the positions an earlier pass has covered), DLM_ECAPACITY (rows > max_rows, span beyond max_seq_len, save_count >
  * max_lookahead, n_seqs > max_seqs). */
 typedef struct {
   int32_t n_seqs;
@@ -116,6 +120,7 @@ typedef struct {
   const int32_t* save_first;   /* host [n_seqs] (NULL with save_count: nothing retained)           */
   const int32_t* save_count;   /* host [n_seqs]                                                    */
   const int32_t* tok_start;    /* host [n_seqs] index into `tokens` of the span's first row        */
+  const int32_t* suffix_len;   /* host [n_seqs] (NULL: 0) cached positions after the span to attend */
   const int32_t* tokens;       /* DEVICE token ids (mask_id on undecoded slots)                    */
   void* logits;                /* DEVICE out [rows, vocab], model dtype                            */
   float* max_logit;            /* DEVICE out [rows]                                                */

@@ -26,6 +26,10 @@ cache (parity with the authors' behaviour is unpinned):
 
 NFE counts forward passes (Sec. 5.1, metrics).
 
+prm["dual_cache"] = 1: in-block passes also attend to the look-ahead positions after the block with the
+keys and values the last prefill / boundary pass computed for them (the suffix half of a dual cache,
+Sec. 5.3: DepCap is compatible with such caches), instead of seeing nothing after the block.
+
 prm["fixed_block"] = B > 0 replaces DepGA-Block by the fixed block size of the comparison methods of
 Sec. 5.1 (vanilla and confidence-threshold decoding with block size 16 / 32 / 64; CAP-Decoding alone
 with block size 32): every block has min(B, remaining) positions and the boundary pass only commits
@@ -56,19 +60,24 @@ def decode_full(cfg, W, prompt, n_gen, prm, trace=None, max_passes=None):
     nfe, blocks, steps = 0, [], []
     l_min, l_max = prm["l_min"], prm["l_max"]
     fixed = int(prm.get("fixed_block", 0))
+    dual = bool(prm.get("dual_cache", 0))
+    look_end = 0  # end of the positions the last prefill / boundary pass covered
 
     class _Stop(Exception):
         pass
 
     def run_pass(kind, start, rows, commit):
-        nonlocal nfe
+        nonlocal nfe, look_end
         if max_passes is not None and nfe >= max_passes:
             raise _Stop
         toks = y[start : start + rows].copy()
-        z = forward_span(cfg, W, cache, toks, start, commit)
+        suffix = look_end - (start + rows) if (dual and kind == "inblock") else 0
+        z = forward_span(cfg, W, cache, toks, start, commit, suffix)
+        if kind != "inblock":
+            look_end = start + rows
         nfe += 1
         if trace is not None:
-            trace.append(dict(op="pass", kind=kind, span_start=start, tokens=toks, commit_len=commit, logits=z))
+            trace.append(dict(op="pass", kind=kind, span_start=start, tokens=toks, commit_len=commit, suffix_len=suffix, logits=z))
         return z
 
     try:

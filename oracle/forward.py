@@ -83,29 +83,43 @@ def swiglu(gate, up):
 
 
 class KVCache:
-    """Post-RoPE keys and values of committed positions, per layer: [kv_len, Hkv, hd]."""
+    """Post-RoPE keys and values of committed positions, per layer: [kv_len, Hkv, hd].
+
+    tail_k / tail_v keep what the last pass computed for the rows it did NOT commit (positions from
+    tail_start on): the "suffix" entries of a dual cache (Sec. 5.3, cache compatibility), visible to a
+    later pass only when it asks for them."""
 
     def __init__(self, cfg):
         shape = (0, cfg["n_kv_heads"], cfg["head_dim"])
         self.k = [np.zeros(shape) for _ in range(cfg["n_layers"])]
         self.v = [np.zeros(shape) for _ in range(cfg["n_layers"])]
+        self.tail_start = 0
+        self.tail_k = [np.zeros(shape) for _ in range(cfg["n_layers"])]
+        self.tail_v = [np.zeros(shape) for _ in range(cfg["n_layers"])]
 
     @property
     def kv_len(self):
         return self.k[0].shape[0] if self.k else 0
 
 
-def forward_span(cfg, W, cache, tokens, span_start, commit_len):
+def forward_span(cfg, W, cache, tokens, span_start, commit_len, suffix_len=0):
     """One forward pass over span rows [span_start, span_start+len(tokens)).
 
     The span attends to the cached prefix [0, kv_len) (kv_len must equal
-    span_start) and to all of its own rows.  Afterwards K (post-RoPE) and V of
-    the first commit_len rows are appended to the cache.  Returns logits [rows, V].
+    span_start), to all of its own rows and, if suffix_len > 0, to the suffix_len
+    positions right after the span with the keys and values an EARLIER pass computed
+    for them (they are not recomputed: the dual-cache approximation).  Afterwards K
+    (post-RoPE) and V of the first commit_len rows are appended to the cache and
+    those of the other rows replace the tail entries from their positions on
+    (tail entries beyond the span's end are kept).  Returns logits [rows, V].
     """
     tokens = np.asarray(tokens, dtype=np.int64)
     A = tokens.shape[0]
     assert cache.kv_len == span_start
     assert 0 <= commit_len <= A
+    end = span_start + A
+    s0 = end - cache.tail_start  # index of the first suffix position in the tail
+    assert suffix_len == 0 or (s0 >= 0 and s0 + suffix_len <= cache.tail_k[0].shape[0]), "suffix positions have no cached keys"
     Hq, Hkv, hd = cfg["n_q_heads"], cfg["n_kv_heads"], cfg["head_dim"]
     eps, theta = cfg["rms_eps"], cfg["rope_theta"]
     pos = span_start + np.arange(A)
@@ -119,8 +133,8 @@ def forward_span(cfg, W, cache, tokens, span_start, commit_len):
         v = qkv[:, (Hq + Hkv) * hd :].reshape(A, Hkv, hd)
         q = rope(q, pos, theta)
         k = rope(k, pos, theta)
-        keys = np.concatenate([cache.k[l], k], axis=0)
-        vals = np.concatenate([cache.v[l], v], axis=0)
+        keys = np.concatenate([cache.k[l], k, cache.tail_k[l][s0 : s0 + suffix_len] if suffix_len else k[:0]], axis=0)
+        vals = np.concatenate([cache.v[l], v, cache.tail_v[l][s0 : s0 + suffix_len] if suffix_len else v[:0]], axis=0)
         o = attention(q, keys, vals).reshape(A, Hq * hd)
         h = h + matmul_nt(o, W["wo"][l])
         x = rmsnorm(h, W["norm2"][l], eps)
@@ -129,5 +143,13 @@ def forward_span(cfg, W, cache, tokens, span_start, commit_len):
         h = h + matmul_nt(swiglu(gu[:, :ffn], gu[:, ffn:]), W["w_down"][l])
         cache.k[l] = np.concatenate([cache.k[l], k[:commit_len]], axis=0)
         cache.v[l] = np.concatenate([cache.v[l], v[:commit_len]], axis=0)
+        # the tail now starts at the first uncommitted row: this pass's values up to the span's end, older ones beyond it
+        keep = max(s0, 0)
+        old_k, old_v = cache.tail_k[l][keep:], cache.tail_v[l][keep:]
+        if s0 < 0:  # (a gap between the span's end and the old tail: nothing beyond the span survives)
+            old_k, old_v = k[:0], v[:0]
+        cache.tail_k[l] = np.concatenate([k[commit_len:], old_k], axis=0)
+        cache.tail_v[l] = np.concatenate([v[commit_len:], old_v], axis=0)
+    cache.tail_start = span_start + commit_len
     x = rmsnorm(h, W["final_norm"], eps)
     return matmul_nt(x, W["lm_head"])

@@ -41,7 +41,7 @@ _I32P = C.POINTER(C.c_int32)
 
 class dlm_step_desc(C.Structure):
     _fields_ = [("n_seqs", C.c_int32)] + [(n, _I32P) for n in
-                ("slot", "row_offsets", "span_start", "commit_len", "kl_first", "kl_count", "save_first", "save_count", "tok_start")] + \
+                ("slot", "row_offsets", "span_start", "commit_len", "kl_first", "kl_count", "save_first", "save_count", "tok_start", "suffix_len")] + \
                [(n, C.c_void_p) for n in ("tokens", "logits", "max_logit", "lse", "entropy", "kl", "conf", "argmax")]
 
 
@@ -194,9 +194,9 @@ class StepOutputs:
 
 
 def dlm_step(state, tokens, out, row_offsets, span_start, commit_len, tok_start, slot=None, kl_first=None, kl_count=None,
-             save_first=None, save_count=None):
+             save_first=None, save_count=None, suffix_len=None):
     """tokens: device int32 tensor; out: StepOutputs; the rest: host int lists (see include/dlm.h)."""
-    keep = [_ints(v) for v in (slot, row_offsets, span_start, commit_len, kl_first, kl_count, save_first, save_count, tok_start)]
+    keep = [_ints(v) for v in (slot, row_offsets, span_start, commit_len, kl_first, kl_count, save_first, save_count, tok_start, suffix_len)]
     d = dlm_step_desc(len(span_start), *keep, tokens.data_ptr(), out.logits.data_ptr(), out.max_logit.data_ptr(), out.lse.data_ptr(),
                       out.entropy.data_ptr(), out.kl.data_ptr(), out.conf.data_ptr(), out.argmax.data_ptr())
     _check(lib().dlm_step(state.handle, C.byref(d), _stream()))

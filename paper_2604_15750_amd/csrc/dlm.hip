@@ -74,7 +74,7 @@ struct dlm_state {
   DevBuf kcache, vcache, prev_logits, prev_lse;
   DevBuf h, x, x2, act, q, part, stats_ws, ssq, counters;
   DevBuf row_seq, row_pos, row_tok, row_slot, rope_cos, rope_sin, prev_row, save_row;
-  std::vector<int> kv_len, prev_cur, prev_base, prev_count;
+  std::vector<int> kv_len, covered_end, prev_cur, prev_base, prev_count;  // covered_end: positions [0, covered_end) hold K and V of some pass
   size_t part_elems;
   Profile prof;
 };
@@ -236,7 +236,7 @@ extern "C" int dlm_state_create(const dlm_model* m, int max_seqs, int max_seq_le
     if (e != hipSuccess) rc = dlm_fail(DLM_EHIP, "dlm_state_create: hipMemset: %s", hipGetErrorString(e));
   }
   if (rc != DLM_OK) { delete s; return rc; }
-  s->kv_len.assign(max_seqs, 0); s->prev_cur.assign(max_seqs, 0); s->prev_base.assign(max_seqs, 0); s->prev_count.assign(max_seqs, 0);
+  s->kv_len.assign(max_seqs, 0); s->covered_end.assign(max_seqs, 0); s->prev_cur.assign(max_seqs, 0); s->prev_base.assign(max_seqs, 0); s->prev_count.assign(max_seqs, 0);
   *out = s;
   return DLM_OK;
 }
@@ -251,7 +251,7 @@ extern "C" void dlm_state_destroy(dlm_state* s) {
 extern "C" int dlm_state_reset(dlm_state* s, int slot) {
   REQUIRE(s, DLM_EINVAL, "dlm_state_reset: null state");
   REQUIRE(slot >= 0 && slot < s->max_seqs, DLM_EINVAL, "dlm_state_reset: slot %d out of range", slot);
-  s->kv_len[slot] = 0; s->prev_count[slot] = 0; s->prev_base[slot] = 0;
+  s->kv_len[slot] = 0; s->covered_end[slot] = 0; s->prev_count[slot] = 0; s->prev_base[slot] = 0;
   return DLM_OK;
 }
 
@@ -466,7 +466,11 @@ extern "C" int dlm_step(dlm_state* s, const dlm_step_desc* d, void* stream) {
     meta.span_start[b] = d->span_start[b];
     meta.slot[b] = am.slot[b] = slot;
     meta.tok_start[b] = d->tok_start[b];
-    am.n_keys[b] = d->span_start[b] + nr;
+    const int suffix = d->suffix_len ? d->suffix_len[b] : 0;
+    REQUIRE(suffix >= 0 && d->span_start[b] + nr + suffix <= (suffix ? s->covered_end[slot] : s->max_seq_len), DLM_EINVAL,
+            "dlm_step: suffix of %d positions after the span of sequence %d reaches beyond the %d positions an earlier pass has covered", suffix, b,
+            s->covered_end[slot]);
+    am.n_keys[b] = d->span_start[b] + nr + suffix;
     if (nr > max_seq_rows) max_seq_rows = nr;
     const int kc = d->kl_count ? d->kl_count[b] : 0, kf = d->kl_count ? d->kl_first[b] : 0;
     const int sc = d->save_count ? d->save_count[b] : 0, sf = d->save_count ? d->save_first[b] : 0;
@@ -491,6 +495,7 @@ extern "C" int dlm_step(dlm_state* s, const dlm_step_desc* d, void* stream) {
   for (int b = 0; b < n; ++b) {  // host bookkeeping: commit the prefix, flip the retained-logit buffers
     const int slot = meta.slot[b];
     s->kv_len[slot] += d->commit_len[b];
+    if (am.row_off[b + 1] - am.row_off[b] + d->span_start[b] > s->covered_end[slot]) s->covered_end[slot] = am.row_off[b + 1] - am.row_off[b] + d->span_start[b];
     if (sm.save_count[b] > 0) {
       s->prev_cur[slot] ^= 1;
       s->prev_base[slot] = d->span_start[b] + sm.save_first[b];

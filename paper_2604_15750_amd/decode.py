@@ -26,12 +26,15 @@ class Decoder:
         """prm: dict(l_min, l_max, lam, smooth_radius, norm_mode, rule, tau_low, tau_high, gamma, mode[, fixed_block]).
 
         fixed_block = B > 0: every block has min(B, remaining) positions instead of the DepGA-Block length (the fixed block
-        sizes of the comparison methods of Sec. 5.1); the boundary pass then compares and retains nothing."""
+        sizes of the comparison methods of Sec. 5.1); the boundary pass then compares and retains nothing.
+        dual_cache = 1: in-block passes also attend to the look-ahead positions after the block, with the keys and values the
+        last prefill / boundary pass left in the cache for them (the suffix half of a dual cache, Sec. 5.3)."""
         self.model, self.cfg, self.prm, self.device = model, model.cfg, dict(prm), device
         self.B, self.P, self.N = batch, prompt_len, gen_len
         self.T = prompt_len + gen_len
         lmax = prm["l_max"]
         self.fixed = int(prm.get("fixed_block", 0))
+        self.dual = bool(prm.get("dual_cache", 0))
         self.look = min(2 * lmax, gen_len)
         steady = batch * (lmax + self.look)
         self.max_rows = max_rows or max(prompt_len + self.look, steady)
@@ -55,6 +58,7 @@ class Decoder:
         self.L = [0] * self.B
         self.left = [0] * self.B
         self.phase = ["prefill"] * self.B
+        self.look_end = [0] * self.B  # end of the positions the sequence's last prefill / boundary pass covered
         self.nfe, self.blocks, self.steps = [0] * self.B, [[] for _ in range(self.B)], [[] for _ in range(self.B)]
         self.launches = 0
         self.rows_log = []  # rows of every dlm_step launch
@@ -104,8 +108,12 @@ class Decoder:
         if self.time_steps:
             ev = (torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True))
             ev[0].record()
+        suffix = [self.look_end[b] - (plans[b][0] + plans[b][1]) if (self.dual and self.phase[b] == "inblock") else 0 for b in group]
         api.dlm_step(self.state, self.tokens, out, row_off, col(0), col(2), [b * self.T + plans[b][0] for b in group], slot=group,
-                     kl_first=col(3), kl_count=col(4), save_first=col(5), save_count=col(6))
+                     kl_first=col(3), kl_count=col(4), save_first=col(5), save_count=col(6), suffix_len=suffix)
+        for b in group:
+            if self.phase[b] != "inblock":
+                self.look_end[b] = plans[b][0] + plans[b][1]
         if self.time_steps:
             ev[1].record()
             self.step_events.append((row_off[-1], ev[0], ev[1]))

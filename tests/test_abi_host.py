@@ -29,7 +29,7 @@ def test_every_declared_symbol_is_exported():
 def test_struct_layouts_match_header():
     assert C.sizeof(api.dlm_config) == 11 * 4
     assert C.sizeof(api.dlm_weights) == 9 * 8
-    assert C.sizeof(api.dlm_step_desc) == 8 + 17 * 8
+    assert C.sizeof(api.dlm_step_desc) == 8 + 18 * 8
     assert C.sizeof(api.dlm_boundary_params) == 20 and C.sizeof(api.dlm_select_params) == 16
 
 

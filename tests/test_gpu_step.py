@@ -73,7 +73,7 @@ def replay(cfg, W_dev, prompt, N, prm, device, logit_tol, max_passes=None, stats
                 svf, svc = commit, rows - commit
             assert state.kv_len(0) == s0
             api.dlm_step(state, tokens, out, [0, rows], [s0], [commit], [s0], kl_first=[klf], kl_count=[klc], save_first=[svf],
-                         save_count=[svc])
+                         save_count=[svc], suffix_len=[rec.get("suffix_len", 0)])
             torch.cuda.synchronize()
             assert state.kv_len(0) == s0 + commit
             z = o_fwd.widen(inputs.tensor_to_numpy(out.logits[:rows]))
@@ -145,6 +145,7 @@ def replay(cfg, W_dev, prompt, N, prm, device, logit_tol, max_passes=None, stats
 
 TINY_SETS = {
     "paper": dict(inputs.PAPER_PARAMS, l_max=32),
+    "dual_cache": dict(inputs.PAPER_PARAMS, l_max=24, lam=0.9, tau_low=0.05, tau_high=0.3, gamma=-14.0, dual_cache=1),
     "scaled": dict(inputs.PAPER_PARAMS, l_max=32, lam=0.9, tau_low=0.05, tau_high=0.3, gamma=-14.0),
     "cumulative": dict(inputs.PAPER_PARAMS, l_max=16, lam=0.98, rule=1, tau_low=0.1, tau_high=0.5, gamma=-12.0),
 }
@@ -163,7 +164,7 @@ def test_tiny_f32_replay(device, name):
 MID = inputs.model_config(2, 512, 4, 2, 128, 1536, 4096, "bf16")
 
 
-@pytest.mark.parametrize("name", ["paper", "scaled"])
+@pytest.mark.parametrize("name", ["paper", "scaled", "dual_cache"])
 def test_mid_bf16_gqa_replay(device, name):
     W = _weights(MID, 5, device)
     prompt = inputs.make_prompts(MID, 1, 100, seed=5)[0]
@@ -273,6 +274,9 @@ def test_step_errors_leave_state_untouched(device):
     with pytest.raises(api.DlmError) as e:  # span beyond max_seq_len
         api.dlm_step(state, tokens, out, row_offsets=[0, 48], span_start=[48], commit_len=[0], tok_start=[0])
     assert e.value.code == -3
+    with pytest.raises(api.DlmError) as e:  # a suffix no pass has covered (positions [0, 52) have been)
+        api.dlm_step(state, tokens, out, row_offsets=[0, 4], span_start=[48], commit_len=[0], tok_start=[0], suffix_len=[1])
+    assert e.value.code == -1
     state.reset(0)
     assert state.kv_len(0) == 0
     torch.cuda.synchronize()

@@ -17,6 +17,7 @@ PARAM_SETS = {
     "scaled": dict(inputs.PAPER_PARAMS, l_max=32, lam=0.9, tau_low=0.05, tau_high=0.3, gamma=-14.0),
     "cumulative": dict(inputs.PAPER_PARAMS, l_max=16, lam=0.98, rule=1, tau_low=0.1, tau_high=0.5, gamma=-12.0),
     "threshold": dict(inputs.PAPER_PARAMS, l_max=32, lam=0.8, tau_high=0.2, mode=1),
+    "dual_cache": dict(inputs.PAPER_PARAMS, l_max=24, lam=0.9, tau_low=0.05, tau_high=0.3, gamma=-14.0, dual_cache=1),
 }
 
 

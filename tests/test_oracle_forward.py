@@ -171,3 +171,30 @@ def test_forward_matches_library_composition():
         h = h + F.linear(F.silu(g) * u, T["w_down"][l])
     ref = F.linear(F.rms_norm(h, (d,), T["final_norm"], eps=1e-5), T["lm_head"]).numpy()
     np.testing.assert_allclose(z, ref, rtol=1e-9, atol=1e-11)
+
+
+def test_suffix_entries_replay_invariant():
+    """Dual-cache suffix: a pass over [0, s+a+u) that commits [0, s) leaves the keys and values of its other rows as tail
+    entries.  Re-running only the rows [s, s+a) with the same tokens, against the cache and the u suffix entries, sees
+    exactly the keys the long pass saw, so it reproduces the long pass's logits for those rows; without the suffix it
+    does not; and the suffix is not recomputed (changing the block's tokens leaves the tail beyond the block as it was)."""
+    cfg = inputs.model_config(2, 64, 4, 2, 32, 96, 50, "f32")
+    W = inputs.weights_to_numpy(inputs.make_weights(cfg, seed=3))
+    rng = np.random.default_rng(5)
+    s, a, u = 7, 5, 6
+    toks = rng.integers(0, 49, size=s + a + u)
+    cache = fw.KVCache(cfg)
+    z_long = fw.forward_span(cfg, W, cache, toks, 0, s)
+    tail_before = [t.copy() for t in cache.tail_k]
+    z_with = fw.forward_span(cfg, W, cache, toks[s : s + a], s, 0, suffix_len=u)
+    assert np.allclose(z_with, z_long[s : s + a], rtol=0, atol=1e-9)
+    # same block tokens: the block's entries are recomputed to the same values, the ones beyond it are kept as they were
+    assert all(np.allclose(t0, t1, rtol=0, atol=1e-9) and np.array_equal(t0[a:], t1[a:]) for t0, t1 in zip(tail_before, cache.tail_k))
+    z_without = fw.forward_span(cfg, W, cache, toks[s : s + a], s, 0)
+    assert np.abs(z_without - z_long[s : s + a]).max() > 1e-3
+    t2 = toks[s : s + a].copy()
+    t2[1] = (t2[1] + 1) % 49
+    fw.forward_span(cfg, W, cache, t2, s, 0, suffix_len=u)
+    assert all(np.array_equal(t0[a:], t1[a:]) for t0, t1 in zip(tail_before, cache.tail_k))  # entries beyond the block are kept
+    with pytest.raises(AssertionError):
+        fw.forward_span(cfg, W, cache, toks[s : s + a], s, 0, suffix_len=u + 1)  # no cached keys there
