@@ -128,7 +128,8 @@ void launch_pack_weight(const bf16_t* w, bf16_t* out, int N, int K, int perm, in
 void launch_pack_act(const bf16_t* x, bf16_t* out, int M, int K, hipStream_t st);  // row-major -> fragment tiles (rows padded to 16 with zeros)
 int gemm_bf16_splits(int M, int N, int K);         // partial tiles [splits][M][N] the launch of this shape needs in GemmEpi::part (1: none)
 int gemm_bf16_ssq_chunks(int M, int N);            // chunks per row of the sums of squares an EPI_RESID launch of this shape writes
-int gemm_tiled_counters(int max_rows, int max_n);  // ticket counters a state needs (zero-initialised, self-resetting)
+int gemm_bf16_counters(int max_rows, int max_n);   // ticket counters a state needs in GemmEpi::counters (zero-initialised, self-resetting)
+int gemm_tiled_counters(int max_rows, int max_n);
 int gemm_tiled_splits(int M, int N, int K);
 int gemm_tiled_ssq_chunks(int M, int N);
 void gemm_tiled_set_target(int wgs);               // tuning: workgroups the K split aims at
@@ -143,7 +144,7 @@ enum { EPI_DIRECT = 0, EPI_QKV = 1, EPI_SWIGLU = 2, EPI_RESID = 3, EPI_SUM = 4 }
 struct GemmEpi {
   int kind;
   float* part;        // [gemm_bf16_splits][M][N] fp32 partial tiles of the tiled kernel when it splits K
-  int* counters;      // gemm_tiled_counters tickets, one per (column group, row block)
+  int* counters;      // gemm_bf16_counters tickets, one per (column group, row block) of a launch that splits K
   RowScale rs;        // 1/rms of the GEMM's input rows (QKV, SWIGLU, DIRECT, SUM; ssq may be null)
   // EPI_QKV (weights packed with PERM_ROTARY)
   const int32_t *row_pos, *row_slot;
@@ -168,6 +169,13 @@ void launch_gemm_bf16(const bf16_t* xt, const bf16_t* wt, int M, int N, int K, c
 #define GEMM_SKINNY_MAX_ROWS 64
 void launch_gemm_skinny(const bf16_t* xt, const bf16_t* wt, int pr, int M, int N, int K, const GemmEpi& e, hipStream_t st);  // M <= GEMM_SKINNY_MAX_ROWS
 void launch_gemm_tiled(const bf16_t* xt, const bf16_t* wt, int M, int N, int K, const GemmEpi& e, hipStream_t st);
+#define GEMM_MID_MAX_ROWS 160  // 65 .. this many rows: the mid kernel (all rows in one workgroup, wavefronts split K)
+#define GEMM_MID_MAX_ROWS_NARROW 256  // ... for matrices of at most 8192 columns
+int gemm_mid_splits(int M, int N, int K);
+int gemm_mid_ssq_chunks(int M, int N);
+int gemm_mid_counters(int max_n);
+void gemm_mid_set_target(int wgs);  // tuning: workgroups the K split aims at
+void launch_gemm_mid(const bf16_t* xt, const bf16_t* wt, int M, int N, int K, const GemmEpi& e, hipStream_t st);  // GEMM_SKINNY_MAX_ROWS < M <= GEMM_MID_MAX_ROWS(_NARROW)
 #define GEMM_MACRO_MIN_ROWS_NARROW 256  // more rows than this: the macro-tile kernel whatever the width
 int gemm_macro_ssq_chunks(int M, int N);
 void launch_gemm_macro(const bf16_t* xt, const bf16_t* wt, int M, int N, int K, const GemmEpi& e, hipStream_t st);

@@ -219,7 +219,7 @@ extern "C" int dlm_state_create(const dlm_model* m, int max_seqs, int max_seq_le
   A(s->ssq, (size_t)max_rows * ssq_chunks * 4);
   int n_counters = 1;
   if (c.dtype == DLM_BF16)
-    for (auto& sh : shapes) { int k = gemm_tiled_counters(max_rows, sh[0]); if (k > n_counters) n_counters = k; }
+    for (auto& sh : shapes) { int k = gemm_bf16_counters(max_rows, sh[0]); if (k > n_counters) n_counters = k; }
   A(s->counters, (size_t)n_counters * 4);
   A(s->row_seq, (size_t)max_rows * 4); A(s->row_pos, (size_t)max_rows * 4); A(s->row_tok, (size_t)max_rows * 4); A(s->row_slot, (size_t)max_rows * 4);
   A(s->rope_cos, (size_t)max_rows * (c.head_dim / 2) * 4); A(s->rope_sin, (size_t)max_rows * (c.head_dim / 2) * 4);
@@ -583,7 +583,7 @@ extern "C" int dlm_gemm_nt(const void* x, const void* w, void* y, int M, int N, 
   if (dtype == DLM_F32) { launch_gemm_f32((const float*)x, (const float*)w, (float*)y, M, N, K, RowScale{nullptr, 0, 0.f, 0.f}, st); return DLM_OK; }
   REQUIRE(N % 32 == 0 && K % 32 == 0, DLM_ESHAPE, "dlm_gemm_nt: bf16 needs N and K to be multiples of 32");
   const size_t mp = (size_t)(M + 15) / 16 * 16;
-  const int n_counters = gemm_tiled_counters(M, N);
+  const int n_counters = gemm_bf16_counters(M, N);
   const size_t tiled_bytes = ((mp * K + (size_t)N * K) * 2 + 15) / 16 * 16;
   const size_t part_bytes = (size_t)gemm_bf16_splits(M, N, K) * M * N * 4;
   void* ws = nullptr;

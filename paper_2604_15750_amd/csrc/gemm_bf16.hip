@@ -57,6 +57,11 @@ bool use_skinny(int M, int N, int kind) { return kind != EPI_DIRECT && M <= GEMM
 // The macro-tile kernel has no K split: it needs enough output tiles of its own.  Wide matrices (QKV, gate/up, LM head) have
 // them from 65 rows on; the narrow ones (O, down: 32 column tiles of 128) only beyond 256 rows, below that the tiled
 // kernel's K split keeps more of the chip busy.
+// the mid kernel: 65 .. 160 rows; narrow matrices (which the macro-tile kernel cannot fill the chip with) up to 256 rows
+bool use_mid(int M, int N) {
+  const int pr = weight_pack_rows(N);
+  return M > GEMM_SKINNY_MAX_ROWS && M <= (pr == 1 ? GEMM_MID_MAX_ROWS_NARROW : GEMM_MID_MAX_ROWS) && N % (16 * pr) == 0;
+}
 bool use_macro(int M, int N) { return M > GEMM_MACRO_MIN_ROWS_NARROW || (M > GEMM_SKINNY_MAX_ROWS && N > 8192); }
 
 }  // namespace
@@ -68,13 +73,20 @@ void launch_pack_act(const bf16_t* x, bf16_t* out, int M, int K, hipStream_t st)
   pack_act_kernel<<<512, 256, 0, st>>>((const bf16x8*)x, (bf16x8*)out, M, K);
 }
 
-int gemm_bf16_splits(int M, int N, int K) { return use_skinny(M, N, EPI_SUM) || use_macro(M, N) ? 1 : gemm_tiled_splits(M, N, K); }
+int gemm_bf16_splits(int M, int N, int K) {
+  return use_skinny(M, N, EPI_SUM) ? 1 : use_mid(M, N) ? gemm_mid_splits(M, N, K) : use_macro(M, N) ? 1 : gemm_tiled_splits(M, N, K);
+}
 int gemm_bf16_ssq_chunks(int M, int N) {
-  return use_skinny(M, N, EPI_RESID) ? N >> 4 : use_macro(M, N) ? gemm_macro_ssq_chunks(M, N) : gemm_tiled_ssq_chunks(M, N);
+  return use_skinny(M, N, EPI_RESID) ? N >> 4 : use_mid(M, N) ? gemm_mid_ssq_chunks(M, N) : use_macro(M, N) ? gemm_macro_ssq_chunks(M, N) : gemm_tiled_ssq_chunks(M, N);
+}
+int gemm_bf16_counters(int max_rows, int max_n) {
+  const int a = gemm_tiled_counters(max_rows, max_n), b = gemm_mid_counters(max_n);
+  return a > b ? a : b;
 }
 
 void launch_gemm_bf16(const bf16_t* xt, const bf16_t* wt, int M, int N, int K, const GemmEpi& e, hipStream_t st) {
   if (use_skinny(M, N, e.kind)) launch_gemm_skinny(xt, wt, weight_pack_rows(N), M, N, K, e, st);
+  else if (use_mid(M, N)) launch_gemm_mid(xt, wt, M, N, K, e, st);
   else if (use_macro(M, N)) launch_gemm_macro(xt, wt, M, N, K, e, st);
   else launch_gemm_tiled(xt, wt, M, N, K, e, st);
 }

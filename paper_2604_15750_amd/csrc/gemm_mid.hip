@@ -1,0 +1,301 @@
+// Mid-size bf16 GEMM (65 .. 160 rows: a block plus its look-ahead window, a few packed blocks):
+// Y[M,N] = X[M,K] * W[N,K]^T, fp32 accumulation, epilogue fused.
+//
+// At these row counts W is still the larger operand, but every column group re-reads X, so the groups
+// have to be wide.  A workgroup of four wavefronts owns ALL the rows (MT row tiles) of CT adjacent
+// column tiles (64 .. 128 columns) and a range of K; its wavefronts split that range among themselves,
+// and each multiplies its k-tiles of the CT W fragments against all MT X fragments (CT MT products
+// per CT + MT fragments fetched), everything in registers:
+//   * W goes HBM -> registers, the k-tile in use and the two after it (a wavefront keeps 2 CT KiB of W
+//     in flight, a workgroup 32 .. 64 KiB: what it takes to keep HBM busy with 128 .. 256 workgroups);
+//     X goes L2 -> registers one k-tile ahead, issued BEFORE the W loads of the same step, so that
+//     waiting for it never waits for younger W loads (the memory counter retires in order);
+//   * no barrier, no LDS inside the loop: a wavefront never waits for another.  (X through
+//     direct-to-LDS loads would save a third of the registers, but the compiler then no longer counts
+//     the register loads beside them and waits for every load in flight once per trip.)
+//   * at the end the four partial accumulators meet in LDS (32 fragments per round), are added in
+//     wavefront order, and each wavefront finishes every fourth output fragment.
+// When the column groups are fewer than the compute units, K is split across workgroups as well:
+// partial tiles go to an fp32 workspace written through to device scope, and the workgroup that takes
+// the last ticket adds them in split order (the protocol of gemm_tiled.hip; a wavefront fetches the
+// same split of all its output fragments in a single trip to memory).
+#include "gemm_epilogue.h"
+
+namespace {
+
+constexpr int TPB = 256, NWV = 4;
+constexpr int WD = 3;  // k-tiles per ring: one in use, two in flight
+
+typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
+constexpr int SC1 = 16;  // cache-policy bit of the raw-buffer builtins: device scope
+
+__device__ inline __amdgpu_buffer_rsrc_t part_rsrc(const float* base) {
+  return __builtin_amdgcn_make_buffer_rsrc((void*)base, 0, 0x7fffffff, 0x00020000);
+}
+
+template <int MT, int CT>
+struct MidShape {
+  static constexpr int F = CT * MT;                 // output fragments of a workgroup
+  static constexpr int FW = (F + NWV - 1) / NWV;    // ... finished by one wavefront
+  static constexpr int FR = F < 32 ? (F + 3) / 4 * 4 : 32;  // fragments per reduction round (a multiple of 4: fragment f stays with wavefront f % 4)
+  static constexpr int ROUNDS = (F + FR - 1) / FR;
+  static constexpr int BODY = NWV * FR * 1024;
+  static constexpr int LDS_BYTES = BODY + MT * 16 * 4 + CT * MT * 16 * 4;  // + 1/rms of the rows + every column tile's sum of squares per row
+};
+
+// grid.x = groups * splits; MT = ceil(M / 16) exactly.
+template <int MT, int CT, int PR, int EPI>
+__global__ __launch_bounds__(TPB) void gemm_mid_kernel(const bf16x8* __restrict__ xt, const bf16x8* __restrict__ wt, int M, int N, int K,
+                                                       int kt_per_split, int splits, GemmEpi e) {
+  typedef MidShape<MT, CT> SH;
+  constexpr int F = SH::F, FW = SH::FW, FR = SH::FR, ROUNDS = SH::ROUNDS;
+  static_assert(2 * (MT + CT) < 64, "two k-tiles in flight must fit the memory counter");
+  extern __shared__ __align__(16) unsigned char lds[];
+  __shared__ int s_last;
+  float* s_rinv = (float*)(lds + SH::BODY);  // [MT * 16]
+  float* s_ssq = s_rinv + MT * 16;           // [CT][MT * 16]
+
+  const int group = blockIdx.x / splits, split = blockIdx.x - group * splits, groups = gridDim.x / splits;
+  const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int KT = K >> 5, NT = N >> 4;
+  const int nt0 = group * CT;
+  const int tb = split * kt_per_split, te = min(KT, tb + kt_per_split);
+  const int per = (te - tb + NWV - 1) / NWV;
+  const int t0 = tb + wave * per, t1 = min(te, t0 + per);  // this wavefront's k-tiles (possibly none)
+
+  constexpr size_t wstep = PR == 2 ? 128 : 64;
+  const bf16x8* wptr[CT];  // fragment (nt0 + r, k-tile t) = wptr[r][t * wstep]; column tiles past the end repeat the last one
+#pragma unroll
+  for (int r = 0; r < CT; ++r) {
+    const int nt = min(nt0 + r, NT - 1);
+    wptr[r] = PR == 2 ? wt + ((size_t)(nt >> 1) * KT * 2 + (nt & 1)) * 64 + lane : wt + (size_t)nt * KT * 64 + lane;
+  }
+  const bf16x8* xptr = xt + lane;  // fragment (j, t) = xptr[(j * KT + t) * 64]
+
+  f32x4 acc[CT][MT];
+#pragma unroll
+  for (int r = 0; r < CT; ++r)
+#pragma unroll
+    for (int j = 0; j < MT; ++j) acc[r][j] = f32x4{0.f, 0.f, 0.f, 0.f};
+  bf16x8 w[WD][CT], x[2][MT];
+
+  // k-tile t (clamped to the wavefront's last one) -> register set `slot`
+  auto load_x = [&](const int slot, int t) {
+    const int tc = min(t, t1 - 1);
+#pragma unroll
+    for (int j = 0; j < MT; ++j) x[slot][j] = xptr[((size_t)j * KT + tc) * 64];
+  };
+  auto load_w = [&](const int slot, int t) {
+    const int tc = min(t, t1 - 1);
+#pragma unroll
+    for (int r = 0; r < CT; ++r) w[slot][r] = wptr[r][(size_t)tc * wstep];
+  };
+  auto compute = [&](const int ws, const int xs) {
+#pragma unroll
+    for (int j = 0; j < MT; ++j)
+#pragma unroll
+      for (int r = 0; r < CT; ++r) acc[r][j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(w[ws][r], x[xs][j], acc[r][j], 0, 0, 0);
+  };
+  // step s of a trip (k-tile t): X of the next k-tile first, then W of the one after it, so that the wait for this k-tile's
+  // operands (the oldest loads) leaves W two k-tiles deep and X one k-tile deep in flight; the scheduling barriers keep the
+  // compiler from sinking the loads down to their uses (which it does under register pressure, undoing the prefetch)
+#define MID_STEP(S, t)                   \
+  {                                      \
+    load_x(((S) + 1) & 1, (t) + 1);      \
+    load_w(((S) + 2) % WD, (t) + 2);     \
+    __builtin_amdgcn_sched_barrier(0);   \
+    compute((S) % WD, (S) & 1);          \
+    __builtin_amdgcn_sched_barrier(0);   \
+  }
+  if (t0 < t1) {
+    load_x(0, t0);
+    load_w(0, t0);
+    load_w(1, t0 + 1);
+    // whole trips of 2 WD steps (the X sets alternate, the W sets rotate), then the steps left over
+    int t = t0;
+    for (; t + 2 * WD <= t1; t += 2 * WD) {
+      MID_STEP(0, t)
+      MID_STEP(1, t + 1)
+      MID_STEP(2, t + 2)
+      MID_STEP(3, t + 3)
+      MID_STEP(4, t + 4)
+      MID_STEP(5, t + 5)
+    }
+    if (t < t1) {
+      MID_STEP(0, t)
+      if (t + 1 < t1) {
+        MID_STEP(1, t + 1)
+        if (t + 2 < t1) {
+          MID_STEP(2, t + 2)
+          if (t + 3 < t1) {
+            MID_STEP(3, t + 3)
+            if (t + 4 < t1) MID_STEP(4, t + 4)
+          }
+        }
+      }
+    }
+  }
+#undef MID_STEP
+
+  // ---- the four partial accumulators -> one finished (or, with a K split, one partial) value per output fragment
+  const int g = lane >> 4, ml = lane & 15;
+  if (EPI != EPI_RESID) block_rinv<TPB>(e.rs, 0, min(M, MT * 16), s_rinv);  // published by the rounds' barriers
+  f32x4* red = (f32x4*)lds;  // [NWV][FR][64]
+  const size_t stride = (size_t)M * N;
+  float* mine = e.part + split * stride;
+  // fragment f = r * MT + j (column tile r, row tile j) in the accumulator layout -> its epilogue
+  auto finish = [&](int f, f32x4 v) {
+    const int r = f / MT, j = f - r * MT;
+    const int nt = nt0 + r, m = j * 16 + ml;
+    float ss = 0.f;
+    if (nt < NT) ss = finish_frag<EPI>(e, M, N, m, nt * 16, g, v, EPI == EPI_RESID ? 1.f : s_rinv[m]);  // uniform in the wavefront
+    if (EPI == EPI_RESID && g == 0) s_ssq[r * MT * 16 + m] = ss;
+  };
+#pragma unroll
+  for (int rd = 0; rd < ROUNDS; ++rd) {
+    if (rd) __syncthreads();  // the previous round has been read
+#pragma unroll
+    for (int i = 0; i < FR; ++i)
+      if (rd * FR + i < F) red[(wave * FR + i) * 64 + lane] = acc[min(rd * FR + i, F - 1) / MT][min(rd * FR + i, F - 1) % MT];
+    __syncthreads();
+    for (int i = wave; i < FR && rd * FR + i < F; i += NWV) {
+      const f32x4 v = ((red[i * 64 + lane] + red[(FR + i) * 64 + lane]) + red[(2 * FR + i) * 64 + lane]) + red[(3 * FR + i) * 64 + lane];
+      const int f = rd * FR + i;
+      if (splits == 1) {
+        finish(f, v);
+      } else {  // partial tile -> workspace, written through to device scope
+        const int r = f / MT, j = f - r * MT;
+        const int nt = nt0 + r, m = j * 16 + ml;
+        if (nt < NT && m < M)
+          __builtin_amdgcn_raw_buffer_store_b128(__builtin_bit_cast(u32x4, v), part_rsrc(mine), ((unsigned)m * N + nt * 16 + 4 * g) * 4u, 0, SC1);
+      }
+    }
+  }
+  if (splits > 1) {
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");  // every wavefront's stores have completed ...
+    __syncthreads();                                        // ... before the workgroup takes its ticket
+    if (tid == 0) {
+      int* ticket = e.counters + group;
+      const int last = __hip_atomic_fetch_add(ticket, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) == splits - 1;
+      if (last) __hip_atomic_store(ticket, 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);  // ready for the next launch
+      s_last = last;
+    }
+    __syncthreads();
+    if (!s_last) return;
+    // the finished tile = the partial tiles added in split order; a wavefront fetches one split of all its fragments per trip
+    f32x4 v[FW];
+    unsigned off[FW];
+#pragma unroll
+    for (int i = 0; i < FW; ++i) {
+      const int f = wave + NWV * i, r = f / MT, j = f - r * MT;
+      const int nt = nt0 + r, m = j * 16 + ml;
+      off[i] = (f < F && nt < NT && m < M) ? ((unsigned)m * N + nt * 16 + 4 * g) * 4u : 0u;  // fragments that do not exist re-read element 0
+      v[i] = f32x4{0.f, 0.f, 0.f, 0.f};
+    }
+    for (int s = 0; s < splits; s += 2) {  // two splits per trip to memory
+      const int s1 = min(s + 1, splits - 1);
+      u32x4 ta[FW], tb[FW];
+#pragma unroll
+      for (int i = 0; i < FW; ++i) ta[i] = __builtin_amdgcn_raw_buffer_load_b128(part_rsrc(e.part + s * stride), off[i], 0, SC1);
+#pragma unroll
+      for (int i = 0; i < FW; ++i) tb[i] = __builtin_amdgcn_raw_buffer_load_b128(part_rsrc(e.part + s1 * stride), off[i], 0, SC1);
+#pragma unroll
+      for (int i = 0; i < FW; ++i) v[i] += __builtin_bit_cast(f32x4, ta[i]);
+      if (s + 1 < splits)
+#pragma unroll
+        for (int i = 0; i < FW; ++i) v[i] += __builtin_bit_cast(f32x4, tb[i]);
+    }
+#pragma unroll
+    for (int i = 0; i < FW; ++i)
+      if (wave + NWV * i < F) finish(wave + NWV * i, v[i]);
+  }
+  if (EPI == EPI_RESID) {  // the workgroup's share of sum h^2 per row: its column tiles in order
+    __syncthreads();
+    if (tid < MT * 16 && tid < M) {
+      float ss = 0.f;
+#pragma unroll
+      for (int r = 0; r < CT; ++r) ss += s_ssq[r * MT * 16 + tid];
+      e.ssq_out[(size_t)tid * groups + group] = ss;
+    }
+  }
+}
+
+int g_mid_wgs = 256;  // workgroups the K split of a narrow matrix aims at
+
+struct MidPlan {
+  int ct, pr, mt, groups, splits, kps;
+};
+
+// What the compute units can load through their L2s (W once, X once per column group; about 45 GB/s each, 10 .. 12 TB/s
+// together) bounds these shapes before HBM does.  Wide matrices: column groups as wide as the accumulators allow (128
+// columns up to 112 rows, 96 beyond), K split in two when that still fits the chip in one round.  Narrow ones (O, down):
+// 64-column groups and a K split of three; wider groups would need more splits to fill the chip, and the partial tiles'
+// round trip through memory costs more than the X re-reads saved (measured).
+MidPlan mid_plan(int M, int N, int K, bool may_split) {
+  MidPlan p;
+  p.pr = weight_pack_rows(N);
+  p.mt = (M + 15) >> 4;
+  p.ct = p.pr == 2 ? (p.mt <= 7 ? 8 : 6) : 4;  // accumulators (4 CT MT registers) + three k-tiles of W + two of X within the register file
+  p.groups = (N + 16 * p.ct - 1) / (16 * p.ct);
+  const int KT = K >> 5;
+  int s = p.pr == 2 ? 256 / p.groups : (g_mid_wgs + p.groups / 2) / p.groups;
+  if (s > (p.pr == 2 ? 2 : 4)) s = p.pr == 2 ? 2 : 4;  // a short serial tail for the last arriver, and little traffic of partial tiles
+  if (s > KT / 16) s = KT / 16;     // at least four k-tiles per wavefront
+  if (s < 1 || !may_split) s = 1;
+  p.kps = (KT + s - 1) / s;
+  p.splits = (KT + p.kps - 1) / p.kps;  // no empty split
+  return p;
+}
+
+template <int MT, int CT, int PR, int EPI>
+void launch_one(const bf16_t* xt, const bf16_t* wt, int M, int N, int K, const MidPlan& p, const GemmEpi& e, hipStream_t st) {
+  typedef MidShape<MT, CT> SH;
+  static bool configured = false;  // raise the dynamic LDS limit of this instantiation once
+  if (!configured) {
+    (void)hipFuncSetAttribute((const void*)gemm_mid_kernel<MT, CT, PR, EPI>, hipFuncAttributeMaxDynamicSharedMemorySize, SH::LDS_BYTES);
+    configured = true;
+  }
+  gemm_mid_kernel<MT, CT, PR, EPI><<<p.groups * p.splits, TPB, SH::LDS_BYTES, st>>>((const bf16x8*)xt, (const bf16x8*)wt, M, N, K, p.kps, p.splits, e);
+}
+
+template <int MT, int EPI>
+void launch_mt(const bf16_t* xt, const bf16_t* wt, int M, int N, int K, const MidPlan& p, const GemmEpi& e, hipStream_t st) {
+  if (p.pr == 2) launch_one<MT, (MT <= 7 ? 8 : 6), 2, EPI>(xt, wt, M, N, K, p, e, st);
+  else launch_one<MT, 4, 1, EPI>(xt, wt, M, N, K, p, e, st);
+}
+
+template <int EPI>
+void launch_epi(const bf16_t* xt, const bf16_t* wt, int M, int N, int K, const MidPlan& p, const GemmEpi& e, hipStream_t st) {
+  switch (p.mt) {
+    case 5: launch_mt<5, EPI>(xt, wt, M, N, K, p, e, st); break;
+    case 6: launch_mt<6, EPI>(xt, wt, M, N, K, p, e, st); break;
+    case 7: launch_mt<7, EPI>(xt, wt, M, N, K, p, e, st); break;
+    case 8: launch_mt<8, EPI>(xt, wt, M, N, K, p, e, st); break;
+    case 9: launch_mt<9, EPI>(xt, wt, M, N, K, p, e, st); break;
+    case 10: launch_mt<10, EPI>(xt, wt, M, N, K, p, e, st); break;
+    // more than 160 rows: narrow matrices only
+    case 11: launch_one<11, 4, 1, EPI>(xt, wt, M, N, K, p, e, st); break;
+    case 12: launch_one<12, 4, 1, EPI>(xt, wt, M, N, K, p, e, st); break;
+    case 13: launch_one<13, 4, 1, EPI>(xt, wt, M, N, K, p, e, st); break;
+    case 14: launch_one<14, 4, 1, EPI>(xt, wt, M, N, K, p, e, st); break;
+    case 15: launch_one<15, 4, 1, EPI>(xt, wt, M, N, K, p, e, st); break;
+    default: launch_one<16, 4, 1, EPI>(xt, wt, M, N, K, p, e, st); break;
+  }
+}
+
+}  // namespace
+
+int gemm_mid_splits(int M, int N, int K) { return mid_plan(M, N, K, true).splits; }
+int gemm_mid_ssq_chunks(int M, int N) { return mid_plan(M, N, 1024, true).groups; }
+int gemm_mid_counters(int max_n) { return (max_n + 63) / 64; }  // 64-column groups are the narrowest
+void gemm_mid_set_target(int wgs) { g_mid_wgs = wgs; }
+
+void launch_gemm_mid(const bf16_t* xt, const bf16_t* wt, int M, int N, int K, const GemmEpi& e, hipStream_t st) {
+  const MidPlan p = mid_plan(M, N, K, e.kind != EPI_DIRECT);  // EPI_DIRECT has no workspace
+  switch (e.kind) {
+    case EPI_QKV: launch_epi<EPI_QKV>(xt, wt, M, N, K, p, e, st); break;
+    case EPI_SWIGLU: launch_epi<EPI_SWIGLU>(xt, wt, M, N, K, p, e, st); break;
+    case EPI_RESID: launch_epi<EPI_RESID>(xt, wt, M, N, K, p, e, st); break;
+    default: launch_epi<EPI_SUM>(xt, wt, M, N, K, p, e, st); break;
+  }
+}
