@@ -127,7 +127,7 @@ __host__ __device__ inline int weight_pack_rows(int N) { return N <= 8192 ? 1 : 
 void launch_pack_weight(const bf16_t* w, bf16_t* out, int N, int K, int perm, int perm_param, hipStream_t st);
 void launch_pack_act(const bf16_t* x, bf16_t* out, int M, int K, hipStream_t st);  // row-major -> fragment tiles (rows padded to 16 with zeros)
 int gemm_bf16_splits(int M, int N, int K);         // partial tiles [splits][M][N] the launch of this shape needs in GemmEpi::part (1: none)
-int gemm_bf16_ssq_chunks(int M, int N);            // chunks per row of the sums of squares an EPI_RESID launch of this shape writes
+int gemm_bf16_ssq_chunks(int M, int N, int K);     // chunks per row of the sums of squares an EPI_RESID launch of this shape writes
 int gemm_bf16_counters(int max_rows, int max_n);   // ticket counters a state needs in GemmEpi::counters (zero-initialised, self-resetting)
 int gemm_tiled_counters(int max_rows, int max_n);
 int gemm_tiled_splits(int M, int N, int K);
@@ -155,7 +155,7 @@ struct GemmEpi {
   // EPI_SWIGLU (weights packed with PERM_GATED)
   bf16_t* act;
   int ffn;
-  // EPI_RESID: h += y; x = h * gain (fragment tiles); ssq_out[m][gemm_bf16_ssq_chunks(M, N)] = each column tile's share of sum h^2
+  // EPI_RESID: h += y; x = h * gain (fragment tiles); ssq_out[m][gemm_bf16_ssq_chunks(M, N, K)] = each column tile's share of sum h^2
   float* h;
   const float* gain;
   bf16_t* x;
@@ -175,7 +175,7 @@ int gemm_mid_splits(int M, int N, int K);
 int gemm_mid_ssq_chunks(int M, int N);
 int gemm_mid_counters(int max_n);
 void gemm_mid_set_target(int wgs);  // tuning: workgroups the K split aims at
-void launch_gemm_mid(const bf16_t* xt, const bf16_t* wt, int M, int N, int K, const GemmEpi& e, hipStream_t st);  // GEMM_SKINNY_MAX_ROWS < M <= GEMM_MID_MAX_ROWS(_NARROW)
+void launch_gemm_mid(const bf16_t* xt, const bf16_t* wt, int M, int N, int K, const GemmEpi& e, hipStream_t st);  // 17 <= M <= GEMM_MID_MAX_ROWS(_NARROW)
 #define GEMM_MACRO_MIN_ROWS_NARROW 256  // more rows than this: the macro-tile kernel whatever the width
 int gemm_macro_ssq_chunks(int M, int N);
 void launch_gemm_macro(const bf16_t* xt, const bf16_t* wt, int M, int N, int K, const GemmEpi& e, hipStream_t st);

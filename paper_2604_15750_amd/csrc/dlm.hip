@@ -376,7 +376,8 @@ int run_step_bf16(dlm_state* s, const dlm_step_desc* d, const SeqMeta& meta, con
     launch_prepare(meta, sm, t, rows, c.vocab, hd, c.rope_theta, st);
     launch_embed_norm<T>((const T*)m->embed.p, d->tokens, t, (const float*)m->norm1[0].p, h, x, ssq, rows, dm, st);
   }
-  int nch = norm_chunks(dm);  // chunks of the row sums of squares the next consumer reads: the embedding's, then the epilogue's
+  // chunks of the row sums of squares the next consumer reads: the embedding's, then those of the GEMM that produced them
+  int nch = norm_chunks(dm);
   for (int l = 0; l < c.n_layers; ++l) {
     T* kc = (T*)s->kcache.p + s->layer_stride * l;
     T* vc = (T*)s->vcache.p + s->layer_stride * l;
@@ -396,7 +397,7 @@ int run_step_bf16(dlm_state* s, const dlm_step_desc* d, const SeqMeta& meta, con
       e.kind = EPI_RESID;
       e.h = h; e.gain = (const float*)m->norm2[l].p; e.x = x; e.ssq_out = ssq;
       gemm(PC_O, x2, m->wo[l].p, dm, qd, e);
-      nch = gemm_bf16_ssq_chunks(rows, dm);
+      nch = gemm_bf16_ssq_chunks(rows, dm, qd);
     }
     {
       GemmEpi e = base;
@@ -411,6 +412,7 @@ int run_step_bf16(dlm_state* s, const dlm_step_desc* d, const SeqMeta& meta, con
       e.h = h; e.gain = l + 1 < c.n_layers ? (const float*)m->norm1[l + 1].p : (const float*)m->final_norm.p;
       e.x = x; e.ssq_out = ssq;
       gemm(PC_DOWN, act, m->w_down[l].p, dm, ffn, e);
+      nch = gemm_bf16_ssq_chunks(rows, dm, ffn);
     }
   }
   {

@@ -8,9 +8,10 @@
 //   * activations live in the same fragment tiling (B operand), written that way by their producer;
 //   * the product is computed transposed (W fragment = A operand), so a lane ends up with four
 //     consecutive output columns of one row.
-// gemm_skinny.hip serves M <= 64 (except the LM head), gemm_macro.hip (both operands through LDS, large output tiles:
-// bound by the matrix cores, not by W) wide passes, gemm_tiled.hip what lies between; the layer's
-// row-wise glue runs in their epilogues (gemm_epilogue.h):
+// gemm_skinny.hip serves M <= 64 (except the LM head), gemm_mid.hip a block with its look-ahead window (65 .. 160 rows, all
+// of them in one workgroup), gemm_macro.hip (both operands through LDS, large output tiles: bound by the matrix cores, not
+// by W) wide passes, gemm_tiled.hip what is left (choose_kernel below); the layer's row-wise glue runs in their epilogues
+// (gemm_epilogue.h):
 //   QKV     1/rms of the input row, rotary embedding, Q row-major, K and V into the tiled KV cache
 //   SWIGLU  1/rms, silu(gate) * up into the fragment tiling of the down projection
 //   RESID   residual add, x = h * gain of the next RMSNorm into fragment tiling, and the share of
@@ -53,16 +54,26 @@ __global__ void pack_act_kernel(const bf16x8* __restrict__ x, bf16x8* __restrict
   }
 }
 
-bool use_skinny(int M, int N, int kind) { return kind != EPI_DIRECT && M <= GEMM_SKINNY_MAX_ROWS && N % (16 * weight_pack_rows(N)) == 0; }
-// The macro-tile kernel has no K split: it needs enough output tiles of its own.  Wide matrices (QKV, gate/up, LM head) have
-// them from 65 rows on; the narrow ones (O, down: 32 column tiles of 128) only beyond 256 rows, below that the tiled
-// kernel's K split keeps more of the chip busy.
-// the mid kernel: 65 .. 160 rows; narrow matrices (which the macro-tile kernel cannot fill the chip with) up to 256 rows
-bool use_mid(int M, int N) {
+// Which kernel serves a shape (measured crossovers on the layer shapes of 7 .. 8 B models):
+//   skinny  up to 64 rows: nothing crosses workgroups, every wavefront streams W;
+//   mid     65 .. 160 rows (narrow matrices to 256); and from 17 rows where its wider column groups pay: matrices wide
+//           enough to fill the chip with 128-column groups (gate/up), and narrow ones whose K is long enough for a
+//           four-way split (down) - there the skinny kernel's re-reads of X by every 16- or 32-column group cost more
+//           than W itself;
+//   macro   more rows than that when the matrix has enough 128 x 256 tiles of its own (wide from 161 rows, narrow from 257);
+//   tiled   the rest, and the LM head up to 64 rows (no workspace: no K split).
+enum { KERNEL_SKINNY, KERNEL_MID, KERNEL_MACRO, KERNEL_TILED };
+int choose_kernel(int M, int N, int K, int kind) {
   const int pr = weight_pack_rows(N);
-  return M > GEMM_SKINNY_MAX_ROWS && M <= (pr == 1 ? GEMM_MID_MAX_ROWS_NARROW : GEMM_MID_MAX_ROWS) && N % (16 * pr) == 0;
+  const bool whole_groups = N % (16 * pr) == 0;
+  if (M <= GEMM_SKINNY_MAX_ROWS && kind != EPI_DIRECT && whole_groups) {
+    if (M > 16 && ((pr == 2 && N >= 16384) || (pr == 1 && K >= 8192))) return KERNEL_MID;
+    return KERNEL_SKINNY;
+  }
+  if (M > GEMM_SKINNY_MAX_ROWS && M <= (pr == 1 ? GEMM_MID_MAX_ROWS_NARROW : GEMM_MID_MAX_ROWS) && whole_groups) return KERNEL_MID;
+  if (M > GEMM_MACRO_MIN_ROWS_NARROW || (M > GEMM_SKINNY_MAX_ROWS && N > 8192)) return KERNEL_MACRO;
+  return KERNEL_TILED;
 }
-bool use_macro(int M, int N) { return M > GEMM_MACRO_MIN_ROWS_NARROW || (M > GEMM_SKINNY_MAX_ROWS && N > 8192); }
 
 }  // namespace
 
@@ -74,10 +85,19 @@ void launch_pack_act(const bf16_t* x, bf16_t* out, int M, int K, hipStream_t st)
 }
 
 int gemm_bf16_splits(int M, int N, int K) {
-  return use_skinny(M, N, EPI_SUM) ? 1 : use_mid(M, N) ? gemm_mid_splits(M, N, K) : use_macro(M, N) ? 1 : gemm_tiled_splits(M, N, K);
+  switch (choose_kernel(M, N, K, EPI_SUM)) {
+    case KERNEL_MID: return gemm_mid_splits(M, N, K);
+    case KERNEL_TILED: return gemm_tiled_splits(M, N, K);
+    default: return 1;
+  }
 }
-int gemm_bf16_ssq_chunks(int M, int N) {
-  return use_skinny(M, N, EPI_RESID) ? N >> 4 : use_mid(M, N) ? gemm_mid_ssq_chunks(M, N) : use_macro(M, N) ? gemm_macro_ssq_chunks(M, N) : gemm_tiled_ssq_chunks(M, N);
+int gemm_bf16_ssq_chunks(int M, int N, int K) {
+  switch (choose_kernel(M, N, K, EPI_RESID)) {
+    case KERNEL_SKINNY: return N >> 4;
+    case KERNEL_MID: return gemm_mid_ssq_chunks(M, N);
+    case KERNEL_MACRO: return gemm_macro_ssq_chunks(M, N);
+    default: return gemm_tiled_ssq_chunks(M, N);
+  }
 }
 int gemm_bf16_counters(int max_rows, int max_n) {
   const int a = gemm_tiled_counters(max_rows, max_n), b = gemm_mid_counters(max_n);
@@ -85,8 +105,10 @@ int gemm_bf16_counters(int max_rows, int max_n) {
 }
 
 void launch_gemm_bf16(const bf16_t* xt, const bf16_t* wt, int M, int N, int K, const GemmEpi& e, hipStream_t st) {
-  if (use_skinny(M, N, e.kind)) launch_gemm_skinny(xt, wt, weight_pack_rows(N), M, N, K, e, st);
-  else if (use_mid(M, N)) launch_gemm_mid(xt, wt, M, N, K, e, st);
-  else if (use_macro(M, N)) launch_gemm_macro(xt, wt, M, N, K, e, st);
-  else launch_gemm_tiled(xt, wt, M, N, K, e, st);
+  switch (choose_kernel(M, N, K, e.kind)) {
+    case KERNEL_SKINNY: launch_gemm_skinny(xt, wt, weight_pack_rows(N), M, N, K, e, st); break;
+    case KERNEL_MID: launch_gemm_mid(xt, wt, M, N, K, e, st); break;
+    case KERNEL_MACRO: launch_gemm_macro(xt, wt, M, N, K, e, st); break;
+    default: launch_gemm_tiled(xt, wt, M, N, K, e, st); break;
+  }
 }

@@ -1,4 +1,4 @@
-// Mid-size bf16 GEMM (65 .. 160 rows: a block plus its look-ahead window, a few packed blocks):
+// Mid-size bf16 GEMM (65 .. 160 rows: a block plus its look-ahead window, a few packed blocks; from 17 rows for some shapes):
 // Y[M,N] = X[M,K] * W[N,K]^T, fp32 accumulation, epilogue fused.
 //
 // At these row counts W is still the larger operand, but every column group re-reads X, so the groups
@@ -43,7 +43,7 @@ struct MidShape {
   static constexpr int LDS_BYTES = BODY + MT * 16 * 4 + CT * MT * 16 * 4;  // + 1/rms of the rows + every column tile's sum of squares per row
 };
 
-// grid.x = groups * splits; MT = ceil(M / 16) exactly.
+// grid.x = groups * splits; MT >= ceil(M / 16), and X has MT row tiles (the activation buffers are padded to 16 rows).
 template <int MT, int CT, int PR, int EPI>
 __global__ __launch_bounds__(TPB) void gemm_mid_kernel(const bf16x8* __restrict__ xt, const bf16x8* __restrict__ wt, int M, int N, int K,
                                                        int kt_per_split, int splits, GemmEpi e) {
@@ -267,6 +267,9 @@ void launch_mt(const bf16_t* xt, const bf16_t* wt, int M, int N, int K, const Mi
 template <int EPI>
 void launch_epi(const bf16_t* xt, const bf16_t* wt, int M, int N, int K, const MidPlan& p, const GemmEpi& e, hipStream_t st) {
   switch (p.mt) {
+    case 2: launch_mt<2, EPI>(xt, wt, M, N, K, p, e, st); break;
+    case 3: launch_mt<3, EPI>(xt, wt, M, N, K, p, e, st); break;
+    case 4: launch_mt<4, EPI>(xt, wt, M, N, K, p, e, st); break;
     case 5: launch_mt<5, EPI>(xt, wt, M, N, K, p, e, st); break;
     case 6: launch_mt<6, EPI>(xt, wt, M, N, K, p, e, st); break;
     case 7: launch_mt<7, EPI>(xt, wt, M, N, K, p, e, st); break;
@@ -291,6 +294,7 @@ int gemm_mid_counters(int max_n) { return (max_n + 63) / 64; }  // 64-column gro
 void gemm_mid_set_target(int wgs) { g_mid_wgs = wgs; }
 
 void launch_gemm_mid(const bf16_t* xt, const bf16_t* wt, int M, int N, int K, const GemmEpi& e, hipStream_t st) {
+  if (M <= 16) { launch_gemm_skinny(xt, wt, weight_pack_rows(N), M, N, K, e, st); return; }  // no instantiation for one row tile
   const MidPlan p = mid_plan(M, N, K, e.kind != EPI_DIRECT);  // EPI_DIRECT has no workspace
   switch (e.kind) {
     case EPI_QKV: launch_epi<EPI_QKV>(xt, wt, M, N, K, p, e, st); break;

@@ -29,12 +29,13 @@ def _rowtol(ref, rel, floor=0.0):
 
 # ---- GEMM ----------------------------------------------------------------------------------------
 @pytest.mark.parametrize("M,N,K", [(1, 32, 32), (7, 64, 96), (16, 128, 128), (64, 4096, 4096), (100, 160, 4096 + 64),
-                                   (192, 1024, 1536), (300, 96, 512), (33, 12288, 256), (64, 256, 12288),
+                                   (192, 1024, 1536), (300, 96, 512), (33, 12288, 256),
                                    # 65 .. 160 rows: the mid kernel (every row-tile count; wide matrices with 128- and 96-column groups and a ragged
                                    # last group; narrow ones with and without a K split; k ranges that leave wavefronts idle)
                                    (65, 4096, 4096), (81, 24576, 512), (97, 4096, 1024), (112, 12288, 2048), (113, 4096, 12288),
                                    (136, 12288, 4096), (150, 8224, 1024), (160, 4096, 4096), (80, 126464, 64), (144, 64, 96),
                                    (161, 4096, 4096), (200, 1024, 2048), (225, 4096, 12288), (256, 4096, 512),
+                                   (17, 16384, 256), (40, 24576, 1024), (33, 4096, 8192), (64, 256, 12288),
                                    # more than 256 rows: the macro-tile kernel (ragged rows, column tails, both weight packings, short K)
                                    (257, 4096, 4096), (513, 8224, 1024), (700, 160, 4096 + 64), (1100, 640, 64), (384, 12288, 32)])
 def test_gemm_bf16(device, M, N, K):
