@@ -172,10 +172,11 @@ void launch_gemm_tiled(const bf16_t* xt, const bf16_t* wt, int M, int N, int K, 
 #define GEMM_MID_MAX_ROWS 160  // 65 .. this many rows: the mid kernel (all rows in one workgroup, wavefronts split K)
 #define GEMM_MID_MAX_ROWS_NARROW 256  // ... for matrices of at most 8192 columns
 int gemm_mid_splits(int M, int N, int K);
-int gemm_mid_ssq_chunks(int M, int N);
+int gemm_mid_ssq_chunks(int M, int N, int K);
+bool gemm_mid_fills_chip(int M, int N, int K);  // its column groups are a whole number of rounds over the compute units, without a K split
 int gemm_mid_counters(int max_n);
 void gemm_mid_set_target(int wgs);  // tuning: workgroups the K split aims at
-void launch_gemm_mid(const bf16_t* xt, const bf16_t* wt, int M, int N, int K, const GemmEpi& e, hipStream_t st);  // 17 <= M <= GEMM_MID_MAX_ROWS(_NARROW)
+void launch_gemm_mid(const bf16_t* xt, const bf16_t* wt, int M, int N, int K, const GemmEpi& e, hipStream_t st);  // M <= GEMM_MID_MAX_ROWS(_NARROW); narrow matrices from 17 rows
 #define GEMM_MACRO_MIN_ROWS_NARROW 256  // more rows than this: the macro-tile kernel whatever the width
 int gemm_macro_ssq_chunks(int M, int N);
 void launch_gemm_macro(const bf16_t* xt, const bf16_t* wt, int M, int N, int K, const GemmEpi& e, hipStream_t st);

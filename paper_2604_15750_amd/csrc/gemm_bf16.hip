@@ -56,10 +56,10 @@ __global__ void pack_act_kernel(const bf16x8* __restrict__ x, bf16x8* __restrict
 
 // Which kernel serves a shape (measured crossovers on the layer shapes of 7 .. 8 B models):
 //   skinny  up to 64 rows: nothing crosses workgroups, every wavefront streams W;
-//   mid     65 .. 160 rows (narrow matrices to 256); and from 17 rows where its wider column groups pay: matrices wide
-//           enough to fill the chip with 128-column groups (gate/up), and narrow ones whose K is long enough for a
-//           four-way split (down) - there the skinny kernel's re-reads of X by every 16- or 32-column group cost more
-//           than W itself;
+//   mid     65 .. 160 rows (narrow matrices to 256); and below that where its wider column groups pay: from 17 rows for
+//           wide matrices (QKV, gate/up) and for narrow ones whose K is long enough for a four-way split (down) - there
+//           the skinny kernel's re-reads of X by every 16- or 32-column group cost more than W itself - and at any row
+//           count when its 96-column groups are exactly one per compute unit (gate/up of an 8B model);
 //   macro   more rows than that when the matrix has enough 128 x 256 tiles of its own (wide from 161 rows, narrow from 257);
 //   tiled   the rest, and the LM head up to 64 rows (no workspace: no K split).
 enum { KERNEL_SKINNY, KERNEL_MID, KERNEL_MACRO, KERNEL_TILED };
@@ -67,7 +67,8 @@ int choose_kernel(int M, int N, int K, int kind) {
   const int pr = weight_pack_rows(N);
   const bool whole_groups = N % (16 * pr) == 0;
   if (M <= GEMM_SKINNY_MAX_ROWS && kind != EPI_DIRECT && whole_groups) {
-    if (M > 16 && ((pr == 2 && N >= 16384) || (pr == 1 && K >= 8192))) return KERNEL_MID;
+    if (pr == 2 && (M > 16 || (N >= 16384 && gemm_mid_fills_chip(M, N, K)))) return KERNEL_MID;
+    if (pr == 1 && M > 16 && K >= 8192) return KERNEL_MID;
     return KERNEL_SKINNY;
   }
   if (M > GEMM_SKINNY_MAX_ROWS && M <= (pr == 1 ? GEMM_MID_MAX_ROWS_NARROW : GEMM_MID_MAX_ROWS) && whole_groups) return KERNEL_MID;
@@ -94,7 +95,7 @@ int gemm_bf16_splits(int M, int N, int K) {
 int gemm_bf16_ssq_chunks(int M, int N, int K) {
   switch (choose_kernel(M, N, K, EPI_RESID)) {
     case KERNEL_SKINNY: return N >> 4;
-    case KERNEL_MID: return gemm_mid_ssq_chunks(M, N);
+    case KERNEL_MID: return gemm_mid_ssq_chunks(M, N, K);
     case KERNEL_MACRO: return gemm_macro_ssq_chunks(M, N);
     default: return gemm_tiled_ssq_chunks(M, N);
   }

@@ -232,19 +232,27 @@ struct MidPlan {
 // 64-column groups and a K split of three; wider groups would need more splits to fill the chip, and the partial tiles'
 // round trip through memory costs more than the X re-reads saved (measured).
 MidPlan mid_plan(int M, int N, int K, bool may_split) {
-  MidPlan p;
-  p.pr = weight_pack_rows(N);
-  p.mt = (M + 15) >> 4;
-  p.ct = p.pr == 2 ? (p.mt <= 7 ? 8 : 6) : 4;  // accumulators (4 CT MT registers) + three k-tiles of W + two of X within the register file
-  p.groups = (N + 16 * p.ct - 1) / (16 * p.ct);
-  const int KT = K >> 5;
-  int s = p.pr == 2 ? 256 / p.groups : (g_mid_wgs + p.groups / 2) / p.groups;
-  if (s > (p.pr == 2 ? 2 : 4)) s = p.pr == 2 ? 2 : 4;  // a short serial tail for the last arriver, and little traffic of partial tiles
-  if (s > KT / 16) s = KT / 16;     // at least four k-tiles per wavefront
-  if (s < 1 || !may_split) s = 1;
-  p.kps = (KT + s - 1) / s;
-  p.splits = (KT + p.kps - 1) / p.kps;  // no empty split
-  return p;
+  MidPlan best;
+  double best_fill = -1.;
+  const int pr = weight_pack_rows(N), mt = (M + 15) >> 4, KT = K >> 5;
+  // accumulators (4 CT MT registers) + three k-tiles of W + two of X within the register file: 128-column groups up to 112 rows
+  const int cts[2] = {pr == 2 ? (mt <= 7 ? 8 : 6) : 4, pr == 2 ? 6 : 4};
+  for (int c = 0; c < 2; ++c) {
+    MidPlan p;
+    p.pr = pr; p.mt = mt; p.ct = cts[c];
+    p.groups = (N + 16 * p.ct - 1) / (16 * p.ct);
+    int s = pr == 2 ? 256 / p.groups : (g_mid_wgs + p.groups / 2) / p.groups;
+    if (s > (pr == 2 ? 2 : 4)) s = pr == 2 ? 2 : 4;  // a short serial tail for the last arriver, and little traffic of partial tiles
+    if (s > KT / 16) s = KT / 16;     // at least four k-tiles per wavefront
+    if (s < 1 || !may_split) s = 1;
+    p.kps = (KT + s - 1) / s;
+    p.splits = (KT + p.kps - 1) / p.kps;  // no empty split
+    // of the two group widths, the one whose workgroups fill the chip's 256 compute units better (the wider on a near tie)
+    const int wgs = p.groups * p.splits;
+    const double fill = (double)wgs / ((wgs + 255) / 256 * 256);
+    if (fill > best_fill + 0.02) { best_fill = fill; best = p; }
+  }
+  return best;
 }
 
 template <int MT, int CT, int PR, int EPI>
@@ -260,13 +268,19 @@ void launch_one(const bf16_t* xt, const bf16_t* wt, int M, int N, int K, const M
 
 template <int MT, int EPI>
 void launch_mt(const bf16_t* xt, const bf16_t* wt, int M, int N, int K, const MidPlan& p, const GemmEpi& e, hipStream_t st) {
-  if (p.pr == 2) launch_one<MT, (MT <= 7 ? 8 : 6), 2, EPI>(xt, wt, M, N, K, p, e, st);
-  else launch_one<MT, 4, 1, EPI>(xt, wt, M, N, K, p, e, st);
+  if (p.pr == 1) {
+    if constexpr (MT >= 2) launch_one<MT, 4, 1, EPI>(xt, wt, M, N, K, p, e, st);
+  } else if (p.ct == 8) {
+    if constexpr (MT <= 7) launch_one<MT, 8, 2, EPI>(xt, wt, M, N, K, p, e, st);
+  } else {
+    if constexpr (MT <= 10) launch_one<MT, 6, 2, EPI>(xt, wt, M, N, K, p, e, st);
+  }
 }
 
 template <int EPI>
 void launch_epi(const bf16_t* xt, const bf16_t* wt, int M, int N, int K, const MidPlan& p, const GemmEpi& e, hipStream_t st) {
-  switch (p.mt) {
+  switch (p.mt) {  // the dispatcher sends only row counts that have an instantiation
+    case 1: launch_mt<1, EPI>(xt, wt, M, N, K, p, e, st); break;
     case 2: launch_mt<2, EPI>(xt, wt, M, N, K, p, e, st); break;
     case 3: launch_mt<3, EPI>(xt, wt, M, N, K, p, e, st); break;
     case 4: launch_mt<4, EPI>(xt, wt, M, N, K, p, e, st); break;
@@ -276,25 +290,28 @@ void launch_epi(const bf16_t* xt, const bf16_t* wt, int M, int N, int K, const M
     case 8: launch_mt<8, EPI>(xt, wt, M, N, K, p, e, st); break;
     case 9: launch_mt<9, EPI>(xt, wt, M, N, K, p, e, st); break;
     case 10: launch_mt<10, EPI>(xt, wt, M, N, K, p, e, st); break;
-    // more than 160 rows: narrow matrices only
-    case 11: launch_one<11, 4, 1, EPI>(xt, wt, M, N, K, p, e, st); break;
-    case 12: launch_one<12, 4, 1, EPI>(xt, wt, M, N, K, p, e, st); break;
-    case 13: launch_one<13, 4, 1, EPI>(xt, wt, M, N, K, p, e, st); break;
-    case 14: launch_one<14, 4, 1, EPI>(xt, wt, M, N, K, p, e, st); break;
-    case 15: launch_one<15, 4, 1, EPI>(xt, wt, M, N, K, p, e, st); break;
-    default: launch_one<16, 4, 1, EPI>(xt, wt, M, N, K, p, e, st); break;
+    case 11: launch_mt<11, EPI>(xt, wt, M, N, K, p, e, st); break;
+    case 12: launch_mt<12, EPI>(xt, wt, M, N, K, p, e, st); break;
+    case 13: launch_mt<13, EPI>(xt, wt, M, N, K, p, e, st); break;
+    case 14: launch_mt<14, EPI>(xt, wt, M, N, K, p, e, st); break;
+    case 15: launch_mt<15, EPI>(xt, wt, M, N, K, p, e, st); break;
+    default: launch_mt<16, EPI>(xt, wt, M, N, K, p, e, st); break;
   }
 }
 
 }  // namespace
 
+// one compute unit's worth of workgroups per 96-column group, no K split: the shapes the mid kernel takes even below 17 rows
+bool gemm_mid_fills_chip(int M, int N, int K) {
+  const MidPlan p = mid_plan(M, N, K, true);
+  return p.splits == 1 && p.groups % 256 == 0;
+}
 int gemm_mid_splits(int M, int N, int K) { return mid_plan(M, N, K, true).splits; }
-int gemm_mid_ssq_chunks(int M, int N) { return mid_plan(M, N, 1024, true).groups; }
+int gemm_mid_ssq_chunks(int M, int N, int K) { return mid_plan(M, N, K, true).groups; }
 int gemm_mid_counters(int max_n) { return (max_n + 63) / 64; }  // 64-column groups are the narrowest
 void gemm_mid_set_target(int wgs) { g_mid_wgs = wgs; }
 
 void launch_gemm_mid(const bf16_t* xt, const bf16_t* wt, int M, int N, int K, const GemmEpi& e, hipStream_t st) {
-  if (M <= 16) { launch_gemm_skinny(xt, wt, weight_pack_rows(N), M, N, K, e, st); return; }  // no instantiation for one row tile
   const MidPlan p = mid_plan(M, N, K, e.kind != EPI_DIRECT);  // EPI_DIRECT has no workspace
   switch (e.kind) {
     case EPI_QKV: launch_epi<EPI_QKV>(xt, wt, M, N, K, p, e, st); break;

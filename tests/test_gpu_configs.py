@@ -43,6 +43,21 @@ def test_twin_replay(device, name, passes):
     print(name, "passes", kinds, "worst relative logit error", r["worst"])
 
 
+@pytest.mark.parametrize("name,rows", [("llada8b_p256_g256", 24), ("llada8b_p256_g256", 40), ("llada8b_p256_g256", 64), ("llada8b_p256_g256", 100),
+                                       ("llada8b_p256_g256", 136), ("llada8b_p256_g256", 160), ("llada8b_p256_g256", 200), ("llada8b_p256_g256", 256),
+                                       ("dream7b_p512_g256", 40), ("dream7b_p512_g256", 150)])
+def test_twin_row_counts(device, name, rows):
+    """One prefill pass of exactly `rows` rows at full widths (prompt of rows - 16 tokens, look-ahead 16), then the first
+    in-block pass: the row counts at which the GEMM dispatcher changes kernel or tile shape, every fused epilogue included."""
+    cfg, _, _, _, _ = _twin(name)
+    W = inputs.make_weights(cfg, seed=0, device=device)
+    prompt = inputs.make_prompts(cfg, 1, rows - 16)[0]
+    r = replay(cfg, W, prompt, 32, dict(SCALED, l_max=8), device, logit_tol=2e-2, max_passes=2)
+    first = [t for t in r["trace"] if t["op"] == "pass"][0]
+    assert first["kind"] == "prefill" and len(first["tokens"]) == rows
+    print(name, rows, "worst relative logit error", r["worst"])
+
+
 def _bf16_dataflow(cfg, W, tokens, device):
     """The pass over `tokens` (no cached prefix) in exact fp32 torch operations with the activations rounded to bf16 at the
     points where a bf16 matrix-core path has to round them (every GEMM input, Q / K / V, the unnormalised attention
