@@ -67,7 +67,7 @@ int choose_kernel(int M, int N, int K, int kind) {
   const int pr = weight_pack_rows(N);
   const bool whole_groups = N % (16 * pr) == 0;
   if (M <= GEMM_SKINNY_MAX_ROWS && kind != EPI_DIRECT && whole_groups) {
-    if (pr == 2 && (M > 16 || (N >= 16384 && gemm_mid_fills_chip(M, N, K)))) return KERNEL_MID;
+    if (pr == 2 && (M > 16 || gemm_mid_fills_chip(M, N, K))) return KERNEL_MID;
     if (pr == 1 && M > 16 && K >= 8192) return KERNEL_MID;
     return KERNEL_SKINNY;
   }

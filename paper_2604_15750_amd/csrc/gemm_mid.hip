@@ -49,7 +49,7 @@ __global__ __launch_bounds__(TPB) void gemm_mid_kernel(const bf16x8* __restrict_
                                                        int kt_per_split, int splits, GemmEpi e) {
   typedef MidShape<MT, CT> SH;
   constexpr int F = SH::F, FW = SH::FW, FR = SH::FR, ROUNDS = SH::ROUNDS;
-  static_assert(2 * (MT + CT) < 64, "two k-tiles in flight must fit the memory counter");
+  static_assert(2 * (CT <= 3 ? 2 : 1) * (MT + CT) < 64, "two steps in flight must fit the memory counter");
   extern __shared__ __align__(16) unsigned char lds[];
   __shared__ int s_last;
   float* s_rinv = (float*)(lds + SH::BODY);  // [MT * 16]
@@ -77,59 +77,75 @@ __global__ __launch_bounds__(TPB) void gemm_mid_kernel(const bf16x8* __restrict_
   for (int r = 0; r < CT; ++r)
 #pragma unroll
     for (int j = 0; j < MT; ++j) acc[r][j] = f32x4{0.f, 0.f, 0.f, 0.f};
-  bf16x8 w[WD][CT], x[2][MT];
+  // a step = KB k-tiles: narrow column groups take two per step, so that a step's loads are still 6 KiB of W
+  constexpr int KB = CT <= 3 ? 2 : 1;
+  bf16x8 w[WD][KB][CT], x[2][KB][MT];
+  const int nsteps = (t1 - t0 + KB - 1) / KB;
+  const bf16x8 zero8 = {0, 0, 0, 0, 0, 0, 0, 0};
 
-  // k-tile t (clamped to the wavefront's last one) -> register set `slot`
-  auto load_x = [&](const int slot, int t) {
-    const int tc = min(t, t1 - 1);
+  // step st of the wavefront (its k-tiles clamped to the wavefront's last one) -> register set `slot`
+  auto load_x = [&](const int slot, int st) {
 #pragma unroll
-    for (int j = 0; j < MT; ++j) x[slot][j] = xptr[((size_t)j * KT + tc) * 64];
+    for (int i = 0; i < KB; ++i) {
+      const int tc = min(t0 + st * KB + i, t1 - 1);
+#pragma unroll
+      for (int j = 0; j < MT; ++j) x[slot][i][j] = xptr[((size_t)j * KT + tc) * 64];
+    }
   };
-  auto load_w = [&](const int slot, int t) {
-    const int tc = min(t, t1 - 1);
+  auto load_w = [&](const int slot, int st) {
 #pragma unroll
-    for (int r = 0; r < CT; ++r) w[slot][r] = wptr[r][(size_t)tc * wstep];
+    for (int i = 0; i < KB; ++i) {
+      const int tc = min(t0 + st * KB + i, t1 - 1);
+#pragma unroll
+      for (int r = 0; r < CT; ++r) w[slot][i][r] = wptr[r][(size_t)tc * wstep];
+    }
   };
-  auto compute = [&](const int ws, const int xs) {
+  auto compute = [&](const int ws, const int xs, int st) {
 #pragma unroll
-    for (int j = 0; j < MT; ++j)
+    for (int i = 0; i < KB; ++i) {
+      const bool past = KB > 1 && t0 + st * KB + i >= t1;  // the surplus k-tile of a ragged last step multiplies zeros
 #pragma unroll
-      for (int r = 0; r < CT; ++r) acc[r][j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(w[ws][r], x[xs][j], acc[r][j], 0, 0, 0);
+      for (int j = 0; j < MT; ++j) {
+        const bf16x8 xv = past ? zero8 : x[xs][i][j];
+#pragma unroll
+        for (int r = 0; r < CT; ++r) acc[r][j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(w[ws][i][r], xv, acc[r][j], 0, 0, 0);
+      }
+    }
   };
-  // step s of a trip (k-tile t): X of the next k-tile first, then W of the one after it, so that the wait for this k-tile's
-  // operands (the oldest loads) leaves W two k-tiles deep and X one k-tile deep in flight; the scheduling barriers keep the
-  // compiler from sinking the loads down to their uses (which it does under register pressure, undoing the prefetch)
-#define MID_STEP(S, t)                   \
+  // step S of a trip: X of the next step first, then W of the one after it, so that the wait for this step's operands (the
+  // oldest loads) leaves W two steps deep and X one step deep in flight; the scheduling barriers keep the compiler from
+  // sinking the loads down to their uses (which it does under register pressure, undoing the prefetch)
+#define MID_STEP(S, st)                  \
   {                                      \
-    load_x(((S) + 1) & 1, (t) + 1);      \
-    load_w(((S) + 2) % WD, (t) + 2);     \
+    load_x(((S) + 1) & 1, (st) + 1);     \
+    load_w(((S) + 2) % WD, (st) + 2);    \
     __builtin_amdgcn_sched_barrier(0);   \
-    compute((S) % WD, (S) & 1);          \
+    compute((S) % WD, (S) & 1, (st));    \
     __builtin_amdgcn_sched_barrier(0);   \
   }
-  if (t0 < t1) {
-    load_x(0, t0);
-    load_w(0, t0);
-    load_w(1, t0 + 1);
+  if (nsteps > 0) {
+    load_x(0, 0);
+    load_w(0, 0);
+    load_w(1, 1);
     // whole trips of 2 WD steps (the X sets alternate, the W sets rotate), then the steps left over
-    int t = t0;
-    for (; t + 2 * WD <= t1; t += 2 * WD) {
-      MID_STEP(0, t)
-      MID_STEP(1, t + 1)
-      MID_STEP(2, t + 2)
-      MID_STEP(3, t + 3)
-      MID_STEP(4, t + 4)
-      MID_STEP(5, t + 5)
+    int st = 0;
+    for (; st + 2 * WD <= nsteps; st += 2 * WD) {
+      MID_STEP(0, st)
+      MID_STEP(1, st + 1)
+      MID_STEP(2, st + 2)
+      MID_STEP(3, st + 3)
+      MID_STEP(4, st + 4)
+      MID_STEP(5, st + 5)
     }
-    if (t < t1) {
-      MID_STEP(0, t)
-      if (t + 1 < t1) {
-        MID_STEP(1, t + 1)
-        if (t + 2 < t1) {
-          MID_STEP(2, t + 2)
-          if (t + 3 < t1) {
-            MID_STEP(3, t + 3)
-            if (t + 4 < t1) MID_STEP(4, t + 4)
+    if (st < nsteps) {
+      MID_STEP(0, st)
+      if (st + 1 < nsteps) {
+        MID_STEP(1, st + 1)
+        if (st + 2 < nsteps) {
+          MID_STEP(2, st + 2)
+          if (st + 3 < nsteps) {
+            MID_STEP(3, st + 3)
+            if (st + 4 < nsteps) MID_STEP(4, st + 4)
           }
         }
       }
@@ -227,17 +243,19 @@ struct MidPlan {
 };
 
 // What the compute units can load through their L2s (W once, X once per column group; about 45 GB/s each, 10 .. 12 TB/s
-// together) bounds these shapes before HBM does.  Wide matrices: column groups as wide as the accumulators allow (128
-// columns up to 112 rows, 96 beyond), K split in two when that still fits the chip in one round.  Narrow ones (O, down):
-// 64-column groups and a K split of three; wider groups would need more splits to fill the chip, and the partial tiles'
-// round trip through memory costs more than the X re-reads saved (measured).
+// together) bounds these shapes before HBM does, and a K split costs a round trip of partial tiles through memory plus a
+// serial tail.  Wide matrices: of the group widths 128 (to 112 rows), 96 and 48 columns, the one that fills the chip's 256
+// compute units best, without a K split if it can (QKV of an 8B model: 256 groups of 48; gate/up: 256 groups of 96).
+// Narrow ones (O, down; at most 256 column tiles): 64-column groups and a four-way K split when K is long (down), 32-column
+// groups and a two-way split when it is short (O); all measured against their alternatives.
 MidPlan mid_plan(int M, int N, int K, bool may_split) {
   MidPlan best;
   double best_fill = -1.;
   const int pr = weight_pack_rows(N), mt = (M + 15) >> 4, KT = K >> 5;
   // accumulators (4 CT MT registers) + three k-tiles of W + two of X within the register file: 128-column groups up to 112 rows
-  const int cts[2] = {pr == 2 ? (mt <= 7 ? 8 : 6) : 4, pr == 2 ? 6 : 4};
-  for (int c = 0; c < 2; ++c) {
+  const int narrow = K >= 8192 || mt > 13 ? 4 : 2;  // short K: the partial tiles of a four-way split cost more than X re-read by twice the groups
+  const int cts[3] = {pr == 2 ? (mt <= 7 ? 8 : 6) : narrow, pr == 2 ? 6 : narrow, pr == 2 ? (mt <= 10 ? 3 : 6) : narrow};
+  for (int c = 0; c < 3; ++c) {
     MidPlan p;
     p.pr = pr; p.mt = mt; p.ct = cts[c];
     p.groups = (N + 16 * p.ct - 1) / (16 * p.ct);
@@ -247,10 +265,11 @@ MidPlan mid_plan(int M, int N, int K, bool may_split) {
     if (s < 1 || !may_split) s = 1;
     p.kps = (KT + s - 1) / s;
     p.splits = (KT + p.kps - 1) / p.kps;  // no empty split
-    // of the two group widths, the one whose workgroups fill the chip's 256 compute units better (the wider on a near tie)
+    // of the group widths, the one whose workgroups fill the chip's 256 compute units best; on a near tie the one without
+    // a K split, then the wider
     const int wgs = p.groups * p.splits;
-    const double fill = (double)wgs / ((wgs + 255) / 256 * 256);
-    if (fill > best_fill + 0.02) { best_fill = fill; best = p; }
+    const double fill = (double)wgs / ((wgs + 255) / 256 * 256) + (p.splits == 1 ? 0.01 : 0.);
+    if (fill > best_fill + 0.005) { best_fill = fill; best = p; }
   }
   return best;
 }
@@ -269,9 +288,12 @@ void launch_one(const bf16_t* xt, const bf16_t* wt, int M, int N, int K, const M
 template <int MT, int EPI>
 void launch_mt(const bf16_t* xt, const bf16_t* wt, int M, int N, int K, const MidPlan& p, const GemmEpi& e, hipStream_t st) {
   if (p.pr == 1) {
-    if constexpr (MT >= 2) launch_one<MT, 4, 1, EPI>(xt, wt, M, N, K, p, e, st);
+    if (p.ct == 2) { if constexpr (MT >= 2 && MT <= 13) launch_one<MT, 2, 1, EPI>(xt, wt, M, N, K, p, e, st); }
+    else if constexpr (MT >= 2) launch_one<MT, 4, 1, EPI>(xt, wt, M, N, K, p, e, st);
   } else if (p.ct == 8) {
     if constexpr (MT <= 7) launch_one<MT, 8, 2, EPI>(xt, wt, M, N, K, p, e, st);
+  } else if (p.ct == 3) {
+    if constexpr (MT <= 10) launch_one<MT, 3, 2, EPI>(xt, wt, M, N, K, p, e, st);
   } else {
     if constexpr (MT <= 10) launch_one<MT, 6, 2, EPI>(xt, wt, M, N, K, p, e, st);
   }
@@ -308,8 +330,9 @@ bool gemm_mid_fills_chip(int M, int N, int K) {
 }
 int gemm_mid_splits(int M, int N, int K) { return mid_plan(M, N, K, true).splits; }
 int gemm_mid_ssq_chunks(int M, int N, int K) { return mid_plan(M, N, K, true).groups; }
-int gemm_mid_counters(int max_n) { return (max_n + 63) / 64; }  // 64-column groups are the narrowest
+int gemm_mid_counters(int max_n) { return (max_n + 31) / 32; }  // 32-column groups are the narrowest
 void gemm_mid_set_target(int wgs) { g_mid_wgs = wgs; }
+
 
 void launch_gemm_mid(const bf16_t* xt, const bf16_t* wt, int M, int N, int K, const GemmEpi& e, hipStream_t st) {
   const MidPlan p = mid_plan(M, N, K, e.kind != EPI_DIRECT);  // EPI_DIRECT has no workspace
