@@ -241,7 +241,7 @@ def main():
                 "mfma_tflops": fl / (ms * 1e-3) / 1e12}
 
     roof = class_roofline(DOMINANT, dom_ms, dom_launches)
-    roof["kernel"] = "gemm_skinny_kernel / gemm_tiled_kernel with the SwiGLU epilogue (gate/up GEMM, every launch of one decode)"
+    roof["kernel"] = "gemm_mid_kernel / gemm_macro_kernel with the SwiGLU epilogue (gate/up GEMM, every launch of one decode)"
     roof["traffic"] = traffic_from_profile(args.workload)
     others = {cls: class_roofline(cls, *prof[cls]) for cls in GEMM_CLASSES}
     # attention against the HBM time of its K/V reads (cached prefix + the span's own rows, every layer); vocabulary statistics
