@@ -107,8 +107,10 @@ int dlm_state_kv_len(const dlm_state* s, int slot);
  *
  * Errors (nothing is launched): DLM_EINVAL (null pointer, n_seqs < 1, offsets not increasing, slot
  * out of range or repeated, span_start != kv_len, commit/kl/save ranges outside the span, a kl row
- * with no retained p^prev, a suffix beyond the positions an earlier pass has covered), DLM_ECAPACITY (rows > max_rows, span beyond max_seq_len, save_count >
- * max_lookahead, n_seqs > max_seqs). */
+ * with no retained p^prev, a suffix beyond the positions an earlier pass has covered),
+ * DLM_ECAPACITY (rows > max_rows, span beyond max_seq_len, save_count > max_lookahead, n_seqs >
+ * max_seqs).  DLM_EHIP: the runtime refused a launch; the state's host bookkeeping is unchanged but
+ * what the kernels that did run wrote (uncommitted cache rows, activations) is unspecified. */
 typedef struct {
   int32_t n_seqs;
   const int32_t* slot;         /* host [n_seqs] state slot of each sequence (NULL: 0, 1, ...)      */

@@ -494,6 +494,8 @@ extern "C" int dlm_step(dlm_state* s, const dlm_step_desc* d, void* stream) {
   int rc = c.dtype == DLM_BF16 ? run_step_bf16(s, d, meta, sm, am, rows, max_seq_rows, st)
                                : run_step_f32(s, d, meta, sm, am, rows, max_seq_rows, st);
   if (rc != DLM_OK) return rc;
+  // a launch that the runtime refused (bad configuration, no resources) would otherwise go unnoticed until a later call
+  DLM_HIP(hipGetLastError());
   for (int b = 0; b < n; ++b) {  // host bookkeeping: commit the prefix, flip the retained-logit buffers
     const int slot = meta.slot[b];
     s->kv_len[slot] += d->commit_len[b];
