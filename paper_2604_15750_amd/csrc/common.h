@@ -1,6 +1,7 @@
 // Internal declarations shared by the HIP sources of libdlm (gfx950 only).
 #pragma once
 #include <hip/hip_runtime.h>
+#include <hip/hip_ext.h>
 #include <stdint.h>
 
 #include "../../include/dlm.h"
@@ -164,6 +165,17 @@ struct GemmEpi {
   bf16_t* out_bf16;
   float* out_f32;
 };
+// The GEMM kernels are launched through hipExtLaunchKernelGGL, which can stamp two events with the kernel's own start and end
+// (the dispatch's timestamps: what a profiler reports, with no marker packets between dependent kernels).  A caller that
+// wants the next GEMM launch of this thread timed sets g_launch_stamp; the launch takes the events and clears it.
+struct LaunchStamp { hipEvent_t start, stop; };
+extern thread_local LaunchStamp g_launch_stamp;
+#define DLM_LAUNCH(kernel, grid, block, lds, st, ...)                                                                           \
+  do {                                                                                                                          \
+    const LaunchStamp ls_ = g_launch_stamp;                                                                                     \
+    g_launch_stamp = LaunchStamp{nullptr, nullptr};                                                                             \
+    hipExtLaunchKernelGGL((kernel), dim3(grid), dim3(block), (unsigned)(lds), (st), ls_.start, ls_.stop, 0, __VA_ARGS__);       \
+  } while (0)
 // Y = X * W^T.  xt: fragment-tiled [Mpad, K]; wt: weights [N, K] as packed by launch_pack_weight.
 void launch_gemm_bf16(const bf16_t* xt, const bf16_t* wt, int M, int N, int K, const GemmEpi& e, hipStream_t st);
 #define GEMM_SKINNY_MAX_ROWS 64

@@ -54,6 +54,8 @@ struct dlm_model {
   std::vector<DevBuf> wqkv, wo, w_gate_up, w_down, norm1, norm2;
 };
 
+thread_local LaunchStamp g_launch_stamp = {nullptr, nullptr};
+
 enum { PC_QKV = 0, PC_O = 1, PC_GATE_UP = 2, PC_DOWN = 3, PC_LM_HEAD = 4, PC_ATTENTION = 5, PC_STATS = 6, PC_OTHER = 7 };
 struct Profile {
   unsigned mask = 0;  // classes whose launches are bracketed by events
@@ -81,18 +83,27 @@ struct dlm_state {
 
 namespace {
 
-struct ProfScope {  // brackets the launches of one kernel class with events when profiling is on
-  Profile& p; hipStream_t st; int cls; bool on; hipEvent_t a = nullptr, b = nullptr;
-  ProfScope(Profile& p_, hipStream_t st_, int cls_, int n_launches = 1) : p(p_), st(st_), cls(cls_), on((p_.mask >> cls_) & 1u) {
+// Times the launches of one kernel class when profiling is on.  A GEMM class is one kernel per scope: its launch stamps the
+// two events itself (kernel start and end, nothing added to the queue).  The other classes are bracketed by recorded events.
+struct ProfScope {
+  Profile& p; hipStream_t st; int cls; bool on, stamped; hipEvent_t a = nullptr, b = nullptr;
+  ProfScope(Profile& p_, hipStream_t st_, int cls_, int n_launches = 1)
+      : p(p_), st(st_), cls(cls_), on((p_.mask >> cls_) & 1u), stamped(cls_ <= PC_LM_HEAD && n_launches == 1) {
     if (!on) return;
     p.launches[cls] += n_launches;
     if (p.pool.empty()) { (void)hipEventCreate(&a); (void)hipEventCreate(&b); }
     else { a = p.pool.back().first; b = p.pool.back().second; p.pool.pop_back(); }
-    (void)hipEventRecord(a, st);
+    if (stamped) g_launch_stamp = LaunchStamp{a, b};
+    else (void)hipEventRecord(a, st);
   }
   ~ProfScope() {
     if (!on) return;
-    (void)hipEventRecord(b, st);
+    if (stamped && g_launch_stamp.start == a) {  // no launch took the events: record them, or reading them would fail
+      g_launch_stamp = LaunchStamp{nullptr, nullptr};
+      (void)hipEventRecord(a, st);
+      stamped = false;
+    }
+    if (!stamped) (void)hipEventRecord(b, st);
     p.pending.push_back({a, b, cls});
   }
 };

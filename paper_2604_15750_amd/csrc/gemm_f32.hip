@@ -49,5 +49,5 @@ __global__ __launch_bounds__(256) void gemm_f32_kernel(const float* __restrict__
 
 void launch_gemm_f32(const float* x, const float* w, float* y, int M, int N, int K, RowScale rs, hipStream_t st) {
   dim3 grid((N + BN - 1) / BN, (M + BM - 1) / BM);
-  gemm_f32_kernel<<<grid, 256, 0, st>>>(x, w, y, M, N, K, rs);
+  DLM_LAUNCH(gemm_f32_kernel, grid, 256, 0, st, x, w, y, M, N, K, rs);
 }

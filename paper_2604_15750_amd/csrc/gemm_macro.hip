@@ -190,7 +190,7 @@ void launch_one(const bf16_t* xt, const bf16_t* wt, int M, int N, int K, const M
     configured = true;
   }
   const int grid = (p.nblocks + 7) / 8 * 8 * p.mblocks;
-  gemm_macro_kernel<WM, WN, PR, EPI><<<grid, TPB, SH::LDS_BYTES, st>>>((const bf16x8*)xt, (const bf16x8*)wt, M, N, K, p.nblocks, p.mblocks, e);
+  DLM_LAUNCH((gemm_macro_kernel<WM, WN, PR, EPI>), grid, TPB, SH::LDS_BYTES, st, (const bf16x8*)xt, (const bf16x8*)wt, M, N, K, p.nblocks, p.mblocks, e);
 }
 
 template <int PR, int EPI>

@@ -265,8 +265,10 @@ MidPlan mid_plan(int M, int N, int K, bool may_split) {
     if (s < 1 || !may_split) s = 1;
     p.kps = (KT + s - 1) / s;
     p.splits = (KT + p.kps - 1) / p.kps;  // no empty split
-    // of the group widths, the one whose workgroups fill the chip's 256 compute units best; on a near tie the one without
-    // a K split, then the wider
+    // more groups of the widest kind than compute units (the LM head): several rounds anyway, the widest re-reads X least
+    if (c == 0 && p.groups >= 256) return p;
+    // otherwise, of the group widths, the one whose workgroups fill the chip's 256 compute units best; on a near tie the
+    // one without a K split, then the wider
     const int wgs = p.groups * p.splits;
     const double fill = (double)wgs / ((wgs + 255) / 256 * 256) + (p.splits == 1 ? 0.01 : 0.);
     if (fill > best_fill + 0.005) { best_fill = fill; best = p; }
@@ -282,7 +284,7 @@ void launch_one(const bf16_t* xt, const bf16_t* wt, int M, int N, int K, const M
     (void)hipFuncSetAttribute((const void*)gemm_mid_kernel<MT, CT, PR, EPI>, hipFuncAttributeMaxDynamicSharedMemorySize, SH::LDS_BYTES);
     configured = true;
   }
-  gemm_mid_kernel<MT, CT, PR, EPI><<<p.groups * p.splits, TPB, SH::LDS_BYTES, st>>>((const bf16x8*)xt, (const bf16x8*)wt, M, N, K, p.kps, p.splits, e);
+  DLM_LAUNCH((gemm_mid_kernel<MT, CT, PR, EPI>), p.groups * p.splits, TPB, SH::LDS_BYTES, st, (const bf16x8*)xt, (const bf16x8*)wt, M, N, K, p.kps, p.splits, e);
 }
 
 template <int MT, int EPI>

@@ -233,7 +233,7 @@ Plan plan(int M, int N, int K, bool may_split = true) {
 template <int MT, int EPI>
 void launch_mt(const bf16_t* xt, const bf16_t* wt, int M, int N, int K, const Plan& p, const GemmEpi& e, hipStream_t st) {
   const int grid = (p.groups + 7) / 8 * 8 * p.splits * p.mblocks;
-#define GO(TR, PR) gemm_tiled_kernel<MT, TR, PR, EPI><<<grid, TPB, 0, st>>>((const bf16x8*)xt, (const bf16x8*)wt, M, N, K, p.kps, p.splits, p.groups, p.mblocks, e)
+#define GO(TR, PR) DLM_LAUNCH((gemm_tiled_kernel<MT, TR, PR, EPI>), grid, TPB, 0, st, (const bf16x8*)xt, (const bf16x8*)wt, M, N, K, p.kps, p.splits, p.groups, p.mblocks, e)
   if (p.pr == 1) GO(2, 1);
   else if (p.tr == 2) GO(2, 2);
   else GO(4, 2);

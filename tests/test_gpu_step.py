@@ -282,3 +282,48 @@ def test_step_errors_leave_state_untouched(device):
     torch.cuda.synchronize()
     state.close()
     model.close()
+
+
+@pytest.mark.parametrize("which", ["f32", "bf16"])
+def test_profile_classes_time_their_launches(device, which):
+    """dlm_profile_enable / dlm_profile_read: every class counts its launches, the times are positive and together no more
+    than the wall time of the passes, a masked class stays at zero, and profiling changes no output bit."""
+    import time
+    cfg = inputs.WORKLOADS["tiny_f32_p64_g64"][0] if which == "f32" else MID
+    W = inputs.make_weights(cfg, seed=0, device=device)
+    model = api.Model(cfg, W)
+    rows, passes = 40, 5
+    state = api.State(model, 1, 64, rows, 0)
+    out = api.StepOutputs(rows, cfg["vocab"], model.torch_dtype, device)
+    tokens = torch.from_numpy(inputs.make_prompts(cfg, 1, 64)[0].astype(np.int32)).to(device)
+
+    def run():
+        for _ in range(passes):
+            api.dlm_step(state, tokens, out, [0, rows], [0], [0], [0])
+        torch.cuda.synchronize()
+        return out.logits[:rows].clone(), out.entropy[:rows].clone()
+
+    plain = run()
+    state.profile_enable(True)
+    state.profile_read(reset=True)
+    t0 = time.perf_counter()
+    timed = run()
+    wall_ms = (time.perf_counter() - t0) * 1e3
+    prof = state.profile_read(reset=True)
+    L = cfg["n_layers"]
+    for name, per_pass in (("gemm_qkv", L), ("gemm_o", L), ("gemm_gate_up", L), ("gemm_down", L), ("gemm_lm_head", 1), ("attention", L),
+                           ("vocab_stats", 1)):
+        ms, n = prof[name]
+        assert n == per_pass * passes and ms > 0, (name, prof[name])
+    assert sum(ms for ms, _ in prof.values()) <= wall_ms, (prof, wall_ms)
+    state.profile_enable(["gemm_gate_up"])
+    only = run()
+    prof = state.profile_read(reset=True)
+    assert prof["gemm_gate_up"][1] == L * passes and prof["gemm_gate_up"][0] > 0
+    assert all(v == (0.0, 0) for k, v in prof.items() if k != "gemm_gate_up"), prof
+    state.profile_enable(False)
+    for a, b in ((plain, timed), (plain, only)):
+        assert torch.equal(a[0].view(torch.int16 if which == "bf16" else torch.int32), b[0].view(torch.int16 if which == "bf16" else torch.int32))
+        assert torch.equal(a[1], b[1])
+    state.close()
+    model.close()
