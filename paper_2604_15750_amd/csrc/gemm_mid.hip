@@ -1,14 +1,15 @@
-// Mid-size bf16 GEMM (65 .. 160 rows: a block plus its look-ahead window, a few packed blocks; from 17 rows for some shapes):
+// Mid-size bf16 GEMM (65 .. 160 rows: a block plus its look-ahead window, a few packed blocks; fewer rows where its wide
+// column groups pay, see choose_kernel in gemm_bf16.hip):
 // Y[M,N] = X[M,K] * W[N,K]^T, fp32 accumulation, epilogue fused.
 //
 // At these row counts W is still the larger operand, but every column group re-reads X, so the groups
 // have to be wide.  A workgroup of four wavefronts owns ALL the rows (MT row tiles) of CT adjacent
-// column tiles (64 .. 128 columns) and a range of K; its wavefronts split that range among themselves,
+// column tiles (32 .. 128 columns) and a range of K; its wavefronts split that range among themselves,
 // and each multiplies its k-tiles of the CT W fragments against all MT X fragments (CT MT products
 // per CT + MT fragments fetched), everything in registers:
-//   * W goes HBM -> registers, the k-tile in use and the two after it (a wavefront keeps 2 CT KiB of W
-//     in flight, a workgroup 32 .. 64 KiB: what it takes to keep HBM busy with 128 .. 256 workgroups);
-//     X goes L2 -> registers one k-tile ahead, issued BEFORE the W loads of the same step, so that
+//   * W goes HBM -> registers, the step in use and the two after it (a step is one k-tile, two for the narrowest
+//     groups; a wavefront keeps 6 .. 16 KiB of W in flight, a workgroup 24 .. 64 KiB: what it takes to keep HBM busy with 128 .. 256 workgroups);
+//     X goes L2 -> registers one step ahead, issued BEFORE the W loads of the same step, so that
 //     waiting for it never waits for younger W loads (the memory counter retires in order);
 //   * no barrier, no LDS inside the loop: a wavefront never waits for another.  (X through
 //     direct-to-LDS loads would save a third of the registers, but the compiler then no longer counts
@@ -127,6 +128,11 @@ __global__ __launch_bounds__(TPB) void gemm_mid_kernel(const bf16x8* __restrict_
     load_x(0, 0);
     load_w(0, 0);
     load_w(1, 1);
+  }
+  // 1/rms of the input rows, needed only by the epilogue: fetched while the first k-tiles are in flight (published by the
+  // barriers of the reduction)
+  if (EPI != EPI_RESID) block_rinv<TPB>(e.rs, 0, min(M, MT * 16), s_rinv);
+  if (nsteps > 0) {
     // whole trips of 2 WD steps (the X sets alternate, the W sets rotate), then the steps left over
     int st = 0;
     for (; st + 2 * WD <= nsteps; st += 2 * WD) {
@@ -155,7 +161,6 @@ __global__ __launch_bounds__(TPB) void gemm_mid_kernel(const bf16x8* __restrict_
 
   // ---- the four partial accumulators -> one finished (or, with a K split, one partial) value per output fragment
   const int g = lane >> 4, ml = lane & 15;
-  if (EPI != EPI_RESID) block_rinv<TPB>(e.rs, 0, min(M, MT * 16), s_rinv);  // published by the rounds' barriers
   f32x4* red = (f32x4*)lds;  // [NWV][FR][64]
   const size_t stride = (size_t)M * N;
   float* mine = e.part + split * stride;
