@@ -72,6 +72,9 @@ __global__ __launch_bounds__(TPB) void gemm_mid_kernel(const bf16x8* __restrict_
     wptr[r] = PR == 2 ? wt + ((size_t)(nt >> 1) * KT * 2 + (nt & 1)) * 64 + lane : wt + (size_t)nt * KT * 64 + lane;
   }
   const bf16x8* xptr = xt + lane;  // fragment (j, t) = xptr[(j * KT + t) * 64]
+  // In the last row tile, lanes whose row does not exist re-read row 0 of their k-group instead of fetching lines of their
+  // own (a fragment's 128-byte lines hold 8 rows each: a block of 8 rows reads half of them); what they get is never stored.
+  const bf16x8* xptr_last = xt + ((MT - 1) * 16 + (lane & 15) < M ? lane : (lane & ~15));
 
   f32x4 acc[CT][MT];
 #pragma unroll
@@ -90,7 +93,7 @@ __global__ __launch_bounds__(TPB) void gemm_mid_kernel(const bf16x8* __restrict_
     for (int i = 0; i < KB; ++i) {
       const int tc = min(t0 + st * KB + i, t1 - 1);
 #pragma unroll
-      for (int j = 0; j < MT; ++j) x[slot][i][j] = xptr[((size_t)j * KT + tc) * 64];
+      for (int j = 0; j < MT; ++j) x[slot][i][j] = (j == MT - 1 ? xptr_last : xptr)[((size_t)j * KT + tc) * 64];
     }
   };
   auto load_w = [&](const int slot, int st) {

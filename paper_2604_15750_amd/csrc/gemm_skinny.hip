@@ -5,7 +5,10 @@
 // registers, and multiplies them on the matrix cores; the accumulators are added through LDS in
 // wavefront order (deterministic).  No workgroup waits for another: no workspace, no counter, no
 // serial tail.  With 256 .. 768 workgroups all resident at once, HBM stays busy from the first load
-// to the last.
+// to the last.  Every workgroup re-reads X through its L2, which costs as much of the compute units'
+// load bandwidth as W itself for the narrow matrices, so lanes whose row does not exist fetch no line of
+// their own (they re-read a row that exists): a fragment's 128-byte lines hold 8 rows each, and a block
+// of 8 rows (the minimum block length) reads half of them.
 #include "gemm_epilogue.h"
 
 namespace {
@@ -22,6 +25,8 @@ __global__ __launch_bounds__(NWV * 64) void gemm_skinny_kernel(const bf16x8* __r
   const int per = (KT + NWV - 1) / NWV;
   const int t_begin = wave * per, t_end = min(KT, t_begin + per);
   const bf16x8 zero8 = {0, 0, 0, 0, 0, 0, 0, 0};
+  // lanes of the last row tile whose row does not exist re-read row 0 of their k-group (whatever they get is never stored)
+  const int xlane_last = (MTILES - 1) * 16 + (lane & 15) < M ? lane : (lane & ~15);
   const bf16x8* wbase = wt + (size_t)blockIdx.x * KT * R * 64 + lane;  // the workgroup's R tiles are one interleaved run
 
   f32x4 acc[R][MT];
@@ -39,7 +44,7 @@ __global__ __launch_bounds__(NWV * 64) void gemm_skinny_kernel(const bf16x8* __r
 #pragma unroll
       for (int r = 0; r < R; ++r) wreg[buf][i][r] = ok ? wbase[((size_t)t * R + r) * 64] : zero8;
 #pragma unroll
-      for (int j = 0; j < MT; ++j) xreg[buf][i][j] = (ok && j < MTILES) ? xt[((size_t)j * KT + t) * 64 + lane] : zero8;
+      for (int j = 0; j < MT; ++j) xreg[buf][i][j] = (ok && j < MTILES) ? xt[((size_t)j * KT + t) * 64 + (j == MTILES - 1 ? xlane_last : lane)] : zero8;
     }
   };
   auto compute = [&](int buf) {
