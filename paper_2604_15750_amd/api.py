@@ -132,7 +132,7 @@ class Model:
         self.torch_dtype = torch.float32 if dt == DLM_F32 else torch.bfloat16
 
     def close(self):
-        if self.handle:
+        if self.handle and lib is not None:  # at interpreter shutdown the module's globals may already be gone
             lib().dlm_model_destroy(self.handle)
             self.handle = None
 
@@ -176,7 +176,7 @@ class State:
         return {name: (ms[i], n[i]) for i, name in enumerate(self.PROFILE_CLASSES)}
 
     def close(self):
-        if self.handle:
+        if self.handle and lib is not None:
             lib().dlm_state_destroy(self.handle)
             self.handle = None
 

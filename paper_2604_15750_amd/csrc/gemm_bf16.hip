@@ -59,7 +59,8 @@ __global__ void pack_act_kernel(const bf16x8* __restrict__ x, bf16x8* __restrict
 //   mid     65 .. 160 rows (narrow matrices to 256); and below that where its wider column groups pay: from 17 rows for
 //           wide matrices (QKV, gate/up) and for narrow ones whose K is long enough for a four-way split (down) - there
 //           the skinny kernel's re-reads of X by every 16- or 32-column group cost more than W itself - and at any row
-//           count when its 96-column groups are exactly one per compute unit (gate/up of an 8B model);
+//           count when its 96-column groups are exactly one per compute unit (gate/up of an 8B model), or when the skinny
+//           kernel would need a second round for a few column tiles (QKV of a 7B model with grouped-query heads);
 //   macro   more rows than that when the matrix has enough 128 x 256 tiles of its own (wide from 161 rows, narrow from 257);
 //   tiled   the rest, and the LM head up to 64 rows (no workspace: no K split).
 enum { KERNEL_SKINNY, KERNEL_MID, KERNEL_MACRO, KERNEL_TILED };
@@ -69,6 +70,9 @@ int choose_kernel(int M, int N, int K, int kind) {
   if (M <= GEMM_SKINNY_MAX_ROWS && kind != EPI_DIRECT && whole_groups) {
     if (pr == 2 && (M > 16 || gemm_mid_fills_chip(M, N, K))) return KERNEL_MID;
     if (pr == 1 && M > 16 && K >= 8192) return KERNEL_MID;
+    // a narrow matrix with a few more than 256 column tiles: the skinny kernel's one-tile workgroups would run a second,
+    // nearly empty round over the compute units; 32-column groups fit in one
+    if (pr == 1 && M <= 16 && (N >> 4) > 256 && (N >> 4) <= 384) return KERNEL_MID;
     return KERNEL_SKINNY;
   }
   if (M > GEMM_SKINNY_MAX_ROWS && M <= (pr == 1 ? GEMM_MID_MAX_ROWS_NARROW : GEMM_MID_MAX_ROWS) && whole_groups) return KERNEL_MID;

@@ -261,13 +261,14 @@ MidPlan mid_plan(int M, int N, int K, bool may_split) {
   double best_fill = -1.;
   const int pr = weight_pack_rows(N), mt = (M + 15) >> 4, KT = K >> 5;
   // accumulators (4 CT MT registers) + three k-tiles of W + two of X within the register file: 128-column groups up to 112 rows
-  const int narrow = K >= 8192 || mt > 13 ? 4 : 2;  // short K: the partial tiles of a four-way split cost more than X re-read by twice the groups
+  const int narrow = (K >= 8192 && mt > 1) || mt > 13 ? 4 : 2;  // short K: the partial tiles of a four-way split cost more than X re-read by twice the groups
   const int cts[3] = {pr == 2 ? (mt <= 7 ? 8 : 6) : narrow, pr == 2 ? 6 : narrow, pr == 2 ? (mt <= 10 ? 3 : 6) : narrow};
   for (int c = 0; c < 3; ++c) {
     MidPlan p;
     p.pr = pr; p.mt = mt; p.ct = cts[c];
     p.groups = (N + 16 * p.ct - 1) / (16 * p.ct);
     int s = pr == 2 ? 256 / p.groups : (g_mid_wgs + p.groups / 2) / p.groups;
+    if (pr == 1 && mt == 1) s = 1;  // one row tile of a narrow matrix comes here only to avoid a second round of 16-column workgroups
     if (s > (pr == 2 ? 2 : 4)) s = pr == 2 ? 2 : 4;  // a short serial tail for the last arriver, and little traffic of partial tiles
     if (s > KT / 16) s = KT / 16;     // at least four k-tiles per wavefront
     if (s < 1 || !may_split) s = 1;
@@ -298,7 +299,7 @@ void launch_one(const bf16_t* xt, const bf16_t* wt, int M, int N, int K, const M
 template <int MT, int EPI>
 void launch_mt(const bf16_t* xt, const bf16_t* wt, int M, int N, int K, const MidPlan& p, const GemmEpi& e, hipStream_t st) {
   if (p.pr == 1) {
-    if (p.ct == 2) { if constexpr (MT >= 2 && MT <= 13) launch_one<MT, 2, 1, EPI>(xt, wt, M, N, K, p, e, st); }
+    if (p.ct == 2) { if constexpr (MT <= 13) launch_one<MT, 2, 1, EPI>(xt, wt, M, N, K, p, e, st); }
     else if constexpr (MT >= 2) launch_one<MT, 4, 1, EPI>(xt, wt, M, N, K, p, e, st);
   } else if (p.ct == 8) {
     if constexpr (MT <= 7) launch_one<MT, 8, 2, EPI>(xt, wt, M, N, K, p, e, st);

@@ -35,7 +35,7 @@ def _rowtol(ref, rel, floor=0.0):
                                    (65, 4096, 4096), (81, 24576, 512), (97, 4096, 1024), (112, 12288, 2048), (113, 4096, 12288),
                                    (136, 12288, 4096), (150, 8224, 1024), (160, 4096, 4096), (80, 126464, 64), (144, 64, 96),
                                    (161, 4096, 4096), (200, 1024, 2048), (225, 4096, 12288), (256, 4096, 512),
-                                   (17, 16384, 256), (40, 24576, 1024), (33, 4096, 8192), (64, 256, 12288),
+                                   (17, 16384, 256), (40, 24576, 1024), (33, 4096, 8192), (64, 256, 12288), (8, 4608, 3584), (16, 6144, 512),
                                    # more than 256 rows: the macro-tile kernel (ragged rows, column tails, both weight packings, short K)
                                    (257, 4096, 4096), (513, 8224, 1024), (700, 160, 4096 + 64), (1100, 640, 64), (384, 12288, 32)])
 def test_gemm_bf16(device, M, N, K):
