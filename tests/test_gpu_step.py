@@ -327,3 +327,29 @@ def test_profile_classes_time_their_launches(device, which):
         assert torch.equal(a[1], b[1])
     state.close()
     model.close()
+
+
+def test_tiny_f32_full_batch_of_32(device):
+    """The largest batch a state holds (32 sequences) packed into shared launches, each decoding exactly as it does alone."""
+    cfg = inputs.TINY
+    W = _weights(cfg, 0, device)
+    prompts = inputs.make_prompts(cfg, 32, 24, seed=3)
+    got = _free_run_matches(cfg, W, prompts, 24, dict(TINY_SETS["scaled"], lam=1.0, l_max=8), device, exact=True)
+    assert got["launches"] < sum(got["nfe"]) / 8
+
+
+def test_tiny_f32_ragged_batch_with_visible_suffix(device):
+    """Packed sequences with the look-ahead suffix visible to in-block passes: every sequence attends to its own suffix only."""
+    cfg = inputs.TINY
+    W = _weights(cfg, 0, device)
+    prompts = inputs.make_prompts(cfg, 4, 40, seed=11)
+    _free_run_matches(cfg, W, prompts, 56, dict(TINY_SETS["dual_cache"], l_max=16), device, exact=True)
+
+
+@pytest.mark.parametrize("P,N", [(1, 1), (3, 5), (64, 8), (5, 9)])
+def test_tiny_f32_degenerate_lengths(device, P, N):
+    """Prompts of one token, generations shorter than L_min or than the look-ahead window: the window and the last block
+    are cut at the end of the sequence."""
+    cfg = inputs.TINY
+    W = _weights(cfg, 0, device)
+    _free_run_matches(cfg, W, inputs.make_prompts(cfg, 1, P, seed=P + N), N, TINY_SETS["scaled"], device, exact=True)
