@@ -7,8 +7,8 @@
 // column tiles (32 .. 128 columns) and a range of K; its wavefronts split that range among themselves,
 // and each multiplies its k-tiles of the CT W fragments against all MT X fragments (CT MT products
 // per CT + MT fragments fetched), everything in registers:
-//   * W goes HBM -> registers, the step in use and the two after it (a step is one k-tile, two for the narrowest
-//     groups; a wavefront keeps 6 .. 16 KiB of W in flight, a workgroup 24 .. 64 KiB: what it takes to keep HBM busy with 128 .. 256 workgroups);
+//   * W goes HBM -> registers, the step in use and the two to four after it, as many as the registers hold (a step is one
+//     k-tile, two for the narrowest groups; a wavefront keeps 8 .. 24 KiB of W in flight, a workgroup 32 .. 96 KiB: what it takes to keep HBM busy with 128 .. 256 workgroups);
 //     X goes L2 -> registers one step ahead, issued BEFORE the W loads of the same step, so that
 //     waiting for it never waits for younger W loads (the memory counter retires in order);
 //   * no barrier, no LDS inside the loop: a wavefront never waits for another.  (X through
@@ -21,11 +21,14 @@
 // the last ticket adds them in split order (the protocol of gemm_tiled.hip; a wavefront fetches the
 // same split of all its output fragments in a single trip to memory).
 #include "gemm_epilogue.h"
+#include <type_traits>
 
 namespace {
 
 constexpr int TPB = 256, NWV = 4;
-constexpr int WD = 3;  // k-tiles per ring: one in use, two in flight
+#ifndef MID_WD_MAX
+#define MID_WD_MAX 4
+#endif
 
 typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
 constexpr int SC1 = 16;  // cache-policy bit of the raw-buffer builtins: device scope
@@ -36,6 +39,14 @@ __device__ inline __amdgpu_buffer_rsrc_t part_rsrc(const float* base) {
 
 template <int MT, int CT>
 struct MidShape {
+  static constexpr int KB = CT <= 3 ? 2 : 1;  // k-tiles per step: narrow column groups take two, so that a step's loads are still 6 KiB of W
+  // steps of W per register ring (one in use, the others in flight): as many as fit beside the accumulators and two steps of
+  // X in about 370 registers, and whose loads the memory counter can count; 3 .. MID_WD_MAX
+  static constexpr int WD_FIT = (92 - CT * MT - 2 * KB * MT) / (KB * CT);
+  static constexpr int WD_CNT = (63 / KB - MT) / CT + 1;
+  static constexpr int WD_ = WD_FIT < WD_CNT ? WD_FIT : WD_CNT;
+  static constexpr int WD = WD_ < 3 ? 3 : WD_ > MID_WD_MAX ? MID_WD_MAX : WD_;
+  static constexpr int TRIP = WD % 2 ? 2 * WD : WD;  // steps after which both the W ring and the two X sets are back where they started
   static constexpr int F = CT * MT;                 // output fragments of a workgroup
   static constexpr int FW = (F + NWV - 1) / NWV;    // ... finished by one wavefront
   static constexpr int FR = F < 32 ? (F + 3) / 4 * 4 : 32;  // fragments per reduction round (a multiple of 4: fragment f stays with wavefront f % 4)
@@ -50,7 +61,8 @@ __global__ __launch_bounds__(TPB) void gemm_mid_kernel(const bf16x8* __restrict_
                                                        int kt_per_split, int splits, GemmEpi e) {
   typedef MidShape<MT, CT> SH;
   constexpr int F = SH::F, FW = SH::FW, FR = SH::FR, ROUNDS = SH::ROUNDS;
-  static_assert(2 * (CT <= 3 ? 2 : 1) * (MT + CT) < 64, "two steps in flight must fit the memory counter");
+  constexpr int KB = SH::KB, WD = SH::WD, TRIP = SH::TRIP;
+  static_assert(KB * (MT + (WD - 1) * CT) < 64, "the loads in flight must fit the memory counter");
   extern __shared__ __align__(16) unsigned char lds[];
   __shared__ int s_last;
   float* s_rinv = (float*)(lds + SH::BODY);  // [MT * 16]
@@ -81,14 +93,12 @@ __global__ __launch_bounds__(TPB) void gemm_mid_kernel(const bf16x8* __restrict_
   for (int r = 0; r < CT; ++r)
 #pragma unroll
     for (int j = 0; j < MT; ++j) acc[r][j] = f32x4{0.f, 0.f, 0.f, 0.f};
-  // a step = KB k-tiles: narrow column groups take two per step, so that a step's loads are still 6 KiB of W
-  constexpr int KB = CT <= 3 ? 2 : 1;
   bf16x8 w[WD][KB][CT], x[2][KB][MT];
   const int nsteps = (t1 - t0 + KB - 1) / KB;
   const bf16x8 zero8 = {0, 0, 0, 0, 0, 0, 0, 0};
 
   // step st of the wavefront (its k-tiles clamped to the wavefront's last one) -> register set `slot`
-  auto load_x = [&](const int slot, int st) {
+  auto load_x = [&](const int slot, int st) __attribute__((always_inline)) {
 #pragma unroll
     for (int i = 0; i < KB; ++i) {
       const int tc = min(t0 + st * KB + i, t1 - 1);
@@ -96,7 +106,7 @@ __global__ __launch_bounds__(TPB) void gemm_mid_kernel(const bf16x8* __restrict_
       for (int j = 0; j < MT; ++j) x[slot][i][j] = (j == MT - 1 ? xptr_last : xptr)[((size_t)j * KT + tc) * 64];
     }
   };
-  auto load_w = [&](const int slot, int st) {
+  auto load_w = [&](const int slot, int st) __attribute__((always_inline)) {
 #pragma unroll
     for (int i = 0; i < KB; ++i) {
       const int tc = min(t0 + st * KB + i, t1 - 1);
@@ -104,7 +114,7 @@ __global__ __launch_bounds__(TPB) void gemm_mid_kernel(const bf16x8* __restrict_
       for (int r = 0; r < CT; ++r) w[slot][i][r] = wptr[r][(size_t)tc * wstep];
     }
   };
-  auto compute = [&](const int ws, const int xs, int st) {
+  auto compute = [&](const int ws, const int xs, int st) __attribute__((always_inline)) {
 #pragma unroll
     for (int i = 0; i < KB; ++i) {
       const bool past = KB > 1 && t0 + st * KB + i >= t1;  // the surplus k-tile of a ragged last step multiplies zeros
@@ -116,51 +126,50 @@ __global__ __launch_bounds__(TPB) void gemm_mid_kernel(const bf16x8* __restrict_
       }
     }
   };
-  // step S of a trip: X of the next step first, then W of the one after it, so that the wait for this step's operands (the
-  // oldest loads) leaves W two steps deep and X one step deep in flight; the scheduling barriers keep the compiler from
-  // sinking the loads down to their uses (which it does under register pressure, undoing the prefetch)
-#define MID_STEP(S, st)                  \
-  {                                      \
-    load_x(((S) + 1) & 1, (st) + 1);     \
-    load_w(((S) + 2) % WD, (st) + 2);    \
-    __builtin_amdgcn_sched_barrier(0);   \
-    compute((S) % WD, (S) & 1, (st));    \
-    __builtin_amdgcn_sched_barrier(0);   \
-  }
+  // step S of a trip: X of the next step first, then W of the step WD - 1 ahead, so that the wait for this step's operands
+  // (the oldest loads) leaves W WD - 1 steps deep and X one step deep in flight; the scheduling barriers keep the compiler
+  // from sinking the loads down to their uses (which it does under register pressure, undoing the prefetch)
+  auto step = [&](auto Sc, int st) __attribute__((always_inline)) {
+    constexpr int S = decltype(Sc)::value;
+    load_x((S + 1) & 1, st + 1);
+    load_w((S + WD - 1) % WD, st + WD - 1);
+    __builtin_amdgcn_sched_barrier(0);
+    compute(S % WD, S & 1, st);
+    __builtin_amdgcn_sched_barrier(0);
+  };
+  // (every lambda here is forced inline: left to its own judgement the compiler keeps the largest variants' steps as
+  // functions, and the operand rings, passed by reference, then live in scratch memory)
+  // whole trips: TRIP steps in a row; the steps left over: nested, not skippable one by one (a path around a step's loads is
+  // one the compiler's count of outstanding loads cannot follow: it would wait for all of them)
+  auto trip = [&](auto self, auto Ic, int st) __attribute__((always_inline)) {
+    constexpr int I = decltype(Ic)::value;
+    if constexpr (I < TRIP) {
+      step(Ic, st + I);
+      self(self, std::integral_constant<int, I + 1>{}, st);
+    }
+  };
+  auto rest = [&](auto self, auto Ic, int st) __attribute__((always_inline)) {
+    constexpr int I = decltype(Ic)::value;
+    if constexpr (I < TRIP - 1) {
+      if (st + I < nsteps) {
+        step(Ic, st + I);
+        self(self, std::integral_constant<int, I + 1>{}, st);
+      }
+    }
+  };
   if (nsteps > 0) {
     load_x(0, 0);
-    load_w(0, 0);
-    load_w(1, 1);
+#pragma unroll
+    for (int i = 0; i < WD - 1; ++i) load_w(i, i);
   }
   // 1/rms of the input rows, needed only by the epilogue: fetched while the first k-tiles are in flight (published by the
   // barriers of the reduction)
   if (EPI != EPI_RESID) block_rinv<TPB>(e.rs, 0, min(M, MT * 16), s_rinv);
   if (nsteps > 0) {
-    // whole trips of 2 WD steps (the X sets alternate, the W sets rotate), then the steps left over
     int st = 0;
-    for (; st + 2 * WD <= nsteps; st += 2 * WD) {
-      MID_STEP(0, st)
-      MID_STEP(1, st + 1)
-      MID_STEP(2, st + 2)
-      MID_STEP(3, st + 3)
-      MID_STEP(4, st + 4)
-      MID_STEP(5, st + 5)
-    }
-    if (st < nsteps) {
-      MID_STEP(0, st)
-      if (st + 1 < nsteps) {
-        MID_STEP(1, st + 1)
-        if (st + 2 < nsteps) {
-          MID_STEP(2, st + 2)
-          if (st + 3 < nsteps) {
-            MID_STEP(3, st + 3)
-            if (st + 4 < nsteps) MID_STEP(4, st + 4)
-          }
-        }
-      }
-    }
+    for (; st + TRIP <= nsteps; st += TRIP) trip(trip, std::integral_constant<int, 0>{}, st);
+    rest(rest, std::integral_constant<int, 0>{}, st);
   }
-#undef MID_STEP
 
   // ---- the four partial accumulators -> one finished (or, with a K split, one partial) value per output fragment
   const int g = lane >> 4, ml = lane & 15;
