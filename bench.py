@@ -161,7 +161,8 @@ def main():
     ap.add_argument("--thresholds", default="paper", choices=["paper", "scaled"],
                     help="paper: the defaults of Sec. 5.1; scaled: thresholds placed inside the confidence range of a random-init model, "
                          "so that CAP-Decoding commits several tokens per pass")
-    ap.add_argument("--micro", default="", choices=["", "vocab_stats"], help="time one kernel alone instead of the decode")
+    ap.add_argument("--micro", default="", choices=["", "vocab_stats", "peaks"],
+                    help="time one kernel alone instead of the decode (peaks: a plain HBM read and a matrix-core loop, what the GPU achieves)")
     ap.add_argument("--rows", type=int, default=3072, help="--micro: rows of the pass (3072 = 16 sequences x 192 rows, the widest batched pass)")
     ap.add_argument("--prev", type=int, default=1, help="--micro vocab_stats: 1 = every row is a KL row (reads the retained logits too)")
     ap.add_argument("--copy-calibration", action="store_true",
@@ -173,6 +174,13 @@ def main():
 
     if args.micro == "vocab_stats":
         micro_vocab_stats(args)
+        return
+    if args.micro == "peaks":
+        import torch
+        from paper_2604_15750_amd import api
+        buf = torch.empty(2 << 30, dtype=torch.uint8, device="cuda:0")
+        print(json.dumps({"micro": "peaks", "hbm_read_GBs": api.probe_hbm_read(buf, reps=20), "hbm_published_GBs": HBM_PEAK_GBS,
+                          "mfma_bf16_TFLOPs": api.probe_mfma_bf16(reps=10), "mfma_bf16_published_TFLOPs": 2500.0}))
         return
 
     import torch
@@ -243,6 +251,13 @@ def main():
     roof = class_roofline(DOMINANT, dom_ms, dom_launches)
     roof["kernel"] = "gemm_mid_kernel / gemm_macro_kernel with the SwiGLU epilogue (gate/up GEMM, every launch of one decode)"
     roof["traffic"] = traffic_from_profile(args.workload)
+    # what this GPU achieves on the same resources with kernels that do nothing else (a plain streaming read of 2 GiB; matrix-core
+    # products out of registers): the published peaks are not reachable by any kernel
+    probe_buf = torch.empty(2 << 30, dtype=torch.uint8, device=dev)
+    achievable = {"hbm_read_GBs": api.probe_hbm_read(probe_buf, reps=10), "mfma_bf16_TFLOPs": api.probe_mfma_bf16(reps=5)}
+    del probe_buf
+    roof["achievable_peak"] = achievable["hbm_read_GBs"]
+    roof["frac_of_achievable"] = roof["achieved"] / achievable["hbm_read_GBs"]
     others = {cls: class_roofline(cls, *prof[cls]) for cls in GEMM_CLASSES}
     # attention against the HBM time of its K/V reads (cached prefix + the span's own rows, every layer); vocabulary statistics
     # against one read of the logits (plus the retained logits on KL rows)
@@ -272,6 +287,7 @@ def main():
         "nfe": passes / B, "tokens_per_pass": B * N / passes, "launches_per_decode": res["launches"],
         "denoise_step_ms": elapsed / args.steps * 1e3 / res["launches"],
         "roofline": roof,
+        "achievable": achievable,
         "roofline_other_kernels": others,
         "decode_floor_ms": floor_ms, "decode_floor_frac": floor_ms / (elapsed / args.steps * 1e3),
         "kernel_ms_per_decode": {k: v[0] for k, v in prof.items()},

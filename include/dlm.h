@@ -213,6 +213,18 @@ int dlm_gemm_nt(const void* x, const void* w, void* y, int M, int N, int K, int 
 int dlm_attention(const void* q, const void* k, const void* v, void* out, int A, int T, int n_q, int n_kv,
                   int head_dim, int dtype, void* stream);
 
+/* ---- what the GPU achieves on the resources the rooflines are drawn against -------------------
+ * For callers that report measurements (bench.py): kernels that do nothing but the one thing, timed
+ * with events on `stream`, which is synchronised before the call returns.
+ *
+ * dlm_probe_hbm_read: streams `bytes` of DEVICE memory at src `reps` times (16-byte loads, every byte
+ * once per repetition; use a buffer larger than the 256 MB memory-side cache) and reports the read
+ * rate in GB/s.  dlm_probe_mfma_bf16: `reps` launches of independent 16x16x32 bf16 products out of
+ * registers on every SIMD, reports TFLOP/s.
+ * Errors: DLM_EINVAL, DLM_ESHAPE (fewer than 16 MiB), DLM_ENOMEM, DLM_EHIP. */
+int dlm_probe_hbm_read(const void* src, size_t bytes, int reps, double* gb_per_s, void* stream);
+int dlm_probe_mfma_bf16(int reps, double* tflop_per_s, void* stream);
+
 /* Per-kernel-class timing of dlm_step: the launches of every class whose bit is set in class_mask
  * are bracketed by HIP events on the caller's stream (0 switches the timing off; events cost queue
  * time, so bracket few classes when a class's own duration matters).  dlm_profile_read synchronises

@@ -55,7 +55,7 @@ class dlm_select_params(C.Structure):
 
 EXPORTS = ["dlm_last_error", "dlm_model_create", "dlm_model_destroy", "dlm_state_create", "dlm_state_destroy", "dlm_state_reset",
            "dlm_state_kv_len", "dlm_step", "block_boundary", "select_parallel", "dlm_vocab_stats_workspace", "dlm_vocab_stats",
-           "dlm_gemm_nt", "dlm_attention", "dlm_profile_enable", "dlm_profile_read"]
+           "dlm_gemm_nt", "dlm_attention", "dlm_profile_enable", "dlm_profile_read", "dlm_probe_hbm_read", "dlm_probe_mfma_bf16"]
 
 
 def lib():
@@ -236,6 +236,20 @@ def dlm_gemm_nt(x, w):
     y = torch.empty((M, N), dtype=x.dtype, device=x.device)
     _check(lib().dlm_gemm_nt(_ptr(x), _ptr(w), _ptr(y), M, N, K, dtype_code(x), _stream()))
     return y
+
+
+def probe_hbm_read(buf, reps=10):
+    """GB/s of a plain streaming read of the device tensor `buf` (see include/dlm.h)."""
+    out = C.c_double()
+    _check(lib().dlm_probe_hbm_read(_ptr(buf), C.c_size_t(buf.numel() * buf.element_size()), reps, C.byref(out), _stream()))
+    return out.value
+
+
+def probe_mfma_bf16(reps=5):
+    """TFLOP/s of independent bf16 matrix-core products out of registers."""
+    out = C.c_double()
+    _check(lib().dlm_probe_mfma_bf16(reps, C.byref(out), _stream()))
+    return out.value
 
 
 def dlm_attention(q, k, v):

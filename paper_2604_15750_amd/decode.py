@@ -150,7 +150,7 @@ class Decoder:
             for j, i in enumerate(bnd):
                 b = group[i]
                 if trace is not None:
-                    trace.append(dict(op="boundary", seq=b, F=self.F[b] + self.L[b], W=lens[j], L=int(Ls[j]),
+                    trace.append(dict(op="boundary", seq=b, F=self.F[b] + self.L[b], W=lens[j], L=int(Ls[j]), cold=bool(cold[j]),
                                       kl=out.kl[starts[j]: starts[j] + lens[j]].cpu().numpy(),
                                       entropy=out.entropy[starts[j]: starts[j] + lens[j]].cpu().numpy()))
                 self.F[b] += self.L[b]

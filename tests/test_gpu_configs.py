@@ -184,3 +184,58 @@ def test_step_rerun_is_bit_identical(device):
                         assert torch.equal(x, y), (rows, rep)
         state.close()
     model.close()
+
+
+@pytest.mark.parametrize("thresholds", ["scaled", "paper"])
+def test_full_depth_decode_invariants_and_decisions(device, thresholds):
+    """A whole decode of configuration 1 at full depth on the GPU (the run the benchmark times), checked without an oracle
+    forward pass: the invariants of the decode schedule, and every decision re-taken by the oracle from the GPU's own
+    outputs of that pass - the statistics of the block's logits recomputed in fp64, DepGA-Block on the GPU's KL / entropy
+    profile, CAP-Decoding on the GPU's logits - exact wherever the oracle's decision margin exceeds the fp32 tolerance."""
+    from oracle import boundary as o_boundary, select as o_select, stats as o_stats
+    cfg, B, P, N, lmax = inputs.WORKLOADS["llada8b_p256_g256"]
+    prm = _f32(dict(SCALED if thresholds == "scaled" else inputs.PAPER_PARAMS, l_max=lmax))
+    W = inputs.make_weights(cfg, seed=0, device=device)
+    model = api.Model(cfg, W)
+    del W
+    prompts = inputs.make_prompts(cfg, 1, P)
+    dec = Decoder(model, 1, P, N, prm, device)
+    trace = []
+    got = dec.run(prompts, trace)
+    mask = cfg["mask_id"]
+    y, blocks, steps, nfe = got["tokens"][0], got["blocks"][0], got["steps"][0], got["nfe"][0]
+    # schedule invariants (Sec. 3, 4.2): the prompt is kept, nothing stays masked, the blocks partition the generation, every
+    # block but the last lies in [L_min, L_max], the first is L_min, every pass decodes at least one token
+    assert (y[:P] == prompts[0]).all() and not (y == mask).any()
+    assert sum(blocks) == N and blocks[0] == prm["l_min"] and all(prm["l_min"] <= b <= lmax for b in blocks[:-1]) and 1 <= blocks[-1] <= lmax
+    assert sum(steps) == N and min(steps) >= 1 and len(blocks) <= nfe <= N and nfe == len(steps)
+    n_sel = n_bnd = exact_sel = exact_bnd = 0
+    last = None
+    for rec in trace:
+        if rec["op"] == "pass":
+            last = rec
+        elif rec["op"] == "boundary":
+            Lr, _, mr = o_boundary.block_boundary(rec["kl"].astype(np.float64), rec["entropy"].astype(np.float64), prm["lam"], prm["l_min"],
+                                                  prm["smooth_radius"], prm["norm_mode"], prm["rule"], cold_start=rec["cold"])
+            n_bnd += 1
+            if mr > 1e-4:
+                exact_bnd += 1
+                assert rec["L"] == Lr, (rec["F"], rec["L"], Lr, mr)
+        elif rec["op"] == "select":
+            F, L = rec["F"], rec["L"]
+            r0 = F - last["span_start"]
+            z = o_fwd.widen(inputs.tensor_to_numpy(last["logits"][r0: r0 + L]))
+            st = o_stats.vocab_stats(z, mask)
+            elig = last["tokens"][r0: r0 + L] == mask
+            ref_sel, mr = o_select.select_parallel(z, st["lse"], st["conf"], st["argmax"], elig, prm["tau_low"], prm["tau_high"], prm["gamma"],
+                                                   prm.get("mode", 0))
+            n_sel += 1
+            assert rec["selected"].sum() >= 1 and not (rec["selected"] & ~elig).any()
+            if mr > 1e-5:
+                exact_sel += 1
+                assert (rec["selected"] == ref_sel).all(), (F, L, mr)
+    assert n_sel == nfe and n_bnd == len(blocks)  # the first block's (cold-start) decision included
+    assert exact_sel >= 0.9 * n_sel and exact_bnd >= 0.8 * n_bnd, (exact_sel, n_sel, exact_bnd, n_bnd)
+    print(thresholds, "NFE", nfe, "blocks", blocks, "selections checked exactly", exact_sel, "of", n_sel, "boundaries", exact_bnd, "of", n_bnd)
+    dec.close()
+    model.close()

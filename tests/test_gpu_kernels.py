@@ -222,3 +222,16 @@ def test_select_parallel(device, dt, mode):
     assert fired["multi"] > 3 or mode == 2
     if mode == 0:
         assert fired["fallback"] > 0 and fired["dropped"] > 3, fired
+
+
+# ---- measurement helpers --------------------------------------------------------------------------
+def test_probes_report_plausible_rates(device):
+    """The two probes bench.py quotes rooflines against: a plain streaming read reaches most of, and no more than, the
+    published 8 TB/s; the matrix-core loop most of, and no more than, the published 2.5 PFLOP/s."""
+    buf = torch.empty(1 << 30, dtype=torch.uint8, device=device)
+    gbs = api.probe_hbm_read(buf, reps=5)
+    tf = api.probe_mfma_bf16(reps=2)
+    assert 3000 < gbs < 8000, gbs
+    assert 1000 < tf < 2600, tf
+    with pytest.raises(api.DlmError):
+        api.probe_hbm_read(torch.empty(1 << 20, dtype=torch.uint8, device=device))
