@@ -97,20 +97,19 @@ __global__ __launch_bounds__(256) void attention_kernel(const T* __restrict__ q,
 }
 
 // ---- bf16 kernel on the matrix cores (attention_core.h) ----------------------------------------------
-// One workgroup per (16-query tile, head, sequence).  A decode pass has few (query tile, head) pairs, so it runs 8
-// wavefronts per workgroup to shorten each wavefront's chain of dependent loads; wide passes (prefill, batches) run 4.
-template <int HD, int NWV>
+// One workgroup per (16-query tile, head, sequence), or DS of them with a share of the head's output dims each.
+template <int HD, int NWV, int DS>
 __global__ __launch_bounds__(NWV * 64) void attention_mfma_kernel(const bf16_t* __restrict__ q, const bf16_t* __restrict__ kcache,
                                                                   const bf16_t* __restrict__ vcache, size_t slot_stride, size_t head_stride,
                                                                   AttnMeta meta, bf16_t* __restrict__ out, bool out_tiled, int n_q, int n_kv) {
-  __shared__ AttnLds<HD, NWV> L;
-  const int b = blockIdx.z, head = blockIdx.y;
-  const int row0 = meta.row_off[b] + blockIdx.x * 16;
+  __shared__ AttnLds<HD, NWV, DS> L;
+  const int b = blockIdx.z, head = blockIdx.y, tile = blockIdx.x / DS, dpart = blockIdx.x - tile * DS;
+  const int row0 = meta.row_off[b] + tile * 16;
   const int row_end = meta.row_off[b + 1];
   if (row0 >= row_end) return;
   const int kvh = head / (n_q / n_kv);
   const size_t region = (size_t)meta.slot[b] * slot_stride + (size_t)kvh * head_stride;
-  attention_tile<HD, NWV>(q, kcache + region, vcache + region, row0, row_end, meta.n_keys[b], head, n_q, out, out_tiled, L);
+  attention_tile<HD, NWV, DS>(q, kcache + region, vcache + region, row0, row_end, meta.n_keys[b], head, n_q, out, out_tiled, L, dpart);
 }
 
 // K [T, n_kv, hd] and V row-major -> the tiled cache layout of one slot (test helper for dlm_attention)
@@ -143,11 +142,14 @@ template <>
 void launch_attention<bf16_t>(const bf16_t* q, const bf16_t* kcache, const bf16_t* vcache, size_t slot_stride, size_t head_stride,
                               const AttnMeta& meta, bf16_t* out, bool out_tiled, int rows, int max_seq_rows, int n_q, int n_kv, int hd,
                               hipStream_t st) {
-  dim3 grid((max_seq_rows + 15) / 16, n_q, meta.n_seqs);
-  const bool wide = (size_t)grid.x * grid.y * grid.z >= 512;  // enough workgroups to fill the chip with 4 wavefronts each
-#define GO(HD, NWV) attention_mfma_kernel<HD, NWV><<<grid, NWV * 64, 0, st>>>(q, kcache, vcache, slot_stride, head_stride, meta, out, out_tiled, n_q, n_kv)
-  if (hd == 32) { if (wide) GO(32, 4); else GO(32, 8); }
-  else if (hd == 64) { if (wide) GO(64, 4); else GO(64, 8); }
-  else { if (wide) GO(128, 4); else GO(128, 8); }
+  const int tiles = (max_seq_rows + 15) / 16;
+  // a narrow pass (few query tiles x heads): eight wavefronts per workgroup to shorten each wavefront's chain of dependent
+  // loads, and the output dims of a head split over four workgroups (two for 64 dims) to spread its K / V traffic
+  const bool narrow = (size_t)tiles * n_q * meta.n_seqs < 128 && hd >= 64;
+  const bool wide = (size_t)tiles * n_q * meta.n_seqs >= 512;  // enough workgroups to fill the chip with 4 wavefronts each
+#define GO(HD, NWV, DS) attention_mfma_kernel<HD, NWV, DS><<<dim3(tiles * DS, n_q, meta.n_seqs), NWV * 64, 0, st>>>(q, kcache, vcache, slot_stride, head_stride, meta, out, out_tiled, n_q, n_kv)
+  if (hd == 32) { if (wide) GO(32, 4, 1); else GO(32, 8, 1); }
+  else if (hd == 64) { if (narrow) GO(64, 8, 2); else if (wide) GO(64, 4, 1); else GO(64, 8, 1); }
+  else { if (narrow) GO(128, 8, 4); else if (wide) GO(128, 4, 1); else GO(128, 8, 1); }
 #undef GO
 }

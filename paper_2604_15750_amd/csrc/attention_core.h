@@ -14,20 +14,25 @@
 #pragma once
 #include "common.h"
 
-template <int HD, int NWV>
-struct AttnLds {  // merge buffers of one workgroup
+template <int HD, int NWV, int DS = 1>
+struct AttnLds {  // merge buffers of one workgroup (HD / DS of the head's dims)
   float sm[NWV][16], sl[NWV][16];
-  float so[NWV][HD][17];
+  float so[NWV][HD / DS][17];
 };
 
 // q: row-major [rows, n_q * HD]; kt / vt: the (slot, kv head) region of the tiled cache; rows [row0, row_end) x head `head`
 // against keys [0, n_keys); out: activation layout [rows, n_q * HD] (out_tiled) or row-major.  Called by every thread of
 // a workgroup of NWV wavefronts.
-template <int HD, int NWV>
+// DS > 1: the workgroup produces only dims [dpart * HD / DS, (dpart + 1) * HD / DS) of the output: it reads all of K (the
+// scores and the softmax are computed by each of the DS workgroups of a head, identically) but only its share of V.  What
+// bounds a narrow pass is what one compute unit can pull through its L2 (about 50 GB/s), and K and V of a head are its whole
+// traffic: four workgroups per head move 5/8 of it each, with nothing to merge.
+template <int HD, int NWV, int DS = 1>
 __device__ inline void attention_tile(const bf16_t* __restrict__ q, const bf16_t* __restrict__ kregion, const bf16_t* __restrict__ vregion,
                                       int row0, int row_end, int n_keys, int head, int n_q, bf16_t* __restrict__ out, bool out_tiled,
-                                      AttnLds<HD, NWV>& L) {
-  constexpr int KS = HD / 32, DT = HD / 16;
+                                      AttnLds<HD, NWV, DS>& L, int dpart = 0) {
+  constexpr int KS = HD / 32, DT = HD / 16 / DS, HDP = HD / DS;
+  static_assert(HDP * 16 >= NWV * 64, "every thread finishes at least one dim");
   constexpr float NEG_BIG = -3.0e38f;
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, g = lane >> 4, c = lane & 15;
   const float scale = rsqrtf((float)HD);
@@ -54,7 +59,7 @@ __device__ inline void attention_tile(const bf16_t* __restrict__ q, const bf16_t
 #pragma unroll
     for (int t = 0; t < 2 * KS; ++t) kf[buf][t] = ok ? kt[((size_t)blk * 2 * KS + t) * 64] : zero8;
 #pragma unroll
-    for (int dt = 0; dt < DT; ++dt) vf[buf][dt] = ok ? vt[((size_t)blk * DT + dt) * 64] : zero8;
+    for (int dt = 0; dt < DT; ++dt) vf[buf][dt] = ok ? vt[((size_t)blk * (DT * DS) + dpart * DT + dt) * 64] : zero8;
   };
   auto step = [&](int buf, int blk) {
     f32x4 s0 = {0.f, 0.f, 0.f, 0.f}, s1 = {0.f, 0.f, 0.f, 0.f};
@@ -112,7 +117,7 @@ __device__ inline void attention_tile(const bf16_t* __restrict__ q, const bf16_t
 #pragma unroll
     for (int i = 0; i < 4; ++i) L.so[wave][16 * dt + 4 * g + i][c] = o[dt][i];
   __syncthreads();
-  constexpr int CH = HD * 16 / (NWV * 64);  // each thread finishes CH consecutive dims of one query
+  constexpr int CH = HDP * 16 / (NWV * 64);  // each thread finishes CH consecutive dims of one query
   const int qi = tid & 15, d0 = (tid >> 4) * CH;
   float M = L.sm[0][qi];
 #pragma unroll
@@ -129,7 +134,7 @@ __device__ inline void attention_tile(const bf16_t* __restrict__ q, const bf16_t
       float acc = 0.f;
 #pragma unroll
       for (int wv = 0; wv < NWV; ++wv) acc += w[wv] * L.so[wv][d][qi];
-      const int col = head * HD + d;
+      const int col = head * HD + dpart * HDP + d;
       const size_t idx = out_tiled ? tile_index(r, col, width) : (size_t)r * width + col;
       out[idx] = (bf16_t)(acc / Lsum);
     }

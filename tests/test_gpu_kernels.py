@@ -66,6 +66,9 @@ def test_gemm_f32(device, M, N, K):
 @pytest.mark.parametrize("dt,A,T,nq,nkv,hd", [
     ("f32", 1, 1, 1, 1, 32), ("f32", 8, 72, 4, 4, 32), ("f32", 37, 101, 4, 2, 64), ("f32", 64, 320, 8, 2, 128),
     ("bf16", 8, 264, 4, 4, 128), ("bf16", 64, 320, 8, 8, 128), ("bf16", 50, 700, 28, 4, 128), ("bf16", 192, 448, 4, 1, 128),
+    # head dims of 64 and 32 (a head's output dims split over two workgroups / not split), and enough (tile, head) pairs that
+    # nothing is split (4 x 32, 40 x 16)
+    ("bf16", 24, 300, 4, 2, 64), ("bf16", 9, 77, 8, 8, 32), ("bf16", 64, 200, 32, 8, 128), ("bf16", 640, 640, 16, 4, 128),
 ])
 def test_attention(device, dt, A, T, nq, nkv, hd):
     tdt = torch.float32 if dt == "f32" else torch.bfloat16
