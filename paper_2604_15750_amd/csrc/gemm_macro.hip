@@ -3,12 +3,12 @@
 //
 // Beyond a few hundred rows the GEMMs leave the weight-streaming regime and are bound by the matrix
 // cores and by how often operands are re-read.  A workgroup of four wavefronts (2 x 2) owns a tile of
-// 32 WM rows x 32 WN columns (128 x 256 or 128 x 128; the kernel is written for any WM, WN, but with
-// 256 x 256 the compiler no longer keeps 256 accumulators and two operand sets in registers without
-// spilling inside the loop) and walks K one k-tile (32) at a time:
+// 32 WM rows x 32 WN columns (192 x 256, 128 x 256 or 128 x 128; the kernel is written for any WM, WN,
+// but with 256 x 256 the compiler no longer keeps 256 accumulators and two operand sets in registers
+// without spilling inside the loop) and walks K one k-tile (32) at a time:
 //   * both operands are already stored as 1 KiB matrix-core fragments (16 rows x 32 k), so a stage of
 //     the pipeline is just 2 WM + 2 WN fragments copied HBM/L2 -> LDS by direct-to-LDS loads (no
-//     registers, no LDS writes): 5 to 8 stages of 16 .. 24 KiB rotate through up to 128 KiB of LDS;
+//     registers, no LDS writes): 4 to 8 stages of 16 .. 28 KiB rotate through up to 128 KiB of LDS;
 //   * a wavefront owns WM x WN fragments of the output (fp32 accumulators, up to 256 registers), reads
 //     its WM + WN operand fragments of the NEXT k-tile from LDS into a second register set while the
 //     matrix cores work on the current one (WM WN products per WM + WN fragment reads);
@@ -167,11 +167,11 @@ struct MacroPlan {
 // the tile with the least estimated time: rounds of workgroups over the chip x products per workgroup, the smaller tiles
 // charged for their heavier LDS traffic
 MacroPlan macro_plan(int M, int N) {
-  const int cand[2][2] = {{4, 8}, {4, 4}};
-  const double penalty[2] = {1.0, 1.25};
+  const int cand[3][2] = {{4, 8}, {4, 4}, {6, 8}};
+  const double penalty[3] = {1.0, 1.25, 0.9};
   MacroPlan best{4, 8, 1, 1};
   double best_cost = 1e300;
-  for (int c = 0; c < 2; ++c) {
+  for (int c = 0; c < 3; ++c) {
     const int bm = 32 * cand[c][0], bn = 32 * cand[c][1];
     const int mb = (M + bm - 1) / bm, nb = (N + bn - 1) / bn;
     const int rounds = (mb * nb + 255) / 256;
@@ -195,7 +195,8 @@ void launch_one(const bf16_t* xt, const bf16_t* wt, int M, int N, int K, const M
 
 template <int PR, int EPI>
 void launch_shape(const bf16_t* xt, const bf16_t* wt, int M, int N, int K, const MacroPlan& p, const GemmEpi& e, hipStream_t st) {
-  if (p.wn == 8) launch_one<4, 8, PR, EPI>(xt, wt, M, N, K, p, e, st);
+  if (p.wm == 6) launch_one<6, 8, PR, EPI>(xt, wt, M, N, K, p, e, st);
+  else if (p.wn == 8) launch_one<4, 8, PR, EPI>(xt, wt, M, N, K, p, e, st);
   else launch_one<4, 4, PR, EPI>(xt, wt, M, N, K, p, e, st);
 }
 

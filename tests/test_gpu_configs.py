@@ -45,7 +45,8 @@ def test_twin_replay(device, name, passes):
 
 @pytest.mark.parametrize("name,rows", [("llada8b_p256_g256", 24), ("llada8b_p256_g256", 40), ("llada8b_p256_g256", 64), ("llada8b_p256_g256", 100),
                                        ("llada8b_p256_g256", 136), ("llada8b_p256_g256", 160), ("llada8b_p256_g256", 200), ("llada8b_p256_g256", 256),
-                                       ("dream7b_p512_g256", 40), ("dream7b_p512_g256", 150)])
+                                       ("dream7b_p512_g256", 40), ("dream7b_p512_g256", 150),
+                                       ("llada8b_p256_g256", 368), ("llada8b_p256_g256", 768)])  # 192 x 256 macro tiles, every epilogue
 def test_twin_row_counts(device, name, rows):
     """One prefill pass of exactly `rows` rows at full widths (prompt of rows - 16 tokens, look-ahead 16), then the first
     in-block pass: the row counts at which the GEMM dispatcher changes kernel or tile shape, every fused epilogue included."""

@@ -37,7 +37,9 @@ def _rowtol(ref, rel, floor=0.0):
                                    (161, 4096, 4096), (200, 1024, 2048), (225, 4096, 12288), (256, 4096, 512),
                                    (17, 16384, 256), (40, 24576, 1024), (33, 4096, 8192), (64, 256, 12288), (8, 4608, 3584), (16, 6144, 512),
                                    # more than 256 rows: the macro-tile kernel (ragged rows, column tails, both weight packings, short K)
-                                   (257, 4096, 4096), (513, 8224, 1024), (700, 160, 4096 + 64), (1100, 640, 64), (384, 12288, 32)])
+                                   (257, 4096, 4096), (513, 8224, 1024), (700, 160, 4096 + 64), (1100, 640, 64), (384, 12288, 32),
+                                   # ... with 192 x 256 tiles (two or four row blocks of 192 instead of three or six of 128)
+                                   (368, 24576, 256), (700, 12288, 128)])
 def test_gemm_bf16(device, M, N, K):
     g = torch.Generator(device="cpu").manual_seed(M * 7 + N + K)
     x = torch.randn(M, K, generator=g).to(torch.bfloat16).to(device)
