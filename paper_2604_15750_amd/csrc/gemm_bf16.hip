@@ -92,6 +92,7 @@ void launch_pack_act(const bf16_t* x, bf16_t* out, int M, int K, hipStream_t st)
 int gemm_bf16_splits(int M, int N, int K) {
   switch (choose_kernel(M, N, K, EPI_SUM)) {
     case KERNEL_MID: return gemm_mid_splits(M, N, K);
+    case KERNEL_MACRO: return gemm_macro_splits(M, N, K);
     case KERNEL_TILED: return gemm_tiled_splits(M, N, K);
     default: return 1;
   }
@@ -105,8 +106,8 @@ int gemm_bf16_ssq_chunks(int M, int N, int K) {
   }
 }
 int gemm_bf16_counters(int max_rows, int max_n) {
-  const int a = gemm_tiled_counters(max_rows, max_n), b = gemm_mid_counters(max_n);
-  return a > b ? a : b;
+  const int a = gemm_tiled_counters(max_rows, max_n), b = gemm_mid_counters(max_n), c = gemm_macro_counters(max_rows, max_n);
+  return a > b ? (a > c ? a : c) : (b > c ? b : c);
 }
 
 void launch_gemm_bf16(const bf16_t* xt, const bf16_t* wt, int M, int N, int K, const GemmEpi& e, hipStream_t st) {

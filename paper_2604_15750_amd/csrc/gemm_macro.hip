@@ -26,6 +26,12 @@ namespace {
 
 constexpr int TPB = 256;
 
+typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
+constexpr int SC1 = 16;  // cache-policy bit of the raw-buffer builtins: device scope
+__device__ inline __amdgpu_buffer_rsrc_t part_rsrc(const float* base) {
+  return __builtin_amdgcn_make_buffer_rsrc((void*)base, 0, 0x7fffffff, 0x00020000);
+}
+
 #define GLOBAL_PTR(p) ((const void __attribute__((address_space(1)))*)(p))
 #define LDS_PTR(p) ((void __attribute__((address_space(3)))*)(p))
 
@@ -41,7 +47,7 @@ struct MacroShape {
 
 template <int WM, int WN, int PR, int EPI>
 __global__ __launch_bounds__(TPB) void gemm_macro_kernel(const bf16x8* __restrict__ xt, const bf16x8* __restrict__ wt, int M, int N, int K,
-                                                         int nblocks, int mblocks, GemmEpi e) {
+                                                         int nblocks, int mblocks, int splits, int kt_per_split, GemmEpi e) {
   typedef MacroShape<WM, WN> SH;
   constexpr int AF = SH::AF, BF = SH::BF, LPS = SH::LPS, STAGE = SH::STAGE, S = SH::S;
   static_assert(AF % 4 == 0 && BF % 4 == 0 && S >= 4 && (S - 2) * LPS < 64, "pipeline shape");
@@ -49,11 +55,14 @@ __global__ __launch_bounds__(TPB) void gemm_macro_kernel(const bf16x8* __restric
   float* s_rinv = (float*)(lds + S * STAGE);  // [AF * 16]
   float* s_ssq = s_rinv + AF * 16;            // [2][AF * 16]
 
-  // workgroup id -> (column block, row block): ids congruent mod 8 share an XCD
-  const int q = blockIdx.x >> 3;
+  // workgroup id -> (column block, K split, row block): ids congruent mod 8 share an XCD
+  int q = blockIdx.x >> 3;
   const int rb = q % mblocks;
-  const int cb = (q / mblocks) * 8 + (blockIdx.x & 7);
+  q /= mblocks;
+  const int split = q % splits;
+  const int cb = (q / splits) * 8 + (blockIdx.x & 7);
   if (cb >= nblocks) return;
+  __shared__ int s_last;
 
   const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int wm = wave >> 1, wn = wave & 1;
@@ -61,8 +70,9 @@ __global__ __launch_bounds__(TPB) void gemm_macro_kernel(const bf16x8* __restric
   const int mt0 = rb * AF, nt0 = cb * BF;
 
   // stage kt % S <- k-tile kt: fragment f (f < AF: X row tile mt0 + f, else W column tile nt0 + f - AF) is moved by wavefront f % 4
+  const int kb = split * kt_per_split, nk = min(KT, kb + kt_per_split) - kb;  // this workgroup's k-tiles: kb .. kb + nk - 1
   auto issue = [&](int kt) {
-    const int t = min(kt, KT - 1);
+    const int t = kb + min(kt, nk - 1);
     unsigned char* base = lds + (kt % S) * STAGE;
 #pragma unroll
     for (int i = 0; i < LPS; ++i) {
@@ -114,15 +124,56 @@ __global__ __launch_bounds__(TPB) void gemm_macro_kernel(const bf16x8* __restric
     read_frags(buf ^ 1, kt + 1);
     multiply(buf);
   };
-  for (int kt = 0; kt < KT; kt += 2) {
+  for (int kt = 0; kt < nk; kt += 2) {
     step(0, kt);
-    if (kt + 1 < KT) step(1, kt + 1);
+    if (kt + 1 < nk) step(1, kt + 1);
   }
   asm volatile("s_waitcnt vmcnt(0)" ::: "memory");  // the surplus loads of the last stages: LDS must be quiet before it is reused
 
-  // ---- epilogue
   const int g = lane >> 4, ml = lane & 15;
   const int m_lo = mt0 * 16;
+  if (splits > 1) {
+    // K split (narrow matrices at a few hundred rows, whose tiles alone cover half of the chip): partial tiles go to the fp32
+    // workspace in the accumulator layout, written through to device scope; the workgroup that takes the tile's last ticket
+    // re-reads them all, one split per trip to memory, adds them in split order and runs the epilogue (gemm_tiled.hip's protocol)
+    const size_t stride = (size_t)M * N;
+    auto offset = [&](int j, int i) { return ((unsigned)((wm * WM + i) * 16 + ml) * N + (nt0 + wn * WN + j) * 16 + 4 * g) * 4u; };
+    auto exists = [&](int j, int i) { return nt0 + wn * WN + j < NT && m_lo + (wm * WM + i) * 16 + ml < M; };
+#pragma unroll
+    for (int j = 0; j < WN; ++j)
+#pragma unroll
+      for (int i = 0; i < WM; ++i)
+        if (exists(j, i))
+          __builtin_amdgcn_raw_buffer_store_b128(__builtin_bit_cast(u32x4, acc[j][i]), part_rsrc(e.part + split * stride + (size_t)m_lo * N), offset(j, i), 0, SC1);
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");  // every wavefront's stores have completed ...
+    __syncthreads();                                        // ... before the workgroup takes its ticket
+    if (tid == 0) {
+      int* ticket = e.counters + cb * mblocks + rb;
+      const int last = __hip_atomic_fetch_add(ticket, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) == splits - 1;
+      if (last) __hip_atomic_store(ticket, 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);  // ready for the next launch
+      s_last = last;
+    }
+    __syncthreads();
+    if (!s_last) return;
+#pragma unroll
+    for (int j = 0; j < WN; ++j)
+#pragma unroll
+      for (int i = 0; i < WM; ++i) acc[j][i] = f32x4{0.f, 0.f, 0.f, 0.f};
+    for (int s0 = 0; s0 < splits; ++s0) {
+      u32x4 t[WN][WM];
+#pragma unroll
+      for (int j = 0; j < WN; ++j)
+#pragma unroll
+        for (int i = 0; i < WM; ++i)
+          t[j][i] = __builtin_amdgcn_raw_buffer_load_b128(part_rsrc(e.part + s0 * stride + (size_t)m_lo * N), exists(j, i) ? offset(j, i) : 0u, 0, SC1);
+#pragma unroll
+      for (int j = 0; j < WN; ++j)
+#pragma unroll
+        for (int i = 0; i < WM; ++i) acc[j][i] += __builtin_bit_cast(f32x4, t[j][i]);
+    }
+  }
+
+  // ---- epilogue
   if (EPI != EPI_RESID) block_rinv<TPB>(e.rs, m_lo, max(0, min(M, m_lo + AF * 16) - m_lo), s_rinv);
   __syncthreads();
   // The accumulators leave the registers through LDS (each wavefront its own region, half of its column tiles at a time), so
@@ -161,12 +212,14 @@ __global__ __launch_bounds__(TPB) void gemm_macro_kernel(const bf16x8* __restric
 }
 
 struct MacroPlan {
-  int wm, wn, nblocks, mblocks;
+  int wm, wn, nblocks, mblocks, splits, kps;
 };
 
 // the tile with the least estimated time: rounds of workgroups over the chip x products per workgroup, the smaller tiles
 // charged for their heavier LDS traffic
-MacroPlan macro_plan(int M, int N) {
+int g_macro_wgs = 256;  // workgroups a K split aims at
+
+MacroPlan macro_plan(int M, int N, int K, bool may_split) {
   const int cand[3][2] = {{4, 8}, {4, 4}, {6, 8}};
   const double penalty[3] = {1.0, 1.25, 0.9};
   MacroPlan best{4, 8, 1, 1};
@@ -176,8 +229,16 @@ MacroPlan macro_plan(int M, int N) {
     const int mb = (M + bm - 1) / bm, nb = (N + bn - 1) / bn;
     const int rounds = (mb * nb + 255) / 256;
     const double cost = (double)rounds * bm * bn * penalty[c];
-    if (cost < best_cost) { best_cost = cost; best = MacroPlan{cand[c][0], cand[c][1], nb, mb}; }
+    if (cost < best_cost) { best_cost = cost; best = MacroPlan{cand[c][0], cand[c][1], nb, mb, 1, 0}; }
   }
+  // tiles that cover at most half of the chip (narrow matrices at a few hundred rows): split K until they cover it
+  const int KT = K >> 5, wgs = best.nblocks * best.mblocks;
+  int s = may_split ? g_macro_wgs / wgs : 1;
+  if (s > 4) s = 4;
+  if (s > KT / 32) s = KT / 32;  // at least 32 k-tiles per workgroup: the pipeline is up to 8 stages deep
+  if (s < 1) s = 1;
+  best.kps = (KT + s - 1) / s;
+  best.splits = (KT + best.kps - 1) / best.kps;  // no empty split
   return best;
 }
 
@@ -189,8 +250,9 @@ void launch_one(const bf16_t* xt, const bf16_t* wt, int M, int N, int K, const M
     (void)hipFuncSetAttribute((const void*)gemm_macro_kernel<WM, WN, PR, EPI>, hipFuncAttributeMaxDynamicSharedMemorySize, SH::LDS_BYTES);
     configured = true;
   }
-  const int grid = (p.nblocks + 7) / 8 * 8 * p.mblocks;
-  DLM_LAUNCH((gemm_macro_kernel<WM, WN, PR, EPI>), grid, TPB, SH::LDS_BYTES, st, (const bf16x8*)xt, (const bf16x8*)wt, M, N, K, p.nblocks, p.mblocks, e);
+  const int grid = (p.nblocks + 7) / 8 * 8 * p.mblocks * p.splits;
+  DLM_LAUNCH((gemm_macro_kernel<WM, WN, PR, EPI>), grid, TPB, SH::LDS_BYTES, st, (const bf16x8*)xt, (const bf16x8*)wt, M, N, K, p.nblocks, p.mblocks,
+             p.splits, p.kps, e);
 }
 
 template <int PR, int EPI>
@@ -208,10 +270,13 @@ void launch_epi(const bf16_t* xt, const bf16_t* wt, int M, int N, int K, const M
 
 }  // namespace
 
-int gemm_macro_ssq_chunks(int M, int N) { return macro_plan(M, N).nblocks; }
+int gemm_macro_ssq_chunks(int M, int N) { return macro_plan(M, N, 32, false).nblocks; }
+int gemm_macro_splits(int M, int N, int K) { return macro_plan(M, N, K, true).splits; }
+int gemm_macro_counters(int max_rows, int max_n) { return ((max_n + 127) / 128) * ((max_rows + 127) / 128); }  // 128 x 128 tiles are the smallest
+void gemm_macro_set_target(int wgs) { g_macro_wgs = wgs; }
 
 void launch_gemm_macro(const bf16_t* xt, const bf16_t* wt, int M, int N, int K, const GemmEpi& e, hipStream_t st) {
-  const MacroPlan p = macro_plan(M, N);
+  const MacroPlan p = macro_plan(M, N, K, e.kind != EPI_DIRECT);  // EPI_DIRECT has no workspace
   switch (e.kind) {
     case EPI_QKV: launch_epi<EPI_QKV>(xt, wt, M, N, K, p, e, st); break;
     case EPI_SWIGLU: launch_epi<EPI_SWIGLU>(xt, wt, M, N, K, p, e, st); break;
