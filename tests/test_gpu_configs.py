@@ -184,6 +184,22 @@ def test_step_rerun_is_bit_identical(device):
                     for x, y in zip(got, first[rows]):
                         assert torch.equal(x, y), (rows, rep)
         state.close()
+    # 257 .. 512 rows: the macro-tile kernel splits K for the narrow matrices (O, down)
+    state = api.State(model, 1, P + N, 400, 0)
+    out = api.StepOutputs(400, cfg["vocab"], model.torch_dtype, device)
+    tokens = torch.from_numpy(inputs.make_prompts(cfg, 1, P + N)[0].astype(np.int32)).to(device)
+    first = {}
+    for rep in range(8):
+        for rows in (300, 400):
+            api.dlm_step(state, tokens, out, [0, rows], [0], [0], [0])
+            torch.cuda.synchronize()
+            got = (out.logits[:rows].view(torch.int16).clone(), out.lse[:rows].clone(), out.argmax[:rows].clone())
+            if rows not in first:
+                first[rows] = got
+            else:
+                for x, y in zip(got, first[rows]):
+                    assert torch.equal(x, y), (rows, rep)
+    state.close()
     model.close()
 
 
