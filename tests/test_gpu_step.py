@@ -353,3 +353,33 @@ def test_tiny_f32_degenerate_lengths(device, P, N):
     cfg = inputs.TINY
     W = _weights(cfg, 0, device)
     _free_run_matches(cfg, W, inputs.make_prompts(cfg, 1, P, seed=P + N), N, TINY_SETS["scaled"], device, exact=True)
+
+
+def _golden():
+    import importlib.util
+    import json
+    import os
+    here = os.path.join(os.path.dirname(os.path.abspath(__file__)), "golden")
+    spec = importlib.util.spec_from_file_location("make_decode_golden", os.path.join(here, "make_decode_golden.py"))
+    mod = importlib.util.module_from_spec(spec)
+    spec.loader.exec_module(mod)
+    with open(os.path.join(here, "tiny_decode.json")) as f:
+        return mod, json.load(f)
+
+
+@pytest.mark.parametrize("name", ["paper", "scaled", "dual_cache", "threshold_block16", "vanilla_block32"])
+def test_tiny_f32_free_run_equals_stored_decode(device, name):
+    """The stored decodes (written from the oracle alone by tests/golden/make_decode_golden.py): block lengths, tokens
+    written per pass, NFE and every token, exactly."""
+    mod, gold = _golden()
+    cfg = inputs.TINY
+    W = _weights(cfg, 0, device)
+    model = api.Model(cfg, W)
+    P, N = gold["prompt_len"], gold["gen_len"]
+    dec = Decoder(model, 1, P, N, _f32(mod.CASES[name]), device)
+    got = dec.run(inputs.make_prompts(cfg, 1, P))
+    ref = gold["cases"][name]
+    assert got["blocks"][0] == ref["blocks"] and got["steps"][0] == ref["steps"] and got["nfe"][0] == ref["nfe"]
+    assert got["tokens"][0].tolist() == ref["tokens"]
+    dec.close()
+    model.close()

@@ -71,3 +71,28 @@ def test_fixed_block_comparison_rules(tiny, block, mode):
         assert r["nfe"] < N and max(r["steps"]) > 1
         vanilla = decode_full(cfg, W, prompt, N, dict(prm, mode=2))
         assert r["nfe"] < vanilla["nfe"]
+
+
+def test_stored_decodes_are_what_the_oracle_writes():
+    """tests/golden/tiny_decode.json is the committed script's output and nothing else: re-deriving two of its cases gives
+    the stored values, and every stored case satisfies the decode's invariants (Sec. 3, Sec. 4.2)."""
+    import importlib.util
+    import json
+    import os
+    here = os.path.join(os.path.dirname(os.path.abspath(__file__)), "golden")
+    spec = importlib.util.spec_from_file_location("make_decode_golden", os.path.join(here, "make_decode_golden.py"))
+    mod = importlib.util.module_from_spec(spec)
+    spec.loader.exec_module(mod)
+    with open(os.path.join(here, "tiny_decode.json")) as f:
+        gold = json.load(f)
+    assert set(gold["cases"]) == set(mod.CASES)
+    for name in ("scaled", "threshold_block16"):
+        assert mod.decode(name) == gold["cases"][name]
+    N, mask = gold["gen_len"], inputs.TINY["mask_id"]
+    for name, r in gold["cases"].items():
+        prm = mod.CASES[name]
+        assert sum(r["blocks"]) == N and sum(r["steps"]) == N and min(r["steps"]) >= 1 and mask not in r["tokens"]
+        first = prm.get("fixed_block") or prm["l_min"]
+        assert r["blocks"][0] == first and max(r["blocks"]) <= prm["l_max"]
+        # one pass per selection step, the prefill's and each boundary pass's selection included (Sec. 4.2)
+        assert r["nfe"] == len(r["steps"])
