@@ -225,6 +225,17 @@ int dlm_attention(const void* q, const void* k, const void* v, void* out, int A,
 int dlm_probe_hbm_read(const void* src, size_t bytes, int reps, double* gb_per_s, void* stream);
 int dlm_probe_mfma_bf16(int reps, double* tflop_per_s, void* stream);
 
+/* Where dlm_step takes the vocabulary statistics of a bf16 model's pass that compares no row with a
+ * retained distribution and retains none (kl_count and save_count all zero: the in-block passes of
+ * Sec. 4.3) and has at most 64 rows.  enable != 0 (the default of a new state): from the LM-head
+ * GEMM's epilogue, which leaves one online-softmax state (maximum, sum of exponentials, their
+ * logit-weighted sum, lowest token id of the maximum; Sec. 4.2 entropy, Sec. 4.3 confidence and
+ * prediction) per row and column group, finished by a small merge: the logits are written but
+ * not read back.  enable == 0: from the streamed reduction over the written logits, as every other
+ * pass does.  Both take the logits as written (rounded to the model's dtype) and leave out the mask
+ * token; their results differ only in the order of the fp32 sums.  Errors: DLM_EINVAL (null state). */
+int dlm_state_fuse_stats(dlm_state* s, int enable);
+
 /* Per-kernel-class timing of dlm_step: the launches of every class whose bit is set in class_mask
  * are bracketed by HIP events on the caller's stream (0 switches the timing off; events cost queue
  * time, so bracket few classes when a class's own duration matters).  dlm_profile_read synchronises

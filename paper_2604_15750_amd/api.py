@@ -55,7 +55,8 @@ class dlm_select_params(C.Structure):
 
 EXPORTS = ["dlm_last_error", "dlm_model_create", "dlm_model_destroy", "dlm_state_create", "dlm_state_destroy", "dlm_state_reset",
            "dlm_state_kv_len", "dlm_step", "block_boundary", "select_parallel", "dlm_vocab_stats_workspace", "dlm_vocab_stats",
-           "dlm_gemm_nt", "dlm_attention", "dlm_profile_enable", "dlm_profile_read", "dlm_probe_hbm_read", "dlm_probe_mfma_bf16"]
+           "dlm_gemm_nt", "dlm_attention", "dlm_profile_enable", "dlm_profile_read", "dlm_probe_hbm_read", "dlm_probe_mfma_bf16",
+           "dlm_state_fuse_stats"]
 
 
 def lib():
@@ -86,6 +87,7 @@ def lib():
                                      [C.c_size_t, C.c_void_p]
         L.dlm_gemm_nt.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_int, C.c_int, C.c_int, C.c_int, C.c_void_p]
         L.dlm_attention.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p] + [C.c_int] * 6 + [C.c_void_p]
+        L.dlm_state_fuse_stats.argtypes = [C.c_void_p, C.c_int]
         L.dlm_profile_enable.argtypes = [C.c_void_p, C.c_uint]
         L.dlm_profile_read.argtypes = [C.c_void_p, C.c_int, C.POINTER(C.c_double), C.POINTER(C.c_int64), C.c_int]
         _lib = L
@@ -154,6 +156,10 @@ class State:
 
     def kv_len(self, slot):
         return _check(lib().dlm_state_kv_len(self.handle, slot))
+
+    def fuse_stats(self, enable):
+        """dlm_state_fuse_stats: statistics of qualifying passes from the LM head's epilogue (default) or from the streamed reduction."""
+        _check(lib().dlm_state_fuse_stats(self.handle, int(bool(enable))))
 
     PROFILE_CLASSES = ("gemm_qkv", "gemm_o", "gemm_gate_up", "gemm_down", "gemm_lm_head", "attention", "vocab_stats", "other")
 

@@ -133,6 +133,7 @@ int gemm_bf16_counters(int max_rows, int max_n);   // ticket counters a state ne
 int gemm_tiled_counters(int max_rows, int max_n);
 int gemm_tiled_splits(int M, int N, int K);
 int gemm_tiled_ssq_chunks(int M, int N);
+int gemm_tiled_stat_parts(int M, int N);
 void gemm_tiled_set_target(int wgs);               // tuning: workgroups the K split aims at
 // rs (optional): every output row m is multiplied by rsqrt(sum_c rs.ssq[m][c] * rs.inv_d + rs.eps).
 struct RowScale {
@@ -140,7 +141,7 @@ struct RowScale {
   int nch;
   float inv_d, eps;
 };
-enum { EPI_DIRECT = 0, EPI_QKV = 1, EPI_SWIGLU = 2, EPI_RESID = 3, EPI_SUM = 4 };
+enum { EPI_DIRECT = 0, EPI_QKV = 1, EPI_SWIGLU = 2, EPI_RESID = 3, EPI_SUM = 4, EPI_STATS = 5 };
 // What the bf16 GEMM does with a finished output tile (see gemm_bf16.hip).
 struct GemmEpi {
   int kind;
@@ -164,7 +165,14 @@ struct GemmEpi {
   // EPI_DIRECT (bf16) / EPI_SUM (either)
   bf16_t* out_bf16;
   float* out_f32;
+  // EPI_STATS (the LM head of a pass that compares and retains no row; at most GEMM_STATS_MAX_ROWS rows): logits to out_bf16 as
+  // EPI_DIRECT does, and per row and column group the online-softmax state of the group's logits as written (rounded to bf16,
+  // token skip_col left out) to stat_parts[m][gemm_bf16_stat_parts(N)]
+  void* stat_parts;
+  int skip_col;
 };
+constexpr int GEMM_STATS_MAX_ROWS = 64;
+int gemm_bf16_stat_parts(int M, int N);              // column groups per row an EPI_STATS launch of this shape writes states for
 // The GEMM kernels are launched through hipExtLaunchKernelGGL, which can stamp two events with the kernel's own start and end
 // (the dispatch's timestamps: what a profiler reports, with no marker packets between dependent kernels).  A caller that
 // wants the next GEMM launch of this thread timed sets g_launch_stamp; the launch takes the events and clears it.
@@ -235,6 +243,10 @@ struct StatsRows {
   float* save_lse;          // indexed by save_row / vocab
 };
 size_t stats_workspace_bytes(int rows);
+constexpr size_t STATS_STATE_BYTES = 32;  // one online-softmax state (stats_part.h)
+// Finishes rows whose online-softmax states were written per column group by an EPI_STATS GEMM: parts [rows][nparts] states
+// (stats_part.h), merged in a fixed order.
+void launch_stats_merge(const void* parts, int rows, int nparts, int vocab, const StatsRows& sr, const StatsOut& o, hipStream_t st);
 template <typename T>
 void launch_vocab_stats(const T* logits, int rows, int vocab, int mask_id, const StatsRows& sr, const StatsOut& o, void* workspace, hipStream_t st);
 

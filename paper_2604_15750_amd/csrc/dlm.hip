@@ -78,6 +78,7 @@ struct dlm_state {
   DevBuf row_seq, row_pos, row_tok, row_slot, rope_cos, rope_sin, prev_row, save_row;
   std::vector<int> kv_len, covered_end, prev_cur, prev_base, prev_count;  // covered_end: positions [0, covered_end) hold K and V of some pass
   size_t part_elems;
+  bool fuse_stats = true;  // passes that qualify take their statistics from the LM head's epilogue (dlm_state_fuse_stats)
   Profile prof;
 };
 
@@ -225,7 +226,15 @@ extern "C" int dlm_state_create(const dlm_model* m, int max_seqs, int max_seq_le
   A(s->act, (size_t)s->max_rows_pad * c.d_ffn * es);
   A(s->q, (size_t)max_rows * qd * es);
   A(s->part, pe * 4);
-  A(s->stats_ws, stats_workspace_bytes(max_rows));
+  size_t stats_bytes = stats_workspace_bytes(max_rows);
+  if (c.dtype == DLM_BF16) {  // or one state per row and column group of the LM head, for the passes that take the statistics from its epilogue
+    const int fr = max_rows < GEMM_STATS_MAX_ROWS ? max_rows : GEMM_STATS_MAX_ROWS;
+    for (int mt = 1; mt <= (fr + 15) / 16; ++mt) {
+      const size_t b = (size_t)fr * gemm_bf16_stat_parts(mt * 16 < fr ? mt * 16 : fr, c.vocab) * STATS_STATE_BYTES;
+      if (b > stats_bytes) stats_bytes = b;
+    }
+  }
+  A(s->stats_ws, stats_bytes);
   const int ssq_chunks = c.dtype == DLM_BF16 ? c.d_model / 16 : norm_chunks(c.d_model);
   A(s->ssq, (size_t)max_rows * ssq_chunks * 4);
   int n_counters = 1;
@@ -270,6 +279,12 @@ extern "C" int dlm_state_kv_len(const dlm_state* s, int slot) {
   REQUIRE(s, DLM_EINVAL, "dlm_state_kv_len: null state");
   REQUIRE(slot >= 0 && slot < s->max_seqs, DLM_EINVAL, "dlm_state_kv_len: slot %d out of range", slot);
   return s->kv_len[slot];
+}
+
+extern "C" int dlm_state_fuse_stats(dlm_state* s, int enable) {
+  REQUIRE(s, DLM_EINVAL, "dlm_state_fuse_stats: null state");
+  s->fuse_stats = enable != 0;
+  return DLM_OK;
 }
 
 extern "C" int dlm_profile_enable(dlm_state* s, unsigned class_mask) {
@@ -426,18 +441,25 @@ int run_step_bf16(dlm_state* s, const dlm_step_desc* d, const SeqMeta& meta, con
       nch = gemm_bf16_ssq_chunks(rows, dm, ffn);
     }
   }
+  // A pass that compares no row with a retained distribution and retains none (every in-block pass) needs no second trip over
+  // its logits: the LM head's epilogue leaves one online-softmax state per row and column group, and a small merge finishes them.
+  bool fused = s->fuse_stats && rows <= GEMM_STATS_MAX_ROWS;
+  for (int b = 0; b < meta.n_seqs; ++b) fused = fused && sm.kl_count[b] == 0 && sm.save_count[b] == 0;
+  StatsRows sr{t.prev_row, t.save_row, s->prev_logits.p, s->prev_logits.p, (const float*)s->prev_lse.p, (float*)s->prev_lse.p};
+  StatsOut so{d->max_logit, d->lse, d->entropy, d->kl, d->conf, d->argmax};
   {
     GemmEpi e = base;
-    e.kind = EPI_DIRECT;
+    e.kind = fused ? EPI_STATS : EPI_DIRECT;
     e.rs = RowScale{ssq, nch, 1.f / (float)dm, c.rms_eps};
     e.out_bf16 = (T*)d->logits;
+    e.stat_parts = s->stats_ws.p;
+    e.skip_col = c.mask_id;
     gemm(PC_LM_HEAD, x, m->lm_head.p, c.vocab, dm, e);
   }
   {
     ProfScope ps(pf, st, PC_STATS);
-    StatsRows sr{t.prev_row, t.save_row, s->prev_logits.p, s->prev_logits.p, (const float*)s->prev_lse.p, (float*)s->prev_lse.p};
-    StatsOut so{d->max_logit, d->lse, d->entropy, d->kl, d->conf, d->argmax};
-    launch_vocab_stats<T>((const T*)d->logits, rows, c.vocab, c.mask_id, sr, so, s->stats_ws.p, st);
+    if (fused) launch_stats_merge(s->stats_ws.p, rows, gemm_bf16_stat_parts(rows, c.vocab), c.vocab, sr, so, st);
+    else launch_vocab_stats<T>((const T*)d->logits, rows, c.vocab, c.mask_id, sr, so, s->stats_ws.p, st);
   }
   return DLM_OK;
 }

@@ -62,9 +62,10 @@ __global__ void pack_act_kernel(const bf16x8* __restrict__ x, bf16x8* __restrict
 //           count when its 96-column groups are exactly one per compute unit (gate/up of an 8B model), or when the skinny
 //           kernel would need a second round for a few column tiles (QKV of a 7B model with grouped-query heads);
 //   macro   more rows than that when the matrix has enough 128 x 256 tiles of its own (wide from 161 rows, narrow from 257);
-//   tiled   the rest, and the LM head up to 64 rows (no workspace: no K split).
+//   tiled   the rest, and the LM head up to 64 rows (no workspace: no K split), with or without the statistics epilogue.
 enum { KERNEL_SKINNY, KERNEL_MID, KERNEL_MACRO, KERNEL_TILED };
 int choose_kernel(int M, int N, int K, int kind) {
+  if (kind == EPI_STATS) return KERNEL_TILED;  // only the tiled kernel has that epilogue (the caller keeps to GEMM_STATS_MAX_ROWS rows)
   const int pr = weight_pack_rows(N);
   const bool whole_groups = N % (16 * pr) == 0;
   if (M <= GEMM_SKINNY_MAX_ROWS && kind != EPI_DIRECT && whole_groups) {
@@ -105,6 +106,7 @@ int gemm_bf16_ssq_chunks(int M, int N, int K) {
     default: return gemm_tiled_ssq_chunks(M, N);
   }
 }
+int gemm_bf16_stat_parts(int M, int N) { return gemm_tiled_stat_parts(M, N); }
 int gemm_bf16_counters(int max_rows, int max_n) {
   const int a = gemm_tiled_counters(max_rows, max_n), b = gemm_mid_counters(max_n), c = gemm_macro_counters(max_rows, max_n);
   return a > b ? (a > c ? a : c) : (b > c ? b : c);

@@ -18,6 +18,7 @@
 // workgroup that arrives last at the tile's ticket re-reads the partial tiles into the accumulator
 // layout, adding them in split order (deterministic), and runs the epilogue.
 #include "gemm_epilogue.h"
+#include "stats_part.h"
 
 namespace {
 
@@ -29,6 +30,44 @@ constexpr int SC1 = 16;  // cache-policy bit of the raw-buffer builtins: device 
 
 __device__ inline __amdgpu_buffer_rsrc_t tile_rsrc(const float* base) {
   return __builtin_amdgcn_make_buffer_rsrc((void*)base, 0, 0x7fffffff, 0x00020000);
+}
+
+// The part of a row's online-softmax state that a pass without a previous-step distribution needs (stats_part.h has the whole):
+// maximum (= the best logit), sum e^(z-m), sum e^(z-m)(z-m), lowest token id of the maximum.
+struct LiteState {
+  float m, s, t;
+  int bi;
+};
+__device__ __attribute__((always_inline)) inline LiteState lite_merge(const LiteState a, const LiteState b) {
+  LiteState r;
+  r.m = fmaxf(a.m, b.m);
+  const float da = a.m - r.m, db = b.m - r.m;
+  const float fa = __expf(da), fb = __expf(db);
+  r.s = fa * a.s + fb * b.s;
+  r.t = fa * (a.t + da * a.s) + fb * (b.t + db * b.s);
+  r.bi = (b.m > a.m || (b.m == a.m && b.bi < a.bi)) ? b.bi : a.bi;
+  return r;
+}
+__device__ __attribute__((always_inline)) inline LiteState lite_shfl_xor(const LiteState p, int o) {
+  return LiteState{__shfl_xor(p.m, o, 64), __shfl_xor(p.s, o, 64), __shfl_xor(p.t, o, 64), __shfl_xor(p.bi, o, 64)};
+}
+// state of four consecutive logits, token ids n .. n+3, token `skip` left out
+__device__ __attribute__((always_inline)) inline LiteState lite_of(f32x4 v, int n, int skip) {
+  float z[4];
+#pragma unroll
+  for (int i = 0; i < 4; ++i) z[i] = (float)(bf16_t)v[i];  // the logit as stored
+  LiteState r{NEG_BIG, 0.f, 0.f, 0x7fffffff};
+#pragma unroll
+  for (int i = 0; i < 4; ++i)
+    if (n + i != skip && z[i] > r.m) { r.m = z[i]; r.bi = n + i; }  // ascending ids and strict '>' keep the lowest id
+#pragma unroll
+  for (int i = 0; i < 4; ++i) {
+    if (n + i == skip) continue;
+    const float d = z[i] - r.m, ex = __expf(d);
+    r.s += ex;
+    r.t = fmaf(ex, d, r.t);
+  }
+  return r;
 }
 
 // TR column tiles per wavefront (workgroups of 64 TR columns); PR = 2: weights packed in interleaved pairs, 1: single runs.
@@ -184,6 +223,43 @@ __global__ __launch_bounds__(TPB) void gemm_tiled_kernel(const bf16x8* __restric
     }
   }
 
+  if constexpr (EPI == EPI_STATS) {
+    // logits as EPI_DIRECT writes them, and the online-softmax state of this workgroup's columns of every row, over the values as
+    // written: lane -> the four lanes of a row -> the wavefront's tiles -> the four wavefronts, each in a fixed order
+    __shared__ LiteState s_state[4][MT * 16];
+    LiteState acc_state[MT];
+#pragma unroll
+    for (int j = 0; j < MT; ++j) acc_state[j] = LiteState{NEG_BIG, 0.f, 0.f, 0x7fffffff};
+#pragma unroll
+    for (int r = 0; r < TR; ++r) {
+      if (nt0 + r >= NT) continue;  // uniform in the wavefront
+#pragma unroll
+      for (int j = 0; j < MT; ++j) {
+        const int m = m_lo + j * 16 + ml, n = (nt0 + r) * 16 + 4 * g;
+        const f32x4 v = acc[r][j] * s_rinv[j * 16 + ml];
+        if (m < M) *(bf16x4*)(e.out_bf16 + (size_t)m * N + n) = to_bf16x4(v);
+        acc_state[j] = lite_merge(acc_state[j], lite_of(v, n, e.skip_col));
+      }
+    }
+#pragma unroll
+    for (int j = 0; j < MT; ++j) {
+      acc_state[j] = lite_merge(acc_state[j], lite_shfl_xor(acc_state[j], 16));
+      acc_state[j] = lite_merge(acc_state[j], lite_shfl_xor(acc_state[j], 32));
+      if (g == 0) s_state[wave][j * 16 + ml] = acc_state[j];
+    }
+    __syncthreads();
+    const int m = m_lo + tid;
+    if (tid < MT * 16 && m < M) {
+      const LiteState w0 = s_state[0][tid], w1 = s_state[1][tid], w2 = s_state[2][tid], w3 = s_state[3][tid];
+      const LiteState r = lite_merge(lite_merge(lite_merge(w0, w1), w2), w3);
+      f32x4* dst = (f32x4*)((Part*)e.stat_parts + (size_t)m * groups + group);  // Part{m, s, t, w = 0, bv = m, bi, pm, ps = 0}
+      static_assert(sizeof(Part) == 32 && offsetof(Part, bv) == 16 && offsetof(Part, bi) == 20, "Part is written as two vectors");
+      dst[0] = f32x4{r.m, r.s, r.t, 0.f};
+      dst[1] = f32x4{r.m, __int_as_float(r.bi), NEG_BIG, 0.f};
+    }
+    return;
+  }
+
   float ssq[MT];
 #pragma unroll
   for (int j = 0; j < MT; ++j) ssq[j] = 0.f;
@@ -240,6 +316,16 @@ void launch_mt(const bf16_t* xt, const bf16_t* wt, int M, int N, int K, const Pl
 #undef GO
 }
 
+// EPI_STATS serves at most GEMM_STATS_MAX_ROWS = 64 rows: four row tiles
+void launch_stats(const bf16_t* xt, const bf16_t* wt, int M, int N, int K, const Plan& p, const GemmEpi& e, hipStream_t st) {
+  switch (p.mt) {
+    case 1: launch_mt<1, EPI_STATS>(xt, wt, M, N, K, p, e, st); break;
+    case 2: launch_mt<2, EPI_STATS>(xt, wt, M, N, K, p, e, st); break;
+    case 3: launch_mt<3, EPI_STATS>(xt, wt, M, N, K, p, e, st); break;
+    default: launch_mt<4, EPI_STATS>(xt, wt, M, N, K, p, e, st); break;
+  }
+}
+
 template <int EPI>
 void launch_epi(const bf16_t* xt, const bf16_t* wt, int M, int N, int K, const Plan& p, const GemmEpi& e, hipStream_t st) {
   switch (p.mt) {
@@ -259,11 +345,13 @@ void launch_epi(const bf16_t* xt, const bf16_t* wt, int M, int N, int K, const P
 void gemm_tiled_set_target(int wgs) { g_target_wgs = wgs; }
 int gemm_tiled_splits(int M, int N, int K) { return plan(M, N, K).splits; }
 int gemm_tiled_ssq_chunks(int M, int N) { return plan(M, N, 32).groups; }
+int gemm_tiled_stat_parts(int M, int N) { return plan(M, N, 32, false).groups; }
 int gemm_tiled_counters(int max_rows, int max_n) { return ((max_n + 127) / 128) * (((max_rows + 15) / 16 + 7) / 8); }  // 128-column groups are the narrowest
 
 void launch_gemm_tiled(const bf16_t* xt, const bf16_t* wt, int M, int N, int K, const GemmEpi& e, hipStream_t st) {
-  const Plan p = plan(M, N, K, e.kind != EPI_DIRECT);  // EPI_DIRECT has no workspace
+  const Plan p = plan(M, N, K, e.kind != EPI_DIRECT && e.kind != EPI_STATS);  // the LM head's epilogues have no workspace
   switch (e.kind) {
+    case EPI_STATS: launch_stats(xt, wt, M, N, K, p, e, st); break;
     case EPI_QKV: launch_epi<EPI_QKV>(xt, wt, M, N, K, p, e, st); break;
     case EPI_SWIGLU: launch_epi<EPI_SWIGLU>(xt, wt, M, N, K, p, e, st); break;
     case EPI_RESID: launch_epi<EPI_RESID>(xt, wt, M, N, K, p, e, st); break;

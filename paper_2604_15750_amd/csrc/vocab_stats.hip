@@ -4,46 +4,11 @@
 // and from those  lse = m + ln s,  conf = 1/s,  H = ln s - t/s,  KL(p||p') = w/s - lse + lse'.
 // The kernel is a pure HBM stream: 16-byte loads, several in flight per lane, rows split over
 // enough workgroups to fill 256 CUs; partial states are merged in a fixed order (deterministic).
-#include "common.h"
+#include "stats_part.h"
 
 namespace {
 
 constexpr int TPB = 256;
-constexpr float NEG_BIG = -3.0e38f;   // "minus infinity" that keeps every product finite
-constexpr float MASKED = -1.0e30f;    // logit given to the mask token: e^(MASKED - m) == 0
-
-struct Part {  // online-softmax state of a slice of one row
-  float m, s, t, w;
-  float bv;    // best logit
-  int bi;      // its token id
-  float pm, ps;  // max and sum e^(z'-pm) of the previous-step row (only when its lse is not stored)
-};
-
-__device__ inline Part part_init() { return Part{NEG_BIG, 0.f, 0.f, 0.f, NEG_BIG, 0x7fffffff, NEG_BIG, 0.f}; }
-
-__device__ inline Part part_merge(const Part& a, const Part& b) {
-  Part r;
-  r.m = fmaxf(a.m, b.m);
-  float da = a.m - r.m, db = b.m - r.m;
-  float fa = __expf(da), fb = __expf(db);
-  r.s = fa * a.s + fb * b.s;
-  r.t = fa * (a.t + da * a.s) + fb * (b.t + db * b.s);
-  r.w = fa * a.w + fb * b.w;
-  bool tb = (b.bv > a.bv) || (b.bv == a.bv && b.bi < a.bi);
-  r.bv = tb ? b.bv : a.bv;
-  r.bi = tb ? b.bi : a.bi;
-  r.pm = fmaxf(a.pm, b.pm);
-  r.ps = __expf(a.pm - r.pm) * a.ps + __expf(b.pm - r.pm) * b.ps;
-  return r;
-}
-
-__device__ inline Part part_shfl_xor(const Part& p, int o) {
-  Part r;
-  r.m = __shfl_xor(p.m, o, 64); r.s = __shfl_xor(p.s, o, 64); r.t = __shfl_xor(p.t, o, 64); r.w = __shfl_xor(p.w, o, 64);
-  r.bv = __shfl_xor(p.bv, o, 64); r.bi = __shfl_xor(p.bi, o, 64); r.pm = __shfl_xor(p.pm, o, 64); r.ps = __shfl_xor(p.ps, o, 64);
-  return r;
-}
-
 // the 64 lane states of a wavefront -> one (valid in every lane): all lanes move to the wavefront's maximum first, then the sums are
 // plain butterflies in a fixed order (deterministic), which costs one exp per lane instead of four per butterfly step
 __device__ inline Part part_wave_reduce(const Part& p) {
@@ -223,11 +188,18 @@ __global__ __launch_bounds__(TPB) void vocab_stats_kernel(const T* __restrict__ 
   }
 }
 
-// one wavefront per row: lane c holds the partial state of chunk c; fixed butterfly order
+// one wavefront per row: lane c holds the partial state of chunk c (of chunks c, c + 64, ... merged in that order); fixed butterfly order
 __global__ __launch_bounds__(64) void vocab_stats_merge_kernel(const Part* __restrict__ parts, int rows, int nchunks, int vocab, StatsRows sr,
                                                                StatsOut o) {
   const int row = blockIdx.x, lane = threadIdx.x;
   Part r = lane < nchunks ? parts[(size_t)row * nchunks + lane] : part_init();
+  for (int c0 = 64; c0 < nchunks; c0 += 512) {  // more states than lanes (the LM-head epilogue's): eight loads in flight, added in order
+    Part q[8];
+#pragma unroll
+    for (int i = 0; i < 8; ++i) q[i] = c0 + 64 * i + lane < nchunks ? parts[(size_t)row * nchunks + c0 + 64 * i + lane] : part_init();
+#pragma unroll
+    for (int i = 0; i < 8; ++i) r = part_merge(r, q[i]);
+  }
 #pragma unroll
   for (int ofs = 32; ofs > 0; ofs >>= 1) r = part_merge(r, part_shfl_xor(r, ofs));
   if (lane != 0) return;
@@ -253,6 +225,10 @@ int pick_chunks(int rows, int vocab, int vec) {
 }  // namespace
 
 size_t stats_workspace_bytes(int rows) { return (size_t)rows * MAX_CHUNKS * sizeof(Part); }
+
+void launch_stats_merge(const void* parts, int rows, int nparts, int vocab, const StatsRows& sr, const StatsOut& o, hipStream_t st) {
+  vocab_stats_merge_kernel<<<rows, 64, 0, st>>>((const Part*)parts, rows, nparts, vocab, sr, o);
+}
 
 template <typename T>
 void launch_vocab_stats(const T* logits, int rows, int vocab, int mask_id, const StatsRows& sr, const StatsOut& o, void* workspace, hipStream_t st) {

@@ -64,6 +64,7 @@ class Decoder:
         self.rows_log = []  # rows of every dlm_step launch
         self.pass_log = []  # per launch: (rows of each packed sequence, cached prefix length of each)
         self.kl_rows = 0    # rows compared with their retained distribution (Eq. 3), all launches together
+        self.stat_log = []  # per launch: (rows, rows compared with or retained as a previous-step distribution)
         self.step_events = []  # (rows, start, end) events around every dlm_step launch when time_steps is set
 
     def _plan(self, b):
@@ -121,6 +122,7 @@ class Decoder:
         self.rows_log.append(row_off[-1])
         self.pass_log.append(([plans[b][1] for b in group], [plans[b][0] for b in group]))
         self.kl_rows += sum(plans[b][4] for b in group)
+        self.stat_log.append((row_off[-1], sum(plans[b][4] + plans[b][6] for b in group)))
         for b in group:
             self.nfe[b] += 1
         # block-boundary decisions for the sequences that just finished a block (or the prompt)

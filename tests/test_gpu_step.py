@@ -383,3 +383,41 @@ def test_tiny_f32_free_run_equals_stored_decode(device, name):
     assert got["tokens"][0].tolist() == ref["tokens"]
     dec.close()
     model.close()
+
+
+# a vocabulary of 129 column groups of the LM head, the last one a quarter full; the mask token sits inside a group
+WIDE_VOCAB = inputs.model_config(1, 256, 2, 2, 128, 512, 16416, "bf16")
+
+
+@pytest.mark.parametrize("L", [1, 8, 24, 64])
+def test_statistics_from_the_lm_head_epilogue(device, L):
+    """An in-block pass (no row compared, none retained) takes its statistics from the LM head's epilogue: the same pass with that
+    switched off gives the same logits bit for bit and the same statistics to rounding, and both agree with the oracle's statistics
+    of those logits (Sec. 4.2 entropy; Sec. 4.3 confidence and prediction)."""
+    cfg = WIDE_VOCAB
+    W = _weights(cfg, 11, device)
+    model = api.Model(cfg, W)
+    P, look, mask = 40, 64, cfg["mask_id"]
+    prompt = inputs.make_prompts(cfg, 1, P, seed=11)[0]
+    tokens = torch.full((P + look,), mask, dtype=torch.int32, device=device)
+    tokens[:P] = torch.from_numpy(prompt.astype(np.int32)).to(device)
+    results = []
+    for fused in (True, False):
+        state = api.State(model, 1, P + look, P + look, look)
+        state.fuse_stats(fused)
+        out = api.StepOutputs(P + look, cfg["vocab"], model.torch_dtype, device)
+        api.dlm_step(state, tokens, out, [0, P + look], [0], [P], [0], kl_first=[0], kl_count=[0], save_first=[P], save_count=[look])
+        api.dlm_step(state, tokens, out, [0, L], [P], [0], [P], kl_first=[0], kl_count=[0], save_first=[0], save_count=[0])
+        torch.cuda.synchronize()
+        results.append({k: getattr(out, k)[:L].cpu().numpy() for k in ("max_logit", "lse", "entropy", "conf", "argmax", "kl")})
+        results[-1]["z"] = o_fwd.widen(inputs.tensor_to_numpy(out.logits[:L]))
+        state.close()
+    a, b = results
+    assert (a["z"] == b["z"]).all()
+    st = o_stats.vocab_stats(a["z"], mask)
+    for got in (a, b):
+        for key in ("max_logit", "lse", "entropy", "conf"):
+            assert (np.abs(got[key] - st[key]) <= 1e-5 * np.maximum(1.0, np.abs(st[key]))).all(), key
+        assert (got["argmax"] == st["argmax"]).all() and (got["kl"] == 0).all()
+    assert (a["max_logit"] == b["max_logit"]).all()
+    model.close()
