@@ -100,3 +100,15 @@ def test_model_and_component_argument_errors():
     assert L.dlm_attention(one, one, one, one, 4, 4, 4, 3, 32, 0, None) == -2
     assert L.dlm_attention(one, one, one, one, 4, 4, 4, 2, 48, 0, None) == -2
     assert L.dlm_vocab_stats_workspace(0) == 0 and L.dlm_vocab_stats_workspace(64) > 0
+
+
+def test_committed_traffic_summary_feeds_the_bench_line():
+    """bench.py takes roofline.traffic of the default workload from the committed counter summary: it must hold both figures, and
+    they must be within a few per cent of the kernel's algorithmic bytes (more would mean re-reads from HBM)."""
+    import sys
+    if ROOT not in sys.path:
+        sys.path.insert(0, ROOT)
+    import bench
+    t = bench.traffic_from_profile("llada8b_p256_g256")
+    algorithmic = 2 * 24576 * 4096  # the gate/up weights of the 8B shape, bf16
+    assert t is not None and 0.98 * algorithmic < t < 1.10 * algorithmic
