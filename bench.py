@@ -164,6 +164,8 @@ def main():
     ap.add_argument("--stats", default="epilogue", choices=["epilogue", "streamed"],
                     help="where passes that compare and retain no row (at most 64 rows) take their vocabulary statistics: the LM head's "
                          "epilogue (the default) or the streamed reduction every other pass uses")
+    ap.add_argument("--weight-copies", type=int, default=1, choices=[0, 1],
+                    help="0: no step-major second copies of the layer matrices (sets DLM_W_STEPS=0 for dlm_model_create)")
     ap.add_argument("--micro", default="", choices=["", "vocab_stats", "peaks"],
                     help="time one kernel alone instead of the decode (peaks: a plain HBM read and a matrix-core loop, what the GPU achieves)")
     ap.add_argument("--rows", type=int, default=3072, help="--micro: rows of the pass (3072 = 16 sequences x 192 rows, the widest batched pass)")
@@ -208,6 +210,8 @@ def main():
         nl = min(args.cpu_layers, cfg["n_layers"])
         W_host = {k: ([inputs.tensor_to_numpy(t) for t in v[:nl]] if isinstance(v, list) else inputs.tensor_to_numpy(v))
                   for k, v in W.items()}
+    if not args.weight_copies:
+        os.environ["DLM_W_STEPS"] = "0"
     model = api.Model(cfg, W)
     del W
     torch.cuda.empty_cache()
@@ -287,7 +291,7 @@ def main():
         "value": tokens / elapsed, "unit": "tokens/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
         "ms_per_step": elapsed / args.steps * 1e3, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": cfg["dtype"], "data": "synthetic",
-        "config": {"workload": args.workload, "batch": B, "prompt_len": P, "gen_len": N, "l_max": lmax, "n_layers": cfg["n_layers"],
+        "config": {"workload": args.workload, "batch": B, "prompt_len": P, "gen_len": N, "l_max": lmax, "n_layers": cfg["n_layers"], "weight_copies": args.weight_copies, "stats": args.stats,
                    "thresholds": "paper defaults (lambda 1.2, L_min 8, tau 0.8/0.95, gamma -16)" if args.thresholds == "paper" else
                                  "scaled to a random-init model (lambda 0.9, L_min 8, tau 0.04/0.25, gamma -36)"},
         "nfe": passes / B, "tokens_per_pass": B * N / passes, "launches_per_decode": res["launches"],

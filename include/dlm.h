@@ -67,6 +67,11 @@ typedef struct dlm_state dlm_state;
 
 /* Copies the weights into library-owned device memory (bf16 matrices are re-tiled for the matrix
  * cores on `stream`).  The caller may release its own tensors once `stream` has been synchronised.
+ * bf16 layer matrices are kept twice where the kernel that serves passes of up to 16 or 32 rows has a
+ * layout of its own for them (what all workgroups read at the same step adjacent in memory): the
+ * model then takes up to twice its layer weights (30 GB for an 8B model).  A copy that does not fit
+ * is left out; the environment variable DLM_W_STEPS=0, read by this call, leaves them all out
+ * (results are bit-identical either way: the same products are added in the same order).
  * Errors: DLM_EINVAL (null pointer, bad dtype), DLM_ESHAPE (unsupported dimensions), DLM_ENOMEM. */
 int dlm_model_create(const dlm_config* cfg, const dlm_weights* w, void* stream, dlm_model** out);
 void dlm_model_destroy(dlm_model* m);

@@ -126,6 +126,14 @@ __host__ __device__ inline int weight_source_row(int n, int perm, int param) {
 }
 __host__ __device__ inline int weight_pack_rows(int N) { return N <= 8192 ? 1 : 2; }  // narrow matrices: one run per 16-column tile
 void launch_pack_weight(const bf16_t* w, bf16_t* out, int N, int K, int perm, int perm_param, hipStream_t st);
+// W [N, K] row-major -> step-major fragments for the kernel that serves (N, K) at up to 16 rows: column groups of ct tiles
+// and W = 4 wavefronts per workgroup (the mid kernel's no-split launches), or ct = 1 and W = 8 (the skinny kernel's 16-column
+// workgroups).  The fragment (column tile g ct + r, k-tile w KT/W + s) that wavefront w of workgroup g reads at its step s sits
+// at (((s G + g) W + w) ct + r) KiB, G = N / (16 ct): what all workgroups read at the same step is one run of memory, and the
+// chip's reads at any moment are one moving window instead of thousands of separate streams.
+void launch_pack_weight_steps(const bf16_t* w, bf16_t* out, int N, int K, int ct, int perm, int perm_param, hipStream_t st);
+int gemm_bf16_steps_ct(int N, int K);  // ct of that layout for (N, K), 0 if the kernel that serves 16 rows has none
+int gemm_mid_steps_ct(int N, int K);   // ... if the mid kernel serves (N, K) at up to 16 rows without a K split, else 0
 void launch_pack_act(const bf16_t* x, bf16_t* out, int M, int K, hipStream_t st);  // row-major -> fragment tiles (rows padded to 16 with zeros)
 int gemm_bf16_splits(int M, int N, int K);         // partial tiles [splits][M][N] the launch of this shape needs in GemmEpi::part (1: none)
 int gemm_bf16_ssq_chunks(int M, int N, int K);     // chunks per row of the sums of squares an EPI_RESID launch of this shape writes
@@ -170,6 +178,9 @@ struct GemmEpi {
   // token skip_col left out) to stat_parts[m][gemm_bf16_stat_parts(N)]
   void* stat_parts;
   int skip_col;
+  // optional second copy of W in the step-major layout (launch_pack_weight_steps) of column groups of w_steps_ct tiles
+  const bf16_t* w_steps;
+  int w_steps_ct;
 };
 constexpr int GEMM_STATS_MAX_ROWS = 64;
 int gemm_bf16_stat_parts(int M, int N);              // column groups per row an EPI_STATS launch of this shape writes states for

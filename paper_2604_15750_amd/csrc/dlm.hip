@@ -7,6 +7,7 @@
 #include <vector>
 
 #include "common.h"
+#include <cstdlib>
 
 // ---- errors ------------------------------------------------------------------------------------
 static thread_local char g_err[512] = "";
@@ -52,6 +53,10 @@ struct dlm_model {
   dlm_config cfg;
   DevBuf embed, final_norm, lm_head;
   std::vector<DevBuf> wqkv, wo, w_gate_up, w_down, norm1, norm2;
+  // second copies of the layer matrices in the step-major layout of the kernel that serves narrow passes (empty when that
+  // kernel has no such layout for the shape): 0.44 GB per layer of an 8B model, 14 GB of 288 in all
+  std::vector<DevBuf> w_steps[4];  // QKV, O, gate/up, down
+  int steps_ct[4] = {0, 0, 0, 0};
 };
 
 thread_local LaunchStamp g_launch_stamp = {nullptr, nullptr};
@@ -175,6 +180,29 @@ extern "C" int dlm_model_create(const dlm_config* cfg, const dlm_weights* w, voi
         step(copy_matrix(m->w_gate_up[l], w->w_gate_up[l], 2 * cfg->d_ffn, d, dt, st, PERM_GATED, cfg->d_ffn)) &&
         step(copy_matrix(m->w_down[l], w->w_down[l], d, cfg->d_ffn, dt, st)) && step(copy_gain(m->norm1[l], w->norm1[l], d, dt, st)) &&
         step(copy_gain(m->norm2[l], w->norm2[l], d, dt, st));
+  }
+  // Second copies of the layer matrices in the step-major layout of the kernel that serves narrow passes (gemm_bf16_steps_ct),
+  // unless the environment says DLM_W_STEPS=0.  They are an optimisation: a matrix whose copy does not fit goes without.
+  if (rc == DLM_OK && dt == DLM_BF16 && !(getenv("DLM_W_STEPS") && atoi(getenv("DLM_W_STEPS")) == 0)) {
+    const int shape[4][4] = {{qkv, d, PERM_ROTARY, cfg->head_dim}, {d, qd, PERM_NONE, 0}, {2 * cfg->d_ffn, d, PERM_GATED, cfg->d_ffn}, {d, cfg->d_ffn, PERM_NONE, 0}};
+    for (int k = 0; k < 4; ++k) {
+      m->steps_ct[k] = gemm_bf16_steps_ct(shape[k][0], shape[k][1]);
+      if (!m->steps_ct[k]) continue;
+      m->w_steps[k] = std::vector<DevBuf>(L);
+      for (int l = 0; l < L; ++l) {
+        void* p = nullptr;
+        if (hipMalloc(&p, (size_t)shape[k][0] * shape[k][1] * 2) != hipSuccess) {
+          (void)hipGetLastError();
+          (void)hipStreamSynchronize(st);  // the packing kernels of the earlier layers write into what is released next
+          m->w_steps[k].clear();
+          m->steps_ct[k] = 0;
+          break;
+        }
+        m->w_steps[k][l].p = p;
+        const void* src = k == 0 ? w->wqkv[l] : k == 1 ? w->wo[l] : k == 2 ? w->w_gate_up[l] : w->w_down[l];
+        launch_pack_weight_steps((const bf16_t*)src, (bf16_t*)p, shape[k][0], shape[k][1], m->steps_ct[k], shape[k][2], shape[k][3], st);
+      }
+    }
   }
   if (rc != DLM_OK) { delete m; return rc; }
   *out = m;
@@ -414,6 +442,7 @@ int run_step_bf16(dlm_state* s, const dlm_step_desc* d, const SeqMeta& meta, con
       e.row_pos = t.row_pos; e.row_slot = t.row_slot; e.rope_cos = t.rope_cos; e.rope_sin = t.rope_sin;
       e.q = q; e.kcache = kc; e.vcache = vc; e.slot_stride = s->slot_stride; e.head_stride = s->head_stride;
       e.n_q = nq; e.n_kv = nkv; e.hd = hd;
+      if (m->steps_ct[0]) { e.w_steps = (const T*)m->w_steps[0][l].p; e.w_steps_ct = m->steps_ct[0]; }
       gemm(PC_QKV, x, m->wqkv[l].p, qd + 2 * nkv * hd, dm, e);
     }
     { ProfScope ps(pf, st, PC_ATTENTION);
@@ -422,6 +451,7 @@ int run_step_bf16(dlm_state* s, const dlm_step_desc* d, const SeqMeta& meta, con
       GemmEpi e = base;
       e.kind = EPI_RESID;
       e.h = h; e.gain = (const float*)m->norm2[l].p; e.x = x; e.ssq_out = ssq;
+      if (m->steps_ct[1]) { e.w_steps = (const T*)m->w_steps[1][l].p; e.w_steps_ct = m->steps_ct[1]; }
       gemm(PC_O, x2, m->wo[l].p, dm, qd, e);
       nch = gemm_bf16_ssq_chunks(rows, dm, qd);
     }
@@ -430,6 +460,7 @@ int run_step_bf16(dlm_state* s, const dlm_step_desc* d, const SeqMeta& meta, con
       e.kind = EPI_SWIGLU;
       e.rs = RowScale{ssq, nch, 1.f / (float)dm, c.rms_eps};
       e.act = act; e.ffn = ffn;
+      if (m->steps_ct[2]) { e.w_steps = (const T*)m->w_steps[2][l].p; e.w_steps_ct = m->steps_ct[2]; }
       gemm(PC_GATE_UP, x, m->w_gate_up[l].p, 2 * ffn, dm, e);
     }
     {
@@ -437,6 +468,7 @@ int run_step_bf16(dlm_state* s, const dlm_step_desc* d, const SeqMeta& meta, con
       e.kind = EPI_RESID;
       e.h = h; e.gain = l + 1 < c.n_layers ? (const float*)m->norm1[l + 1].p : (const float*)m->final_norm.p;
       e.x = x; e.ssq_out = ssq;
+      if (m->steps_ct[3]) { e.w_steps = (const T*)m->w_steps[3][l].p; e.w_steps_ct = m->steps_ct[3]; }
       gemm(PC_DOWN, act, m->w_down[l].p, dm, ffn, e);
       nch = gemm_bf16_ssq_chunks(rows, dm, ffn);
     }

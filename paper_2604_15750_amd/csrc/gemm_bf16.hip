@@ -40,6 +40,22 @@ __global__ void pack_weight_kernel(const bf16x8* __restrict__ w, bf16x8* __restr
   }
 }
 
+__global__ void pack_weight_steps_kernel(const bf16x8* __restrict__ w, bf16x8* __restrict__ out, int N, int K, int ct, int nwv, int perm, int param) {
+  const int KT = K >> 5, G = N / (16 * ct), per = KT / nwv;
+  const size_t total = (size_t)(N >> 4) * KT * 64;
+  for (size_t idx = (size_t)blockIdx.x * blockDim.x + threadIdx.x; idx < total; idx += (size_t)gridDim.x * blockDim.x) {
+    const int lane = idx & 63;
+    size_t f = idx >> 6;
+    const int r = f % ct; f /= ct;
+    const int wv = f % nwv; f /= nwv;
+    const int grp = f % G;
+    const int s = (int)(f / G);
+    const int n = weight_source_row((grp * ct + r) * 16 + (lane & 15), perm, param);
+    const int k8 = (wv * per + s) * 4 + (lane >> 4);
+    out[idx] = w[(size_t)n * (K >> 3) + k8];
+  }
+}
+
 // X [M, K] row-major -> fragment tiles [ceil(M/16)][K/32]; rows beyond M are zero.
 __global__ void pack_act_kernel(const bf16x8* __restrict__ x, bf16x8* __restrict__ out, int M, int K) {
   const int KT = K >> 5;
@@ -85,6 +101,16 @@ int choose_kernel(int M, int N, int K, int kind) {
 
 void launch_pack_weight(const bf16_t* w, bf16_t* out, int N, int K, int perm, int perm_param, hipStream_t st) {
   pack_weight_kernel<<<2048, 256, 0, st>>>((const bf16x8*)w, (bf16x8*)out, N, K, weight_pack_rows(N), perm, perm_param);
+}
+void launch_pack_weight_steps(const bf16_t* w, bf16_t* out, int N, int K, int ct, int perm, int perm_param, hipStream_t st) {
+  pack_weight_steps_kernel<<<2048, 256, 0, st>>>((const bf16x8*)w, (bf16x8*)out, N, K, ct, ct == 1 ? 8 : 4, perm, perm_param);
+}
+int gemm_bf16_steps_ct(int N, int K) {
+  switch (choose_kernel(16, N, K, EPI_SUM)) {
+    case KERNEL_MID: return gemm_mid_steps_ct(N, K);
+    case KERNEL_SKINNY: return (weight_pack_rows(N) == 1 && (K >> 5) % 8 == 0) ? 1 : 0;
+    default: return 0;
+  }
 }
 void launch_pack_act(const bf16_t* x, bf16_t* out, int M, int K, hipStream_t st) {
   pack_act_kernel<<<512, 256, 0, st>>>((const bf16x8*)x, (bf16x8*)out, M, K);

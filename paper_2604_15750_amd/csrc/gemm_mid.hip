@@ -26,6 +26,7 @@
 namespace {
 
 constexpr int TPB = 256, NWV = 4;
+constexpr int MID_STEPS_MAX_MT = 2;  // row tiles up to which a launch may read the step-major copy of W
 #ifndef MID_WD_MAX
 #define MID_WD_MAX 4
 #endif
@@ -56,7 +57,8 @@ struct MidShape {
 };
 
 // grid.x = groups * splits; MT >= ceil(M / 16), and X has MT row tiles (the activation buffers are padded to 16 rows).
-template <int MT, int CT, int PR, int EPI>
+// STEPS: W is read from the step-major copy (e.w_steps) instead of wt.
+template <int MT, int CT, int PR, int EPI, bool STEPS = false>
 __global__ __launch_bounds__(TPB) void gemm_mid_kernel(const bf16x8* __restrict__ xt, const bf16x8* __restrict__ wt, int M, int N, int K,
                                                        int kt_per_split, int splits, GemmEpi e) {
   typedef MidShape<MT, CT> SH;
@@ -76,12 +78,18 @@ __global__ __launch_bounds__(TPB) void gemm_mid_kernel(const bf16x8* __restrict_
   const int per = (te - tb + NWV - 1) / NWV;
   const int t0 = tb + wave * per, t1 = min(te, t0 + per);  // this wavefront's k-tiles (possibly none)
 
-  constexpr size_t wstep = PR == 2 ? 128 : 64;
-  const bf16x8* wptr[CT];  // fragment (nt0 + r, k-tile t) = wptr[r][t * wstep]; column tiles past the end repeat the last one
+  // fragment (nt0 + r, k-tile t) = wptr[r][(t - tsub) * wstep]; column tiles past the end repeat the last one.  With the step-major
+  // copy (no K split, whole groups, KT a multiple of 4: the host checks) the wavefront's step s is at wptr[r][s * wstep]
+  static_assert(!STEPS || MT <= MID_STEPS_MAX_MT, "the larger variants have no register to spare for a run-time stride");
+  constexpr bool steps = STEPS;
+  const size_t wstep = steps ? (size_t)groups * NWV * CT * 64 : (PR == 2 ? 128 : 64);
+  const int tsub = steps ? t0 : 0;
+  const bf16x8* wptr[CT];
 #pragma unroll
   for (int r = 0; r < CT; ++r) {
     const int nt = min(nt0 + r, NT - 1);
-    wptr[r] = PR == 2 ? wt + ((size_t)(nt >> 1) * KT * 2 + (nt & 1)) * 64 + lane : wt + (size_t)nt * KT * 64 + lane;
+    wptr[r] = steps ? (const bf16x8*)e.w_steps + ((size_t)(group * NWV + wave) * CT + r) * 64 + lane
+                    : PR == 2 ? wt + ((size_t)(nt >> 1) * KT * 2 + (nt & 1)) * 64 + lane : wt + (size_t)nt * KT * 64 + lane;
   }
   const bf16x8* xptr = xt + lane;  // fragment (j, t) = xptr[(j * KT + t) * 64]
   // In the last row tile, lanes whose row does not exist re-read row 0 of their k-group instead of fetching lines of their
@@ -111,7 +119,7 @@ __global__ __launch_bounds__(TPB) void gemm_mid_kernel(const bf16x8* __restrict_
     for (int i = 0; i < KB; ++i) {
       const int tc = min(t0 + st * KB + i, t1 - 1);
 #pragma unroll
-      for (int r = 0; r < CT; ++r) w[slot][i][r] = wptr[r][(size_t)tc * wstep];
+      for (int r = 0; r < CT; ++r) w[slot][i][r] = wptr[r][(size_t)(tc - tsub) * wstep];
     }
   };
   auto compute = [&](const int ws, const int xs, int st) __attribute__((always_inline)) {
@@ -302,6 +310,17 @@ void launch_one(const bf16_t* xt, const bf16_t* wt, int M, int N, int K, const M
     (void)hipFuncSetAttribute((const void*)gemm_mid_kernel<MT, CT, PR, EPI>, hipFuncAttributeMaxDynamicSharedMemorySize, SH::LDS_BYTES);
     configured = true;
   }
+  if constexpr (MT <= MID_STEPS_MAX_MT) {
+    if (e.w_steps) {
+      static bool configured_steps = false;
+      if (!configured_steps) {
+        (void)hipFuncSetAttribute((const void*)gemm_mid_kernel<MT, CT, PR, EPI, true>, hipFuncAttributeMaxDynamicSharedMemorySize, SH::LDS_BYTES);
+        configured_steps = true;
+      }
+      DLM_LAUNCH((gemm_mid_kernel<MT, CT, PR, EPI, true>), p.groups * p.splits, TPB, SH::LDS_BYTES, st, (const bf16x8*)xt, (const bf16x8*)wt, M, N, K, p.kps, p.splits, e);
+      return;
+    }
+  }
   DLM_LAUNCH((gemm_mid_kernel<MT, CT, PR, EPI>), p.groups * p.splits, TPB, SH::LDS_BYTES, st, (const bf16x8*)xt, (const bf16x8*)wt, M, N, K, p.kps, p.splits, e);
 }
 
@@ -354,8 +373,16 @@ int gemm_mid_counters(int max_n) { return (max_n + 31) / 32; }  // 32-column gro
 void gemm_mid_set_target(int wgs) { g_mid_wgs = wgs; }
 
 
-void launch_gemm_mid(const bf16_t* xt, const bf16_t* wt, int M, int N, int K, const GemmEpi& e, hipStream_t st) {
-  const MidPlan p = mid_plan(M, N, K, e.kind != EPI_DIRECT);  // EPI_DIRECT has no workspace
+int gemm_mid_steps_ct(int N, int K) {
+  const MidPlan p = mid_plan(16, N, K, true);
+  return (gemm_mid_fills_chip(16, N, K) && N % (16 * p.ct) == 0 && (K >> 5) % NWV == 0) ? p.ct : 0;
+}
+
+void launch_gemm_mid(const bf16_t* xt, const bf16_t* wt, int M, int N, int K, const GemmEpi& e_in, hipStream_t st) {
+  const MidPlan p = mid_plan(M, N, K, e_in.kind != EPI_DIRECT);  // EPI_DIRECT has no workspace
+  GemmEpi e = e_in;
+  // the step-major copy serves exactly the launches it was laid out for
+  if (!(e.w_steps && p.mt <= MID_STEPS_MAX_MT && e.w_steps_ct == p.ct && p.splits == 1 && N % (16 * p.ct) == 0 && (K >> 5) % NWV == 0)) e.w_steps = nullptr;
   switch (e.kind) {
     case EPI_QKV: launch_epi<EPI_QKV>(xt, wt, M, N, K, p, e, st); break;
     case EPI_SWIGLU: launch_epi<EPI_SWIGLU>(xt, wt, M, N, K, p, e, st); break;

@@ -15,7 +15,8 @@ namespace {
 
 // grid.x = N / (16 R) workgroups of NWV wavefronts; wavefront w multiplies k-tiles [w*per, (w+1)*per) of the
 // workgroup's R column tiles against all MT row tiles, D k-tiles per batch, two batches of registers.
-template <int MT, int R, int NWV, int D, int EPI>
+// STEPS: W is read from the step-major copy (e.w_steps) instead of wt.
+template <int MT, int R, int NWV, int D, int EPI, bool STEPS = false>
 __global__ __launch_bounds__(NWV * 64) void gemm_skinny_kernel(const bf16x8* __restrict__ xt, const bf16x8* __restrict__ wt, int M, int N,
                                                                int K, GemmEpi e) {
   __shared__ f32x4 red[NWV][R * MT][64];
@@ -27,7 +28,13 @@ __global__ __launch_bounds__(NWV * 64) void gemm_skinny_kernel(const bf16x8* __r
   const bf16x8 zero8 = {0, 0, 0, 0, 0, 0, 0, 0};
   // lanes of the last row tile whose row does not exist re-read row 0 of their k-group (whatever they get is never stored)
   const int xlane_last = (MTILES - 1) * 16 + (lane & 15) < M ? lane : (lane & ~15);
-  const bf16x8* wbase = wt + (size_t)blockIdx.x * KT * R * 64 + lane;  // the workgroup's R tiles are one interleaved run
+  // the workgroup's R tiles are one interleaved run; in the step-major copy (R = 1, KT a multiple of NWV: the host checks) the
+  // wavefront's step s is fragment (s * workgroups + this workgroup) * NWV + wave
+  static_assert(!STEPS || R == 1, "the step-major copy is laid out for 16-column workgroups");
+  constexpr bool steps = STEPS;
+  const bf16x8* wbase = steps ? (const bf16x8*)e.w_steps + ((size_t)blockIdx.x * NWV + wave) * 64 + lane : wt + (size_t)blockIdx.x * KT * R * 64 + lane;
+  const size_t wstride = steps ? (size_t)gridDim.x * NWV * 64 : R * 64;
+  const int tsub = steps ? t_begin : 0;
 
   f32x4 acc[R][MT];
 #pragma unroll
@@ -42,7 +49,7 @@ __global__ __launch_bounds__(NWV * 64) void gemm_skinny_kernel(const bf16x8* __r
       const int t = tb + i;
       const bool ok = t < t_end;
 #pragma unroll
-      for (int r = 0; r < R; ++r) wreg[buf][i][r] = ok ? wbase[((size_t)t * R + r) * 64] : zero8;
+      for (int r = 0; r < R; ++r) wreg[buf][i][r] = ok ? wbase[(size_t)(t - tsub) * wstride + r * 64] : zero8;
 #pragma unroll
       for (int j = 0; j < MT; ++j) xreg[buf][i][j] = (ok && j < MTILES) ? xt[((size_t)j * KT + t) * 64 + (j == MTILES - 1 ? xlane_last : lane)] : zero8;
     }
@@ -88,7 +95,8 @@ __global__ __launch_bounds__(NWV * 64) void gemm_skinny_kernel(const bf16x8* __r
 // batch depth: 8 KiB of W in flight per wavefront for up to 32 rows, half of that beyond (the X fragments take the registers)
 template <int MT, int EPI>
 void launch_skinny(const bf16_t* xt, const bf16_t* wt, int pr, int M, int N, int K, const GemmEpi& e, hipStream_t st) {
-  if (pr == 1) DLM_LAUNCH((gemm_skinny_kernel<MT, 1, 8, (MT <= 2 ? 8 : 4), EPI>), N / 16, 512, 0, st, (const bf16x8*)xt, (const bf16x8*)wt, M, N, K, e);
+  if (pr == 1 && e.w_steps) DLM_LAUNCH((gemm_skinny_kernel<MT, 1, 8, (MT <= 2 ? 8 : 4), EPI, true>), N / 16, 512, 0, st, (const bf16x8*)xt, (const bf16x8*)wt, M, N, K, e);
+  else if (pr == 1) DLM_LAUNCH((gemm_skinny_kernel<MT, 1, 8, (MT <= 2 ? 8 : 4), EPI>), N / 16, 512, 0, st, (const bf16x8*)xt, (const bf16x8*)wt, M, N, K, e);
   else DLM_LAUNCH((gemm_skinny_kernel<MT, 2, 4, (MT <= 2 ? 4 : 2), EPI>), N / 32, 256, 0, st, (const bf16x8*)xt, (const bf16x8*)wt, M, N, K, e);
 }
 
@@ -102,7 +110,9 @@ void launch_epi(const bf16_t* xt, const bf16_t* wt, int pr, int M, int N, int K,
 
 }  // namespace
 
-void launch_gemm_skinny(const bf16_t* xt, const bf16_t* wt, int pr, int M, int N, int K, const GemmEpi& e, hipStream_t st) {
+void launch_gemm_skinny(const bf16_t* xt, const bf16_t* wt, int pr, int M, int N, int K, const GemmEpi& e_in, hipStream_t st) {
+  GemmEpi e = e_in;
+  if (!(e.w_steps && e.w_steps_ct == 1 && pr == 1 && (K >> 5) % 8 == 0)) e.w_steps = nullptr;  // the step-major copy serves the launches it was laid out for
   switch (e.kind) {
     case EPI_QKV: launch_epi<EPI_QKV>(xt, wt, pr, M, N, K, e, st); break;
     case EPI_SWIGLU: launch_epi<EPI_SWIGLU>(xt, wt, pr, M, N, K, e, st); break;

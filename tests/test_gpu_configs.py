@@ -256,3 +256,38 @@ def test_full_depth_decode_invariants_and_decisions(device, thresholds):
     print(thresholds, "NFE", nfe, "blocks", blocks, "selections checked exactly", exact_sel, "of", n_sel, "boundaries", exact_bnd, "of", n_bnd)
     dec.close()
     model.close()
+
+
+@pytest.mark.parametrize("name", ["llada8b_p256_g256", "dream7b_p512_g256"])
+def test_step_major_weight_copies_change_no_bit(device, name):
+    """The second, step-major copies of the layer matrices that narrow passes read (all four matrices at these widths) hold the
+    same fragments in another order, and the kernels add the same products in the same order: a prefill pass (standard layout
+    either way) and in-block passes of 8, 16 and 32 rows give bit-identical logits and statistics with and without the copies."""
+    import os
+    cfg, _, _, _, _ = _twin(name)
+    W = inputs.make_weights(cfg, seed=0, device=device)
+    P, look = 48, 32
+    tokens = torch.full((P + look,), cfg["mask_id"], dtype=torch.int32, device=device)
+    tokens[:P] = torch.from_numpy(inputs.make_prompts(cfg, 1, P)[0].astype(np.int32)).to(device)
+    results = []
+    for copies in ("1", "0"):
+        os.environ["DLM_W_STEPS"] = copies
+        try:
+            model = api.Model(cfg, W)
+        finally:
+            del os.environ["DLM_W_STEPS"]
+        got = []
+        for L in (8, 16, 32):
+            state = api.State(model, 1, P + look, P + look, look)
+            out = api.StepOutputs(P + look, cfg["vocab"], model.torch_dtype, device)
+            api.dlm_step(state, tokens, out, [0, P + look], [0], [P], [0], kl_first=[0], kl_count=[0], save_first=[P], save_count=[look])
+            api.dlm_step(state, tokens, out, [0, L], [P], [0], [P], kl_first=[0], kl_count=[0], save_first=[0], save_count=[0])
+            torch.cuda.synchronize()
+            got.append([out.logits[:L].clone()] + [getattr(out, k)[:L].clone() for k in ("max_logit", "lse", "entropy", "conf", "argmax")])
+            state.close()
+        results.append(got)
+        model.close()
+    for a, b in zip(*results):
+        for x, y in zip(a, b):
+            assert torch.equal(x, y)
+    assert float(results[0][0][0].float().abs().max()) > 0
