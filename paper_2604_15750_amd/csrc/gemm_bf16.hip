@@ -108,7 +108,10 @@ void launch_pack_weight_steps(const bf16_t* w, bf16_t* out, int N, int K, int ct
 int gemm_bf16_steps_ct(int N, int K) {
   switch (choose_kernel(16, N, K, EPI_SUM)) {
     case KERNEL_MID: return gemm_mid_steps_ct(N, K);
-    case KERNEL_SKINNY: return (weight_pack_rows(N) == 1 && (K >> 5) % 8 == 0) ? 1 : 0;
+    case KERNEL_SKINNY: {  // one column tile and 8 wavefronts per workgroup, or a pair of tiles and 4
+      const int pr = weight_pack_rows(N);
+      return ((K >> 5) % (pr == 1 ? 8 : 4) == 0 && N % (16 * pr) == 0) ? pr : 0;
+    }
     default: return 0;
   }
 }

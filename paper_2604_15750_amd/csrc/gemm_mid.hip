@@ -375,7 +375,7 @@ void gemm_mid_set_target(int wgs) { g_mid_wgs = wgs; }
 
 int gemm_mid_steps_ct(int N, int K) {
   const MidPlan p = mid_plan(16, N, K, true);
-  return (gemm_mid_fills_chip(16, N, K) && N % (16 * p.ct) == 0 && (K >> 5) % NWV == 0) ? p.ct : 0;
+  return (p.splits == 1 && N % (16 * p.ct) == 0 && (K >> 5) % NWV == 0) ? p.ct : 0;
 }
 
 void launch_gemm_mid(const bf16_t* xt, const bf16_t* wt, int M, int N, int K, const GemmEpi& e_in, hipStream_t st) {

@@ -28,12 +28,11 @@ __global__ __launch_bounds__(NWV * 64) void gemm_skinny_kernel(const bf16x8* __r
   const bf16x8 zero8 = {0, 0, 0, 0, 0, 0, 0, 0};
   // lanes of the last row tile whose row does not exist re-read row 0 of their k-group (whatever they get is never stored)
   const int xlane_last = (MTILES - 1) * 16 + (lane & 15) < M ? lane : (lane & ~15);
-  // the workgroup's R tiles are one interleaved run; in the step-major copy (R = 1, KT a multiple of NWV: the host checks) the
-  // wavefront's step s is fragment (s * workgroups + this workgroup) * NWV + wave
-  static_assert(!STEPS || R == 1, "the step-major copy is laid out for 16-column workgroups");
+  // the workgroup's R tiles are one interleaved run; in the step-major copy (KT a multiple of NWV: the host checks) the
+  // wavefront's step s is the R fragments from ((s * workgroups + this workgroup) * NWV + wave) * R on
   constexpr bool steps = STEPS;
-  const bf16x8* wbase = steps ? (const bf16x8*)e.w_steps + ((size_t)blockIdx.x * NWV + wave) * 64 + lane : wt + (size_t)blockIdx.x * KT * R * 64 + lane;
-  const size_t wstride = steps ? (size_t)gridDim.x * NWV * 64 : R * 64;
+  const bf16x8* wbase = steps ? (const bf16x8*)e.w_steps + ((size_t)blockIdx.x * NWV + wave) * R * 64 + lane : wt + (size_t)blockIdx.x * KT * R * 64 + lane;
+  const size_t wstride = steps ? (size_t)gridDim.x * NWV * R * 64 : R * 64;
   const int tsub = steps ? t_begin : 0;
 
   f32x4 acc[R][MT];
@@ -97,6 +96,7 @@ template <int MT, int EPI>
 void launch_skinny(const bf16_t* xt, const bf16_t* wt, int pr, int M, int N, int K, const GemmEpi& e, hipStream_t st) {
   if (pr == 1 && e.w_steps) DLM_LAUNCH((gemm_skinny_kernel<MT, 1, 8, (MT <= 2 ? 8 : 4), EPI, true>), N / 16, 512, 0, st, (const bf16x8*)xt, (const bf16x8*)wt, M, N, K, e);
   else if (pr == 1) DLM_LAUNCH((gemm_skinny_kernel<MT, 1, 8, (MT <= 2 ? 8 : 4), EPI>), N / 16, 512, 0, st, (const bf16x8*)xt, (const bf16x8*)wt, M, N, K, e);
+  else if (e.w_steps) DLM_LAUNCH((gemm_skinny_kernel<MT, 2, 4, (MT <= 2 ? 4 : 2), EPI, true>), N / 32, 256, 0, st, (const bf16x8*)xt, (const bf16x8*)wt, M, N, K, e);
   else DLM_LAUNCH((gemm_skinny_kernel<MT, 2, 4, (MT <= 2 ? 4 : 2), EPI>), N / 32, 256, 0, st, (const bf16x8*)xt, (const bf16x8*)wt, M, N, K, e);
 }
 
@@ -112,7 +112,8 @@ void launch_epi(const bf16_t* xt, const bf16_t* wt, int pr, int M, int N, int K,
 
 void launch_gemm_skinny(const bf16_t* xt, const bf16_t* wt, int pr, int M, int N, int K, const GemmEpi& e_in, hipStream_t st) {
   GemmEpi e = e_in;
-  if (!(e.w_steps && e.w_steps_ct == 1 && pr == 1 && (K >> 5) % 8 == 0)) e.w_steps = nullptr;  // the step-major copy serves the launches it was laid out for
+  // the step-major copy serves the launches it was laid out for: pr column tiles per workgroup, 8 wavefronts (pr 1) or 4 (pr 2)
+  if (!(e.w_steps && e.w_steps_ct == pr && (K >> 5) % (pr == 1 ? 8 : 4) == 0 && N % (16 * pr) == 0)) e.w_steps = nullptr;
   switch (e.kind) {
     case EPI_QKV: launch_epi<EPI_QKV>(xt, wt, pr, M, N, K, e, st); break;
     case EPI_SWIGLU: launch_epi<EPI_SWIGLU>(xt, wt, pr, M, N, K, e, st); break;
