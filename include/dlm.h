@@ -67,7 +67,7 @@ typedef struct dlm_state dlm_state;
 
 /* Copies the weights into library-owned device memory (bf16 matrices are re-tiled for the matrix
  * cores on `stream`).  The caller may release its own tensors once `stream` has been synchronised.
- * bf16 layer matrices are kept twice where the kernel that serves passes of up to 16 or 32 rows has a
+ * bf16 layer matrices are kept twice where the kernel that serves passes of up to 16 to 64 rows has a
  * layout of its own for them (what all workgroups read at the same step adjacent in memory): the
  * model then takes up to twice its layer weights (30 GB for an 8B model).  A copy that does not fit
  * is left out; the environment variable DLM_W_STEPS=0, read by this call, leaves them all out

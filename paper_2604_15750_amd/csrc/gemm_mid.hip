@@ -26,7 +26,7 @@
 namespace {
 
 constexpr int TPB = 256, NWV = 4;
-constexpr int MID_STEPS_MAX_MT = 2;  // row tiles up to which a launch may read the step-major copy of W
+constexpr int MID_STEPS_MAX_MT = 4;  // row tiles up to which a launch may read the step-major copy of W
 #ifndef MID_WD_MAX
 #define MID_WD_MAX 4
 #endif
