@@ -165,7 +165,7 @@ def main():
                     help="where passes that compare and retain no row (at most 64 rows) take their vocabulary statistics: the LM head's "
                          "epilogue (the default) or the streamed reduction every other pass uses")
     ap.add_argument("--weight-copies", type=int, default=1, choices=[0, 1],
-                    help="0: no step-major second copies of the layer matrices (sets DLM_W_STEPS=0 for dlm_model_create)")
+                    help="0: no step-major second copies of the layer matrices (DLM_W_STEPS=0 for dlm_model_create)")
     ap.add_argument("--micro", default="", choices=["", "vocab_stats", "peaks"],
                     help="time one kernel alone instead of the decode (peaks: a plain HBM read and a matrix-core loop, what the GPU achieves)")
     ap.add_argument("--rows", type=int, default=3072, help="--micro: rows of the pass (3072 = 16 sequences x 192 rows, the widest batched pass)")
@@ -210,9 +210,7 @@ def main():
         nl = min(args.cpu_layers, cfg["n_layers"])
         W_host = {k: ([inputs.tensor_to_numpy(t) for t in v[:nl]] if isinstance(v, list) else inputs.tensor_to_numpy(v))
                   for k, v in W.items()}
-    if not args.weight_copies:
-        os.environ["DLM_W_STEPS"] = "0"
-    model = api.Model(cfg, W)
+    model = api.Model(cfg, W, weight_copies=bool(args.weight_copies))
     del W
     torch.cuda.empty_cache()
     t_setup = time.perf_counter() - t0

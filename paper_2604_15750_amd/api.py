@@ -117,9 +117,10 @@ def dtype_code(t):
 
 
 class Model:
-    """dlm_model_create / dlm_model_destroy.  cfg: dict of inputs.model_config; W: dict of device tensors."""
+    """dlm_model_create / dlm_model_destroy.  cfg: dict of inputs.model_config; W: dict of device tensors.
+    weight_copies=False sets DLM_W_STEPS=0 for the call: no step-major second copies of the layer matrices."""
 
-    def __init__(self, cfg, W):
+    def __init__(self, cfg, W, weight_copies=True):
         self.cfg = dict(cfg)
         dt = DLM_F32 if cfg["dtype"] == "f32" else DLM_BF16
         c = dlm_config(cfg["n_layers"], cfg["d_model"], cfg["n_q_heads"], cfg["n_kv_heads"], cfg["head_dim"], cfg["d_ffn"],
@@ -128,7 +129,17 @@ class Model:
         keep = [arr(W[k]) for k in ("wqkv", "wo", "w_gate_up", "w_down", "norm1", "norm2")]
         w = dlm_weights(W["embed"].data_ptr(), *keep, W["final_norm"].data_ptr(), W["lm_head"].data_ptr())
         h = C.c_void_p()
-        _check(lib().dlm_model_create(C.byref(c), C.byref(w), _stream(), C.byref(h)))
+        before = os.environ.get("DLM_W_STEPS")
+        if not weight_copies:
+            os.environ["DLM_W_STEPS"] = "0"
+        try:
+            _check(lib().dlm_model_create(C.byref(c), C.byref(w), _stream(), C.byref(h)))
+        finally:
+            if not weight_copies:
+                if before is None:
+                    del os.environ["DLM_W_STEPS"]
+                else:
+                    os.environ["DLM_W_STEPS"] = before
         torch.cuda.current_stream().synchronize()  # the caller may now drop W
         self.handle = h
         self.torch_dtype = torch.float32 if dt == DLM_F32 else torch.bfloat16

@@ -262,22 +262,17 @@ def test_full_depth_decode_invariants_and_decisions(device, thresholds):
 def test_step_major_weight_copies_change_no_bit(device, name):
     """The second, step-major copies of the layer matrices that narrow passes read (all four matrices at these widths) hold the
     same fragments in another order, and the kernels add the same products in the same order: a prefill pass (standard layout
-    either way) and in-block passes of 8, 16 and 32 rows give bit-identical logits and statistics with and without the copies."""
-    import os
+    either way) and in-block passes of 8 to 64 rows give bit-identical logits and statistics with and without the copies."""
     cfg, _, _, _, _ = _twin(name)
     W = inputs.make_weights(cfg, seed=0, device=device)
-    P, look = 48, 32
+    P, look = 48, 64
     tokens = torch.full((P + look,), cfg["mask_id"], dtype=torch.int32, device=device)
     tokens[:P] = torch.from_numpy(inputs.make_prompts(cfg, 1, P)[0].astype(np.int32)).to(device)
     results = []
-    for copies in ("1", "0"):
-        os.environ["DLM_W_STEPS"] = copies
-        try:
-            model = api.Model(cfg, W)
-        finally:
-            del os.environ["DLM_W_STEPS"]
+    for copies in (True, False):
+        model = api.Model(cfg, W, weight_copies=copies)
         got = []
-        for L in (8, 16, 32):
+        for L in (8, 16, 32, 48, 64):
             state = api.State(model, 1, P + look, P + look, look)
             out = api.StepOutputs(P + look, cfg["vocab"], model.torch_dtype, device)
             api.dlm_step(state, tokens, out, [0, P + look], [0], [P], [0], kl_first=[0], kl_count=[0], save_first=[P], save_count=[look])
