@@ -91,10 +91,11 @@ __global__ __launch_bounds__(NWV * 64) void gemm_skinny_kernel(const bf16x8* __r
   }
 }
 
-// batch depth: 8 KiB of W in flight per wavefront for up to 32 rows, half of that beyond (the X fragments take the registers)
+// batch depth: 8 KiB of W in flight per wavefront for up to 32 rows, half of that beyond (the X fragments take the registers);
+// the step-major copy reads best with batches of four (measured: deeper batches add queueing, not bandwidth)
 template <int MT, int EPI>
 void launch_skinny(const bf16_t* xt, const bf16_t* wt, int pr, int M, int N, int K, const GemmEpi& e, hipStream_t st) {
-  if (pr == 1 && e.w_steps) DLM_LAUNCH((gemm_skinny_kernel<MT, 1, 8, (MT <= 2 ? 8 : 4), EPI, true>), N / 16, 512, 0, st, (const bf16x8*)xt, (const bf16x8*)wt, M, N, K, e);
+  if (pr == 1 && e.w_steps) DLM_LAUNCH((gemm_skinny_kernel<MT, 1, 8, 4, EPI, true>), N / 16, 512, 0, st, (const bf16x8*)xt, (const bf16x8*)wt, M, N, K, e);
   else if (pr == 1) DLM_LAUNCH((gemm_skinny_kernel<MT, 1, 8, (MT <= 2 ? 8 : 4), EPI>), N / 16, 512, 0, st, (const bf16x8*)xt, (const bf16x8*)wt, M, N, K, e);
   else if (e.w_steps) DLM_LAUNCH((gemm_skinny_kernel<MT, 2, 4, (MT <= 2 ? 4 : 2), EPI, true>), N / 32, 256, 0, st, (const bf16x8*)xt, (const bf16x8*)wt, M, N, K, e);
   else DLM_LAUNCH((gemm_skinny_kernel<MT, 2, 4, (MT <= 2 ? 4 : 2), EPI>), N / 32, 256, 0, st, (const bf16x8*)xt, (const bf16x8*)wt, M, N, K, e);
