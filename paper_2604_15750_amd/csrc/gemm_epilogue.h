@@ -34,13 +34,44 @@ __device__ inline void block_rinv(const RowScale& rs, int m_lo, int rows, float*
   }
 }
 
+// What an epilogue reads from memory besides the product, fetched ahead (at the start of the kernel, while the first weights
+// are in flight) for the fragment a wavefront finishes first, so that the end of a short kernel does not wait for a round
+// trip: EPI_RESID the four residual values and gains of the lane, EPI_QKV the lane's rotary cosines and sines.
+struct EpiAhead {
+  f32x4 a, b;
+  bool have;
+};
+__device__ inline EpiAhead epi_none() { return EpiAhead{f32x4{0.f, 0.f, 0.f, 0.f}, f32x4{0.f, 0.f, 0.f, 0.f}, false}; }
+template <int EPI>
+__device__ inline EpiAhead epi_ahead(const GemmEpi& e, int M, int N, int m, int nc, int g) {
+  EpiAhead r = epi_none();
+  if (EPI == EPI_RESID) {
+    if (m < M && nc < N) {
+      r.a = *(const f32x4*)(e.h + (size_t)m * N + nc + 4 * g);
+      r.b = *(const f32x4*)(e.gain + nc + 4 * g);
+      r.have = true;
+    }
+  } else if (EPI == EPI_QKV) {
+    const int hd = e.hd, half = hd >> 1;
+    if (m < M && nc < N && g < 2 && nc / hd < e.n_q + e.n_kv) {
+      const int i = 8 * ((nc % hd) >> 4) + 4 * g;
+      r.a = *(const f32x4*)(e.rope_cos + (size_t)m * half + i);
+      r.b = *(const f32x4*)(e.rope_sin + (size_t)m * half + i);
+      r.have = true;
+    }
+  }
+  return r;
+}
+
 // Rotary pair group: a = packed columns nc+4gp .. +3 of a 16-column tile starting at packed column nc,
 // b = the same + 8; they are dims i .. i+3 and i+half .. i+half+3 of one head (weights packed with PERM_ROTARY).
-__device__ inline void finish_qkv(const GemmEpi& e, int m, int nc, int gp, f32x4 a, f32x4 b) {
+__device__ inline void finish_qkv(const GemmEpi& e, int m, int nc, int gp, f32x4 a, f32x4 b, const EpiAhead ahead = epi_none()) {
   const int hd = e.hd, half = hd >> 1;
   const int head = nc / hd, i = 8 * ((nc % hd) >> 4) + 4 * gp;
   if (head < e.n_q + e.n_kv) {
-    const f32x4 c = *(const f32x4*)(e.rope_cos + (size_t)m * half + i), sn = *(const f32x4*)(e.rope_sin + (size_t)m * half + i);
+    const bool pre = ahead.have;
+    const f32x4 c = pre ? ahead.a : *(const f32x4*)(e.rope_cos + (size_t)m * half + i);
+    const f32x4 sn = pre ? ahead.b : *(const f32x4*)(e.rope_sin + (size_t)m * half + i);
     const f32x4 ra = a * c - b * sn, rb = b * c + a * sn;
     a = ra;
     b = rb;
@@ -77,11 +108,12 @@ __device__ inline void finish_swiglu(const GemmEpi& e, int m, int nc, int gp, f3
 }
 
 // residual add and next norm's x for columns n .. n+3 of row m; returns the four columns' share of sum h^2
-__device__ inline float finish_resid(const GemmEpi& e, int m, int n, int N, f32x4 y) {
+__device__ inline float finish_resid(const GemmEpi& e, int m, int n, int N, f32x4 y, const EpiAhead ahead = epi_none()) {
   const size_t o = (size_t)m * N + n;
-  const f32x4 v = *(const f32x4*)(e.h + o) + y;
+  const bool pre = ahead.have;
+  const f32x4 v = (pre ? ahead.a : *(const f32x4*)(e.h + o)) + y;
   *(f32x4*)(e.h + o) = v;
-  const f32x4 g = *(const f32x4*)(e.gain + n);
+  const f32x4 g = pre ? ahead.b : *(const f32x4*)(e.gain + n);
   *(bf16x4*)(e.x + tile_index(m, n, N)) = to_bf16x4(v * g);
   return v[0] * v[0] + v[1] * v[1] + v[2] * v[2] + v[3] * v[3];
 }
@@ -96,19 +128,19 @@ __device__ inline void finish_sum(const GemmEpi& e, int m, int n, int N, f32x4 v
 // Called by all 64 lanes of a wavefront together (it exchanges values between lanes).  EPI_RESID returns the tile's share of
 // sum h^2 of row m (in every lane of the row), the others 0.
 template <int EPI>
-__device__ inline float finish_frag(const GemmEpi& e, int M, int N, int m, int nc, int g, f32x4 v, float rinv) {
+__device__ inline float finish_frag(const GemmEpi& e, int M, int N, int m, int nc, int g, f32x4 v, float rinv, const EpiAhead ahead = epi_none()) {
   if (EPI == EPI_QKV || EPI == EPI_SWIGLU) {
     f32x4 b;  // the partner group, columns + 8, sits 32 lanes up
 #pragma unroll
     for (int i = 0; i < 4; ++i) b[i] = __shfl_xor(v[i], 32, 64);
     if (g < 2 && m < M) {
-      if (EPI == EPI_QKV) finish_qkv(e, m, nc, g, v * rinv, b * rinv);
+      if (EPI == EPI_QKV) finish_qkv(e, m, nc, g, v * rinv, b * rinv, ahead);
       else finish_swiglu(e, m, nc, g, v * rinv, b * rinv);
     }
     return 0.f;
   }
   if (EPI == EPI_RESID) {
-    float ss = m < M ? finish_resid(e, m, nc + 4 * g, N, v) : 0.f;
+    float ss = m < M ? finish_resid(e, m, nc + 4 * g, N, v, ahead) : 0.f;
     ss += __shfl_xor(ss, 16, 64);
     ss += __shfl_xor(ss, 32, 64);
     return ss;

@@ -173,6 +173,13 @@ __global__ __launch_bounds__(TPB) void gemm_mid_kernel(const bf16x8* __restrict_
   // 1/rms of the input rows, needed only by the epilogue: fetched while the first k-tiles are in flight (published by the
   // barriers of the reduction)
   if (EPI != EPI_RESID) block_rinv<TPB>(e.rs, 0, min(M, MT * 16), s_rinv);
+  // ... and so is what the epilogue of the fragment this wavefront finishes first (fragment `wave`) reads from memory, in the
+  // variants of narrow passes, which are short enough for that round trip to show
+  EpiAhead ahead = epi_none();
+  if constexpr (MT <= 2 && (EPI == EPI_RESID || EPI == EPI_QKV)) {
+    if (splits == 1 && wave < F && nt0 + wave / MT < NT)
+      ahead = epi_ahead<EPI>(e, M, N, (wave % MT) * 16 + (lane & 15), (nt0 + wave / MT) * 16, lane >> 4);
+  }
   if (nsteps > 0) {
     int st = 0;
     for (; st + TRIP <= nsteps; st += TRIP) trip(trip, std::integral_constant<int, 0>{}, st);
@@ -189,7 +196,7 @@ __global__ __launch_bounds__(TPB) void gemm_mid_kernel(const bf16x8* __restrict_
     const int r = f / MT, j = f - r * MT;
     const int nt = nt0 + r, m = j * 16 + ml;
     float ss = 0.f;
-    if (nt < NT) ss = finish_frag<EPI>(e, M, N, m, nt * 16, g, v, EPI == EPI_RESID ? 1.f : s_rinv[m]);  // uniform in the wavefront
+    if (nt < NT) ss = finish_frag<EPI>(e, M, N, m, nt * 16, g, v, EPI == EPI_RESID ? 1.f : s_rinv[m], f == wave ? ahead : epi_none());  // uniform in the wavefront
     if (EPI == EPI_RESID && g == 0) s_ssq[r * MT * 16 + m] = ss;
   };
 #pragma unroll

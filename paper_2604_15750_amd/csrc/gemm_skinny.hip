@@ -63,8 +63,12 @@ __global__ __launch_bounds__(NWV * 64) void gemm_skinny_kernel(const bf16x8* __r
   };
 
   load(0, t_begin);
-  // 1/rms of the input rows, needed only by the epilogue: fetched while the first batch is in flight
+  // 1/rms of the input rows, needed only by the epilogue: fetched while the first batch is in flight; so is what the epilogue
+  // of the tile this wavefront finishes first reads from memory (tile rj = wave of the R * MT)
   if (EPI != EPI_RESID) block_rinv<NWV * 64>(e.rs, 0, min(M, MT * 16), s_rinv);
+  EpiAhead ahead = epi_none();
+  if ((EPI == EPI_RESID || EPI == EPI_QKV) && wave < R * MT)
+    ahead = epi_ahead<EPI>(e, M, N, (wave % MT) * 16 + (lane & 15), (blockIdx.x * R + wave / MT) * 16, lane >> 4);
   for (int tb = t_begin; tb < t_end; tb += 2 * D) {
     load(1, tb + D);
     compute(0);
@@ -86,7 +90,7 @@ __global__ __launch_bounds__(NWV * 64) void gemm_skinny_kernel(const bf16x8* __r
     f32x4 v = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
     for (int w = 0; w < NWV; ++w) v += red[w][rj][lane];
-    const float ss = finish_frag<EPI>(e, M, N, m, nt * 16, g, v, EPI == EPI_RESID ? 1.f : s_rinv[j * 16 + ml]);
+    const float ss = finish_frag<EPI>(e, M, N, m, nt * 16, g, v, EPI == EPI_RESID ? 1.f : s_rinv[j * 16 + ml], rj == wave ? ahead : epi_none());
     if (EPI == EPI_RESID && g == 0 && m < M) e.ssq_out[(size_t)m * (N >> 4) + nt] = ss;
   }
 }
