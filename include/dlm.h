@@ -96,7 +96,7 @@ int dlm_state_kv_len(const dlm_state* s, int slot);
  * Each row attends (bidirectionally) to the slot's cached prefix [0, kv_len) and to all rows of
  * its own span; span_start[b] must equal the slot's kv_len.  After the pass the first
  * commit_len[b] rows join the cache (Sec. 5.2: prefix KV cached per decoded block).
- * suffix_len[b] > 0 (dual cache, Sec. 5.3): the rows also attend to the suffix_len[b] positions right
+ * suffix_len[b] > 0 (dual cache, Sec. 5.2, Q2): the rows also attend to the suffix_len[b] positions right
  * after the span, with the keys and values an earlier pass over those positions left in the cache
  * (every pass writes the K and V of all its rows at their positions; only the committed ones count
  * as prefix).  They are not recomputed.
@@ -109,6 +109,8 @@ int dlm_state_kv_len(const dlm_state* s, int slot);
  *   all other rows.
  * The logits of the save_count[b] rows starting at relative row save_first[b] are retained as the
  * slot's new p^prev (replacing the old one after this pass has read it).
+ * `tokens` is device memory the host cannot inspect: an id outside [0, vocab) is read as the nearest
+ * valid id (clamped), never as an address outside the embedding table.
  *
  * Errors (nothing is launched): DLM_EINVAL (null pointer, n_seqs < 1, offsets not increasing, slot
  * out of range or repeated, span_start != kv_len, commit/kl/save ranges outside the span, a kl row
@@ -181,7 +183,8 @@ int block_boundary(const float* I, const float* H, const int32_t* win_start, con
  * Outputs: selected_out DEVICE uint8 [same indexing as logits rows; only block rows written];
  * n_selected_out DEVICE [n_seqs]; if apply_tokens != 0, tokens[i] = argmax[i] for the selected
  * rows (Eq. 2); margin_out DEVICE [n_seqs] (nullable) = the smallest distance of an examined
- * quantity from the threshold or neighbour that decides it.
+ * quantity from the threshold or neighbour that decides it.  An argmax entry outside [0, vocab) is
+ * clamped into it before it indexes the logits.
  * Errors: DLM_EINVAL (null, n_seqs < 1, bad dtype/mode, tau_high < tau_low in mode 0, vocab < 2),
  * DLM_ECAPACITY (block_len < 0 or > 256, n_seqs > 32). */
 typedef struct {

@@ -28,7 +28,7 @@ NFE counts forward passes (Sec. 5.1, metrics).
 
 prm["dual_cache"] = 1: in-block passes also attend to the look-ahead positions after the block with the
 keys and values the last prefill / boundary pass computed for them (the suffix half of a dual cache,
-Sec. 5.3: DepCap is compatible with such caches), instead of seeing nothing after the block.
+Sec. 5.2, Q2: DepCap is compatible with such caches), instead of seeing nothing after the block.
 
 prm["fixed_block"] = B > 0 replaces DepGA-Block by the fixed block size of the comparison methods of
 Sec. 5.1 (vanilla and confidence-threshold decoding with block size 16 / 32 / 64; CAP-Decoding alone

@@ -86,7 +86,7 @@ class KVCache:
     """Post-RoPE keys and values of committed positions, per layer: [kv_len, Hkv, hd].
 
     tail_k / tail_v keep what the last pass computed for the rows it did NOT commit (positions from
-    tail_start on): the "suffix" entries of a dual cache (Sec. 5.3, cache compatibility), visible to a
+    tail_start on): the "suffix" entries of a dual cache (Sec. 5.2, Q2: cache compatibility), visible to a
     later pass only when it asks for them."""
 
     def __init__(self, cfg):

@@ -222,7 +222,7 @@ void launch_prepare(const SeqMeta& meta, const StatsMeta& sm, RowTables t, int r
 int norm_chunks(int d);
 template <typename T>
 void launch_embed_norm(const T* embed, const int32_t* tokens, const RowTables& t, const float* gain, float* h, T* x, float* ssq, int rows,
-                       int d, hipStream_t st);
+                       int d, int vocab, hipStream_t st);
 // h += sum_s part[s]; x = h * gain; ssq
 template <typename T>
 void launch_reduce_residual_norm(const float* part, int splits, float* h, const float* gain, T* x, float* ssq, int rows, int d, hipStream_t st);

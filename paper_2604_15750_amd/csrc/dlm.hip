@@ -362,7 +362,7 @@ int run_step_f32(dlm_state* s, const dlm_step_desc* d, const SeqMeta& meta, cons
   {
     ProfScope ps(pf, st, PC_OTHER, 2);
     launch_prepare(meta, sm, t, rows, c.vocab, hd, c.rope_theta, st);
-    launch_embed_norm<T>((const T*)m->embed.p, d->tokens, t, (const float*)m->norm1[0].p, h, x, ssq, rows, dm, st);
+    launch_embed_norm<T>((const T*)m->embed.p, d->tokens, t, (const float*)m->norm1[0].p, h, x, ssq, rows, dm, c.vocab, st);
   }
   for (int l = 0; l < c.n_layers; ++l) {
     T* kc = (T*)s->kcache.p + s->layer_stride * l;
@@ -428,7 +428,7 @@ int run_step_bf16(dlm_state* s, const dlm_step_desc* d, const SeqMeta& meta, con
   {
     ProfScope ps(pf, st, PC_OTHER, 2);
     launch_prepare(meta, sm, t, rows, c.vocab, hd, c.rope_theta, st);
-    launch_embed_norm<T>((const T*)m->embed.p, d->tokens, t, (const float*)m->norm1[0].p, h, x, ssq, rows, dm, st);
+    launch_embed_norm<T>((const T*)m->embed.p, d->tokens, t, (const float*)m->norm1[0].p, h, x, ssq, rows, dm, c.vocab, st);
   }
   // chunks of the row sums of squares the next consumer reads: the embedding's, then those of the GEMM that produced them
   int nch = norm_chunks(dm);

@@ -56,10 +56,13 @@ __device__ inline float row_rinv(const float* __restrict__ ssq, int r, int nch, 
 template <typename T>
 __global__ __launch_bounds__(256) void embed_norm_kernel(const T* __restrict__ embed, const int32_t* __restrict__ tokens, RowTables t,
                                                          const float* __restrict__ gain, float* __restrict__ h, T* __restrict__ x,
-                                                         float* __restrict__ ssq, int d) {
+                                                         float* __restrict__ ssq, int d, int vocab) {
   __shared__ float buf[4];
   const int r = blockIdx.y, k = blockIdx.x * NORM_CHUNK + threadIdx.x * 4;
-  const T* e = embed + (size_t)tokens[t.row_tok[r]] * d;
+  // the token buffer is the caller's device memory, which the host cannot validate: an id outside the vocabulary is clamped
+  // into it instead of reading outside the embedding table
+  const int tok = min(max(tokens[t.row_tok[r]], 0), vocab - 1);
+  const T* e = embed + (size_t)tok * d;
   float ss = 0.f;
   if (k < d) {
     f32x4 v, g = *(const f32x4*)(gain + k);
@@ -174,8 +177,8 @@ int norm_chunks(int d) { return (d + NORM_CHUNK - 1) / NORM_CHUNK; }
 
 template <typename T>
 void launch_embed_norm(const T* embed, const int32_t* tokens, const RowTables& t, const float* gain, float* h, T* x, float* ssq, int rows,
-                       int d, hipStream_t st) {
-  embed_norm_kernel<T><<<dim3(norm_chunks(d), rows), 256, 0, st>>>(embed, tokens, t, gain, h, x, ssq, d);
+                       int d, int vocab, hipStream_t st) {
+  embed_norm_kernel<T><<<dim3(norm_chunks(d), rows), 256, 0, st>>>(embed, tokens, t, gain, h, x, ssq, d, vocab);
 }
 template <typename T>
 void launch_reduce_residual_norm(const float* part, int splits, float* h, const float* gain, T* x, float* ssq, int rows, int d, hipStream_t st) {
@@ -195,7 +198,7 @@ void launch_rope_kv(const float* part, int splits, const float* ssq, int d, floa
 }
 
 #define INST(T)                                                                                                                      \
-  template void launch_embed_norm<T>(const T*, const int32_t*, const RowTables&, const float*, float*, T*, float*, int, int, hipStream_t); \
+  template void launch_embed_norm<T>(const T*, const int32_t*, const RowTables&, const float*, float*, T*, float*, int, int, int, hipStream_t); \
   template void launch_reduce_residual_norm<T>(const float*, int, float*, const float*, T*, float*, int, int, hipStream_t);             \
   template void launch_silu_mul<T>(const float*, int, const float*, int, float, T*, int, int, hipStream_t);                             \
   template void launch_rope_kv<T>(const float*, int, const float*, int, float, const RowTables&, const SeqMeta&, T*, T*, T*, size_t,    \

@@ -145,16 +145,20 @@ __global__ __launch_bounds__(TPB) void gemm_macro_kernel(const bf16x8* __restric
       for (int i = 0; i < WM; ++i)
         if (exists(j, i))
           __builtin_amdgcn_raw_buffer_store_b128(__builtin_bit_cast(u32x4, acc[j][i]), part_rsrc(e.part + split * stride + (size_t)m_lo * N), offset(j, i), 0, SC1);
-    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");  // every wavefront's stores have completed ...
-    __syncthreads();                                        // ... before the workgroup takes its ticket
+    // Hand-off across workgroups (possibly across XCDs, whose L2s are separate): every wavefront waits until its own partial
+    // stores, written through to device scope, have been acknowledged; then the workgroup takes its ticket with release order
+    // at device scope, and the last arriver reads the partial tiles (device-scope loads) behind an acquire.
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+    __syncthreads();
     if (tid == 0) {
       int* ticket = e.counters + cb * mblocks + rb;
-      const int last = __hip_atomic_fetch_add(ticket, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) == splits - 1;
+      const int last = __hip_atomic_fetch_add(ticket, 1, __ATOMIC_RELEASE, __HIP_MEMORY_SCOPE_AGENT) == splits - 1;
       if (last) __hip_atomic_store(ticket, 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);  // ready for the next launch
       s_last = last;
     }
     __syncthreads();
     if (!s_last) return;
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "agent");
 #pragma unroll
     for (int j = 0; j < WN; ++j)
 #pragma unroll

@@ -220,16 +220,20 @@ __global__ __launch_bounds__(TPB) void gemm_mid_kernel(const bf16x8* __restrict_
     }
   }
   if (splits > 1) {
-    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");  // every wavefront's stores have completed ...
-    __syncthreads();                                        // ... before the workgroup takes its ticket
+    // Hand-off across workgroups (possibly across XCDs, whose L2s are separate): every wavefront waits until its own partial
+    // stores, written through to device scope, have been acknowledged; then the workgroup takes its ticket with release order
+    // at device scope, and the last arriver reads the partial tiles (device-scope loads) behind an acquire.
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+    __syncthreads();
     if (tid == 0) {
       int* ticket = e.counters + group;
-      const int last = __hip_atomic_fetch_add(ticket, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) == splits - 1;
+      const int last = __hip_atomic_fetch_add(ticket, 1, __ATOMIC_RELEASE, __HIP_MEMORY_SCOPE_AGENT) == splits - 1;
       if (last) __hip_atomic_store(ticket, 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);  // ready for the next launch
       s_last = last;
     }
     __syncthreads();
     if (!s_last) return;
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "agent");
     // the finished tile = the partial tiles added in split order; a wavefront fetches one split of all its fragments per trip
     f32x4 v[FW];
     unsigned off[FW];

@@ -12,11 +12,12 @@
 // same W) get adjacent workgroup ids congruent mod 8, i.e. they run at the same time on the same XCD
 // and the second reader finds W in that XCD's L2.
 // K is split across workgroups when columns x row blocks cannot fill the chip: partial tiles go to
-// an fp32 workspace, written through and read with device scope (sc1) rather than bracketed by
-// device-scope fences, which would write back and invalidate a whole L2 per workgroup (a tile row
-// of one workgroup is at least 512 contiguous bytes, so no cache line has two writers); the
-// workgroup that arrives last at the tile's ticket re-reads the partial tiles into the accumulator
-// layout, adding them in split order (deterministic), and runs the epilogue.
+// an fp32 workspace, written through and read with device scope (sc1; a tile row of one workgroup
+// is at least 512 contiguous bytes, so no cache line has two writers).  Every wavefront waits for the
+// acknowledgement of its own stores before the workgroup's barrier, the ticket is taken with release
+// order at device scope, and the workgroup that arrives last passes an acquire fence before it
+// re-reads the partial tiles into the accumulator layout, adds them in split order (deterministic)
+// and runs the epilogue.
 #include "gemm_epilogue.h"
 #include "stats_part.h"
 
@@ -189,16 +190,20 @@ __global__ __launch_bounds__(TPB) void gemm_tiled_kernel(const bf16x8* __restric
                                                  ((unsigned)(j * 16 + ml) * N + (nt0 + r) * 16 + 4 * g) * 4u, 0, SC1);
       }
     }
-    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");  // every wavefront's stores have completed ...
-    __syncthreads();                                        // ... before the workgroup takes its ticket
+    // Hand-off across workgroups (possibly across XCDs, whose L2s are separate): every wavefront waits until its own partial
+    // stores, written through to device scope, have been acknowledged; then the workgroup takes its ticket with release order
+    // at device scope, and the last arriver reads the partial tiles (device-scope loads) behind an acquire.
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+    __syncthreads();
     if (tid == 0) {
       int* ticket = e.counters + group * mblocks + rb;
-      const int last = __hip_atomic_fetch_add(ticket, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) == splits - 1;
+      const int last = __hip_atomic_fetch_add(ticket, 1, __ATOMIC_RELEASE, __HIP_MEMORY_SCOPE_AGENT) == splits - 1;
       if (last) __hip_atomic_store(ticket, 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);  // ready for the next launch
       s_last = last;
     }
     __syncthreads();
     if (!s_last) return;
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "agent");
     // the finished tile = the partial tiles added in split order; eight loads in flight per trip to memory
 #pragma unroll
     for (int r = 0; r < TR; ++r) {

@@ -49,7 +49,7 @@ __global__ __launch_bounds__(TPB) void select_kernel(const T* __restrict__ logit
 
   c[i] = act ? conf_g[row0 + i] : -1.f;
   lse[i] = act ? lse_g[row0 + i] : 0.f;
-  yh[i] = act ? argmax_g[row0 + i] : 0;
+  yh[i] = act ? min(max(argmax_g[row0 + i], 0), vocab - 1) : 0;  // a caller-supplied prediction outside the vocabulary is clamped into it
   elig[i] = act && tokens[tok0 + i] == mask_id;
   sel[i] = 0;
   alive[i] = 0;

@@ -28,7 +28,7 @@ class Decoder:
         fixed_block = B > 0: every block has min(B, remaining) positions instead of the DepGA-Block length (the fixed block
         sizes of the comparison methods of Sec. 5.1); the boundary pass then compares and retains nothing.
         dual_cache = 1: in-block passes also attend to the look-ahead positions after the block, with the keys and values the
-        last prefill / boundary pass left in the cache for them (the suffix half of a dual cache, Sec. 5.3)."""
+        last prefill / boundary pass left in the cache for them (the suffix half of a dual cache, Sec. 5.2, Q2)."""
         self.model, self.cfg, self.prm, self.device = model, model.cfg, dict(prm), device
         self.B, self.P, self.N = batch, prompt_len, gen_len
         self.T = prompt_len + gen_len

@@ -75,7 +75,7 @@ def main():
         emit("methods", "CAP-Decoding, block 32", dict(base, fixed_block=32, mode=0))
         emit("methods", "DepGA-Block + confidence threshold", dict(base, mode=1))
         emit("methods", "DepCap (DepGA-Block + CAP-Decoding)", dict(base, mode=0))
-        emit("methods", "DepCap, suffix visible in the block", dict(base, mode=0, dual_cache=1))  # the dual cache of Sec. 5.3
+        emit("methods", "DepCap, suffix visible in the block", dict(base, mode=0, dual_cache=1))  # the dual cache of Sec. 5.2
     if "l_gen" in what:  # App. B.1
         for n in (128, 256, 512, 1024):
             if P + n <= 4096:

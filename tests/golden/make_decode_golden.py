@@ -27,7 +27,7 @@ CASES = {
     "paper": dict(inputs.PAPER_PARAMS, l_max=32),
     # thresholds inside a random-init model's confidence range: every branch of Alg. 1 is taken
     "scaled": dict(inputs.PAPER_PARAMS, l_max=32, lam=0.9, tau_low=0.05, tau_high=0.3, gamma=-14.0),
-    # in-block passes that also see the look-ahead suffix (Sec. 5.3)
+    # in-block passes that also see the look-ahead suffix (Sec. 5.2, Q2)
     "dual_cache": dict(inputs.PAPER_PARAMS, l_max=24, lam=0.9, tau_low=0.05, tau_high=0.3, gamma=-14.0, dual_cache=1),
     # the comparison rules of Sec. 5.1 at a fixed block size
     "threshold_block16": dict(inputs.PAPER_PARAMS, l_max=32, fixed_block=16, mode=1, tau_low=0.05, tau_high=0.2, gamma=-14.0),
