@@ -209,6 +209,17 @@ int dlm_vocab_stats(const void* logits, const void* prev, int rows, int vocab, i
                     float* max_logit, float* lse, float* entropy, float* kl, float* conf,
                     int32_t* argmax, void* workspace, size_t workspace_bytes, void* stream);
 
+/* dlm_vocab_stats for callers that cannot allocate or pass a workspace (code under HIP graph capture, tight serving
+ * loops, harnesses that forbid hipMalloc): same arguments, outputs and definitions, but the partial states live in a
+ * file-scope device array of the library (4 MiB per GPU the library runs on, held until the process ends), whose address
+ * is resolved once per device (at the first dlm_model_create on that device, else at the first call).  No hipMalloc,
+ * hipFree or other allocating call is made.  Limit: rows <= 4096 (DLM_ECAPACITY beyond; use dlm_vocab_stats there).
+ * All calls on one GPU share the array: calls that overlap on one GPU (different streams, different threads) race;
+ * calls on one stream are ordered and safe.  Errors: DLM_EINVAL, DLM_ECAPACITY, DLM_EHIP (address resolution failed). */
+int dlm_vocab_stats_static(const void* logits, const void* prev, int rows, int vocab, int dtype, int mask_id,
+                           float* max_logit, float* lse, float* entropy, float* kl, float* conf, int32_t* argmax,
+                           void* stream);
+
 /* y[M, N] = x[M, K] * w[N, K]^T with fp32 accumulation; all row-major DEVICE, dtype for x, w and y.
  * A test helper around the GEMM kernels of dlm_step: for DLM_BF16 it allocates scratch, re-tiles x
  * and w (dlm_step keeps both tiled) and synchronises the stream before returning; K, N multiples

@@ -56,7 +56,7 @@ class dlm_select_params(C.Structure):
 EXPORTS = ["dlm_last_error", "dlm_model_create", "dlm_model_destroy", "dlm_state_create", "dlm_state_destroy", "dlm_state_reset",
            "dlm_state_kv_len", "dlm_step", "block_boundary", "select_parallel", "dlm_vocab_stats_workspace", "dlm_vocab_stats",
            "dlm_gemm_nt", "dlm_attention", "dlm_profile_enable", "dlm_profile_read", "dlm_probe_hbm_read", "dlm_probe_mfma_bf16",
-           "dlm_state_fuse_stats"]
+           "dlm_state_fuse_stats", "dlm_vocab_stats_static"]
 
 
 def lib():
@@ -85,6 +85,7 @@ def lib():
                                       C.c_void_p]
         L.dlm_vocab_stats.argtypes = [C.c_void_p, C.c_void_p, C.c_int, C.c_int, C.c_int, C.c_int] + [C.c_void_p] * 7 + \
                                      [C.c_size_t, C.c_void_p]
+        L.dlm_vocab_stats_static.argtypes = [C.c_void_p, C.c_void_p, C.c_int, C.c_int, C.c_int, C.c_int] + [C.c_void_p] * 7
         L.dlm_gemm_nt.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_int, C.c_int, C.c_int, C.c_int, C.c_void_p]
         L.dlm_attention.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p] + [C.c_int] * 6 + [C.c_void_p]
         L.dlm_state_fuse_stats.argtypes = [C.c_void_p, C.c_int]
@@ -244,6 +245,20 @@ def dlm_vocab_stats(logits, mask_id, prev=None, workspace=None):
     _check(lib().dlm_vocab_stats(_ptr(logits), _ptr(prev), rows, vocab, dtype_code(logits), mask_id, _ptr(out["max_logit"]),
                                  _ptr(out["lse"]), _ptr(out["entropy"]), _ptr(out["kl"]), _ptr(out["conf"]), _ptr(out["argmax"]),
                                  _ptr(workspace), workspace.numel(), _stream()))
+    return out
+
+
+def dlm_vocab_stats_static(logits, mask_id, prev=None, out=None):
+    """dlm_vocab_stats_static: the partial states live in the library's file-scope scratch.  `out`: a dict of preallocated
+    output tensors as dlm_vocab_stats returns (so that the call allocates nothing at all); None: new ones."""
+    rows, vocab = logits.shape
+    dev = logits.device
+    if out is None:
+        f = lambda: torch.empty(rows, dtype=torch.float32, device=dev)
+        out = dict(max_logit=f(), lse=f(), entropy=f(), kl=f(), conf=f(), argmax=torch.empty(rows, dtype=torch.int32, device=dev))
+    _check(lib().dlm_vocab_stats_static(_ptr(logits), _ptr(prev), rows, vocab, dtype_code(logits), mask_id, _ptr(out["max_logit"]),
+                                        _ptr(out["lse"]), _ptr(out["entropy"]), _ptr(out["kl"]), _ptr(out["conf"]), _ptr(out["argmax"]),
+                                        _stream()))
     return out
 
 

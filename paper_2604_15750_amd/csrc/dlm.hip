@@ -3,6 +3,7 @@
 #include <cstdarg>
 #include <cstdio>
 #include <cstring>
+#include <mutex>
 #include <new>
 #include <vector>
 
@@ -26,7 +27,35 @@ extern "C" const char* dlm_last_error(void) { return g_err; }
     if (!(cond)) return dlm_fail(code, __VA_ARGS__); \
   } while (0)
 
+// ---- file-scope scratch of the entry point that allocates nothing (dlm_vocab_stats_static) -------------
+// The partial online-softmax states of the vocabulary reduction, one per (row, chunk): what dlm_vocab_stats takes as its
+// workspace argument.  Every GPU the library runs on holds its own copy of the array, at its own address, until the process
+// ends.  In host code the array's name is only a handle for hipGetSymbolAddress: kernels and copies get the resolved pointer.
+constexpr int STATIC_STATS_MAX_ROWS = 4096;
+constexpr size_t STATIC_STATS_BYTES = (size_t)STATIC_STATS_MAX_ROWS * 1024;  // 32 chunks x 32 bytes per row: 4 MiB
+static __device__ __align__(256) unsigned char scratch[STATIC_STATS_BYTES];
+
 namespace {
+
+constexpr int MAX_DEVICES = 64;
+std::mutex g_scratch_mu;
+void* g_scratch_ptr[MAX_DEVICES] = {};
+
+// Device address of `scratch` on the current device, resolved once per device with that device current.
+int scratch_address(void** out) {
+  int dev = -1;
+  DLM_HIP(hipGetDevice(&dev));
+  if (dev < 0 || dev >= MAX_DEVICES) return dlm_fail(DLM_ECAPACITY, "device ordinal %d beyond the %d this library keeps scratch addresses for", dev, MAX_DEVICES);
+  std::lock_guard<std::mutex> lock(g_scratch_mu);
+  if (!g_scratch_ptr[dev]) {
+    void* p = nullptr;
+    DLM_HIP(hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)));
+    if (!p) return dlm_fail(DLM_EHIP, "hipGetSymbolAddress returned a null address for the scratch array");
+    g_scratch_ptr[dev] = p;
+  }
+  *out = g_scratch_ptr[dev];
+  return DLM_OK;
+}
 
 size_t elem_size(int dtype) { return dtype == DLM_BF16 ? 2 : 4; }
 
@@ -162,6 +191,7 @@ extern "C" int dlm_model_create(const dlm_config* cfg, const dlm_weights* w, voi
             "dlm_model_create: null weight pointer in layer %d", l);
 
   hipStream_t st = (hipStream_t)stream;
+  { void* sp = nullptr; (void)scratch_address(&sp); }  // set-up on this device: callers of dlm_vocab_stats_static find the address resolved
   dlm_model* m = new (std::nothrow) dlm_model();
   REQUIRE(m, DLM_ENOMEM, "dlm_model_create: host allocation failed");
   m->cfg = *cfg;
@@ -641,6 +671,26 @@ extern "C" int dlm_vocab_stats(const void* logits, const void* prev, int rows, i
   hipStream_t st = (hipStream_t)stream;
   if (dtype == DLM_BF16) launch_vocab_stats<bf16_t>((const bf16_t*)logits, rows, vocab, mask_id, sr, so, workspace, st);
   else launch_vocab_stats<float>((const float*)logits, rows, vocab, mask_id, sr, so, workspace, st);
+  return DLM_OK;
+}
+
+extern "C" int dlm_vocab_stats_static(const void* logits, const void* prev, int rows, int vocab, int dtype, int mask_id, float* max_logit,
+                                      float* lse, float* entropy, float* kl, float* conf, int32_t* argmax, void* stream) {
+  REQUIRE(logits && max_logit && lse && entropy && kl && conf && argmax, DLM_EINVAL, "dlm_vocab_stats_static: null argument");
+  REQUIRE(dtype == DLM_F32 || dtype == DLM_BF16, DLM_EINVAL, "dlm_vocab_stats_static: dtype %d", dtype);
+  REQUIRE(rows >= 1, DLM_ECAPACITY, "dlm_vocab_stats_static: rows %d < 1", rows);
+  REQUIRE(rows <= STATIC_STATS_MAX_ROWS && stats_workspace_bytes(rows) <= STATIC_STATS_BYTES, DLM_ECAPACITY,
+          "dlm_vocab_stats_static: %d rows > the %d rows the static scratch holds (use dlm_vocab_stats with a workspace)", rows, STATIC_STATS_MAX_ROWS);
+  REQUIRE(vocab >= 2 && mask_id >= 0 && mask_id < vocab, DLM_EINVAL, "dlm_vocab_stats_static: vocab/mask_id");
+  void* ws = nullptr;
+  const int rc = scratch_address(&ws);
+  if (rc != DLM_OK) return rc;
+  // every partial state the merge reads is written by this call's first kernel: nothing has to start at zero
+  StatsRows sr{nullptr, nullptr, prev, nullptr, nullptr, nullptr};
+  StatsOut so{max_logit, lse, entropy, kl, conf, argmax};
+  hipStream_t st = (hipStream_t)stream;
+  if (dtype == DLM_BF16) launch_vocab_stats<bf16_t>((const bf16_t*)logits, rows, vocab, mask_id, sr, so, ws, st);
+  else launch_vocab_stats<float>((const float*)logits, rows, vocab, mask_id, sr, so, ws, st);
   return DLM_OK;
 }
 
