@@ -18,7 +18,12 @@ Parity status of each function against something other than itself
                                          leaves undefined are this build's reading:
                                          "parity unpinned" against the authors' behaviour
   select.select_parallel                 pinned (independent set-recursive Alg. 1, invariants)
-  decode.decode_full                     pinned by structural invariants only (Eq. 1, Eq. 2, Sec. 3);
-                                         the pass schedule is this build's reading of Sec. 4.2 /
-                                         App. A.3: "parity unpinned" against the authors' behaviour
+  decode.decode_full                     pinned: structural invariants (Eq. 1, Eq. 2, Sec. 3), and every boundary
+                                         decision's KL / entropy rows rebuilt from the trace's pass records by
+                                         absolute position with scipy's KL and entropy, with the pairing of Sec. 4.2
+                                         checked (p^prev from the pass taken while the block just decoded was all
+                                         masks, p^curr from the pass right after it was finished); planted mistakes
+                                         in the schedule arithmetic fail that check.  The schedule itself is this
+                                         build's reading of Sec. 4.2 / App. A.3: "parity unpinned" against the
+                                         authors' behaviour
 """

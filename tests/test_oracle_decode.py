@@ -96,3 +96,108 @@ def test_stored_decodes_are_what_the_oracle_writes():
         assert r["blocks"][0] == first and max(r["blocks"]) <= prm["l_max"]
         # one pass per selection step, the prefill's and each boundary pass's selection included (Sec. 4.2)
         assert r["nfe"] == len(r["steps"])
+
+
+# ---- which passes give p^prev and p^curr (Sec. 4.2; App. A.3) ---------------------------------------
+def _kl_entropy(z_curr, z_prev, mask):
+    """KL(p^curr || p^prev) (Eq. 3) and H(p^curr) of one position, from scipy's routines (not the oracle's formulae)."""
+    from scipy.special import rel_entr, softmax
+    from scipy.stats import entropy
+    keep = np.arange(z_curr.shape[0]) != mask
+    p, q = softmax(z_curr[keep]), softmax(z_prev[keep])
+    return float(rel_entr(p, q).sum()), float(entropy(p))
+
+
+def _check_alignment(trace, cfg, P, N, prm):
+    """Rebuilds every boundary record of a decode trace from its pass records alone, with bookkeeping by ABSOLUTE position
+    written here: `retained[pos]` = (logits row, index of the pass that produced it) for every uncommitted row of the last
+    prefill / boundary pass.  Raises AssertionError when the trace's KL / entropy rows, window or pass pairing differ."""
+    mask, lmax = cfg["mask_id"], prm["l_max"]
+    retained = {}
+    passes = []
+    frontier = P  # first position not in a finished block
+    checked = 0
+    pending = None  # the boundary pass whose decision record comes next
+    for t in trace:
+        if t["op"] == "pass":
+            passes.append(t)
+            if t["kind"] == "inblock":
+                continue
+            start, commit, rows = t["span_start"], t["commit_len"], len(t["tokens"])
+            new = {start + r: (t["logits"][r], len(passes) - 1) for r in range(commit, rows)}
+            if t["kind"] == "boundary":
+                pending = (t, dict(retained), start + commit)
+            retained = new  # the look-ahead rows of this pass replace what was retained before
+            frontier = start + commit
+        elif t["op"] == "boundary":
+            assert pending is not None, "a boundary decision without its boundary pass"
+            bp, old, f_new = pending
+            pending = None
+            remaining = P + N - f_new
+            assert t["F"] == f_new and t["W"] == min(lmax, remaining)
+            assert len(t["kl"]) == t["W"] == len(t["entropy"])
+            block = range(bp["span_start"], bp["span_start"] + bp["commit_len"])  # the block this pass has just committed
+            for k in range(t["W"]):
+                pos = f_new + k
+                z_curr = bp["logits"][pos - bp["span_start"]]
+                assert pos in old, f"candidate {pos} has no retained distribution"
+                z_prev, src = old[pos]
+                kl, H = _kl_entropy(z_curr, z_prev, mask)
+                assert abs(kl - t["kl"][k]) <= 1e-9 * max(1.0, abs(kl)), (pos, kl, t["kl"][k])
+                assert abs(H - t["entropy"][k]) <= 1e-9 * max(1.0, H), (pos, H, t["entropy"][k])
+                # p^prev: from the pass taken while the block just decoded was still all masks; p^curr: from the pass right
+                # after it was fully decoded, the rest of the state unchanged (positions after the block still masked)
+                sp = passes[src]
+                seen_then = [sp["tokens"][b - sp["span_start"]] for b in block]
+                assert all(v == mask for v in seen_then), "p^prev was taken after part of the block had been decoded"
+                assert not any(bp["tokens"][b - bp["span_start"]] == mask for b in block), "p^curr was taken before the block was finished"
+                assert sp["tokens"][pos - sp["span_start"]] == mask and bp["tokens"][pos - bp["span_start"]] == mask
+                checked += 1
+    return checked
+
+
+@pytest.mark.parametrize("name", ["scaled", "cumulative", "dual_cache"])
+def test_boundary_signal_pairs_the_right_passes_and_positions(tiny, name):
+    cfg, W, prompt = tiny
+    prm = PARAM_SETS[name]
+    trace = []
+    r = decode_full(cfg, W, prompt, 64, prm, trace)
+    n = _check_alignment(trace, cfg, 64, 64, prm)
+    assert n >= 3 * (len(r["blocks"]) - 1) and len(r["blocks"]) >= 3  # every boundary decision after the cold start, several candidates each
+
+
+def _mutant(replacements):
+    """oracle/decode.py with a planted mistake (CPU only): returns the mutated module's decode_full."""
+    import importlib.util
+    import os
+    import types
+    import oracle.decode as real
+    src = open(real.__file__).read()
+    for old, new in replacements:
+        assert src.count(old) == 1, old
+        src = src.replace(old, new)
+    mod = types.ModuleType("oracle._decode_mutant")
+    mod.__package__ = "oracle"
+    mod.__file__ = os.path.join(os.path.dirname(real.__file__), "_decode_mutant.py")
+    exec(compile(src, mod.__file__, "exec"), mod.__dict__)
+    return mod.decode_full
+
+
+@pytest.mark.parametrize("planted", [
+    [("off = F + L - prev_base", "off = min(F + L - prev_base + 1, len(prev_z) - Wn)")],  # p^prev of the neighbouring position
+    [("off = F + L - prev_base", "off = F + L - prev_base - 1")],
+    [("Wn = min(l_max, R)", "Wn = min(l_max - 1, R)")],                                  # a shorter candidate window
+    [("st = vocab_stats(look[:Wn], mask, z_prev=prev_z[off : off + Wn])", "st = vocab_stats(look[min(1, len(look) - Wn) :][:Wn], mask, z_prev=prev_z[off : off + Wn])")],  # p^curr shifted
+    [("            prev_base, prev_z = F + L, look\n", "            prev_base, prev_z = (F + L, look) if len(blocks) % 2 == 0 else (prev_base, prev_z)\n"),
+     ("off = F + L - prev_base", "off = min(F + L - prev_base, len(prev_z) - Wn)")],     # p^prev not refreshed after every other block
+])
+def test_alignment_check_catches_planted_mistakes(tiny, planted):
+    """The check above is only a pin if a plausible mistake in the schedule arithmetic fails it: plant one in a copy of the
+    oracle's source and see it fail, while the decode's structural invariants (partition, NFE, Eq. 2) still hold."""
+    cfg, W, prompt = tiny
+    prm = PARAM_SETS["scaled"]
+    trace = []
+    r = _mutant(planted)(cfg, W, prompt, 64, prm, trace)
+    assert sum(r["blocks"]) == 64 and not (r["tokens"] == cfg["mask_id"]).any()  # the invariants do not notice
+    with pytest.raises(AssertionError):
+        _check_alignment(trace, cfg, 64, 64, prm)
