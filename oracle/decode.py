@@ -43,7 +43,7 @@ from .select import select_parallel
 from .stats import vocab_stats
 
 
-def decode_full(cfg, W, prompt, n_gen, prm, trace=None, max_passes=None):
+def decode_full(cfg, W, prompt, n_gen, prm, trace=None, max_passes=None, stop_after=None):
     """prm: dict(l_min, l_max, lam, smooth_radius, norm_mode, rule, tau_low, tau_high, gamma, mode).
 
     Returns dict(tokens [P+N], nfe, blocks [list of L], steps [tokens written per
@@ -51,6 +51,8 @@ def decode_full(cfg, W, prompt, n_gen, prm, trace=None, max_passes=None):
     decision is appended (inputs and outputs, for replay against another
     implementation).  max_passes stops the decode early after that many forward
     passes (for sampling the first passes of a large model); the result is then partial.
+    stop_after = "boundary" (or another pass kind) stops it, likewise, once a pass of that kind and
+    the decisions that follow it have been taken.
     """
     mask = cfg["mask_id"]
     P, N = len(prompt), n_gen
@@ -62,14 +64,16 @@ def decode_full(cfg, W, prompt, n_gen, prm, trace=None, max_passes=None):
     fixed = int(prm.get("fixed_block", 0))
     dual = bool(prm.get("dual_cache", 0))
     look_end = 0  # end of the positions the last prefill / boundary pass covered
+    seen_stop_kind = False
 
     class _Stop(Exception):
         pass
 
     def run_pass(kind, start, rows, commit):
-        nonlocal nfe, look_end
-        if max_passes is not None and nfe >= max_passes:
+        nonlocal nfe, look_end, seen_stop_kind
+        if (max_passes is not None and nfe >= max_passes) or seen_stop_kind:
             raise _Stop
+        seen_stop_kind = stop_after is not None and kind == stop_after
         toks = y[start : start + rows].copy()
         suffix = look_end - (start + rows) if (dual and kind == "inblock") else 0
         z = forward_span(cfg, W, cache, toks, start, commit, suffix)

@@ -2,7 +2,7 @@
 // [0, n_keys) of the sequence's KV-cache slot (cached prefix + the span's own rows, which the
 // rotary/KV kernel has already written there).  Grouped-query heads share K/V.
 //
-// fp32 kernel (head_dim 32/64/128, row-major cache [pos][n_kv*hd]): one workgroup per (16-query
+// fp32 model (head_dim 32/64/128, row-major cache [pos][n_kv*hd]): one workgroup per (16-query
 // tile, head, sequence); keys are streamed in tiles through LDS with an online softmax in fp32.
 #include "attention_core.h"
 
@@ -96,12 +96,12 @@ __global__ __launch_bounds__(256) void attention_kernel(const T* __restrict__ q,
   }
 }
 
-// ---- bf16 kernel on the matrix cores (attention_core.h) ----------------------------------------------
+// ---- bf16 models: on the matrix cores, half-precision operands (attention_core.h) -----------------------------
 // One workgroup per (16-query tile, head, sequence), or DS of them with a share of the head's output dims each.
 template <int HD, int NWV, int DS>
-__global__ __launch_bounds__(NWV * 64) void attention_mfma_kernel(const bf16_t* __restrict__ q, const bf16_t* __restrict__ kcache,
-                                                                  const bf16_t* __restrict__ vcache, size_t slot_stride, size_t head_stride,
-                                                                  AttnMeta meta, bf16_t* __restrict__ out, bool out_tiled, int n_q, int n_kv) {
+__global__ __launch_bounds__(NWV * 64) void attention_mfma_kernel(const f16_t* __restrict__ q, const f16_t* __restrict__ kcache,
+                                                                  const f16_t* __restrict__ vcache, size_t slot_stride, size_t head_stride,
+                                                                  AttnMeta meta, bf16_t* __restrict__ out, bool out_pair, int n_q, int n_kv) {
   __shared__ AttnLds<HD, NWV, DS> L;
   const int b = blockIdx.z, head = blockIdx.y, tile = blockIdx.x / DS, dpart = blockIdx.x - tile * DS;
   const int row0 = meta.row_off[b] + tile * 16;
@@ -109,25 +109,29 @@ __global__ __launch_bounds__(NWV * 64) void attention_mfma_kernel(const bf16_t* 
   if (row0 >= row_end) return;
   const int kvh = head / (n_q / n_kv);
   const size_t region = (size_t)meta.slot[b] * slot_stride + (size_t)kvh * head_stride;
-  attention_tile<HD, NWV, DS>(q, kcache + region, vcache + region, row0, row_end, meta.n_keys[b], head, n_q, out, out_tiled, L, dpart);
+  attention_tile<HD, NWV, DS>(q, kcache + region, vcache + region, row0, row_end, meta.n_keys[b], head, n_q, out, out_pair, L, dpart);
 }
 
-// K [T, n_kv, hd] and V row-major -> the tiled cache layout of one slot (test helper for dlm_attention)
-__global__ void pack_kv_kernel(const bf16_t* __restrict__ k, const bf16_t* __restrict__ v, bf16_t* __restrict__ kt, bf16_t* __restrict__ vt,
+// K [T, n_kv, hd] and V row-major bf16 -> the tiled half-precision cache layout of one slot (test helper for dlm_attention)
+__global__ void pack_kv_kernel(const bf16_t* __restrict__ k, const bf16_t* __restrict__ v, f16_t* __restrict__ kt, f16_t* __restrict__ vt,
                                int T, int n_kv, int hd, size_t head_stride) {
   const size_t total = (size_t)T * n_kv * hd;
   for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < total; i += (size_t)gridDim.x * blockDim.x) {
     const int d = i % hd, h = (i / hd) % n_kv, pos = i / ((size_t)hd * n_kv);
-    kt[(size_t)h * head_stride + kv_k_index(pos, d, hd)] = k[i];
-    vt[(size_t)h * head_stride + kv_v_index(pos, d, hd)] = v[i];
+    kt[(size_t)h * head_stride + kv_k_index(pos, d, hd)] = to_f16_sat((float)k[i]);
+    vt[(size_t)h * head_stride + kv_v_index(pos, d, hd)] = to_f16_sat((float)v[i]);
   }
+}
+__global__ void to_f16_kernel(const bf16_t* __restrict__ src, f16_t* __restrict__ dst, size_t n) {
+  for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < n; i += (size_t)gridDim.x * blockDim.x) dst[i] = to_f16_sat((float)src[i]);
 }
 
 }  // namespace
 
-void launch_pack_kv(const bf16_t* k, const bf16_t* v, bf16_t* kt, bf16_t* vt, int T, int n_kv, int hd, size_t head_stride, hipStream_t st) {
+void launch_pack_kv(const bf16_t* k, const bf16_t* v, f16_t* kt, f16_t* vt, int T, int n_kv, int hd, size_t head_stride, hipStream_t st) {
   pack_kv_kernel<<<256, 256, 0, st>>>(k, v, kt, vt, T, n_kv, hd, head_stride);
 }
+void launch_to_f16(const bf16_t* src, f16_t* dst, size_t n, hipStream_t st) { to_f16_kernel<<<256, 256, 0, st>>>(src, dst, n); }
 
 template <>
 void launch_attention<float>(const float* q, const float* kcache, const float* vcache, size_t slot_stride, size_t head_stride, const AttnMeta& meta,
@@ -138,16 +142,14 @@ void launch_attention<float>(const float* q, const float* kcache, const float* v
   else attention_kernel<float, 128><<<grid, 256, 0, st>>>(q, kcache, vcache, slot_stride, meta, out, out_tiled, n_q, n_kv);
 }
 
-template <>
-void launch_attention<bf16_t>(const bf16_t* q, const bf16_t* kcache, const bf16_t* vcache, size_t slot_stride, size_t head_stride,
-                              const AttnMeta& meta, bf16_t* out, bool out_tiled, int rows, int max_seq_rows, int n_q, int n_kv, int hd,
-                              hipStream_t st) {
+void launch_attention_f16(const f16_t* q, const f16_t* kcache, const f16_t* vcache, size_t slot_stride, size_t head_stride, const AttnMeta& meta,
+                          bf16_t* out, bool out_pair, int rows, int max_seq_rows, int n_q, int n_kv, int hd, hipStream_t st) {
   const int tiles = (max_seq_rows + 15) / 16;
   // a narrow pass (few query tiles x heads): eight wavefronts per workgroup to shorten each wavefront's chain of dependent
   // loads, and the output dims of a head split over four workgroups (two for 64 dims) to spread its K / V traffic
   const bool narrow = (size_t)tiles * n_q * meta.n_seqs < 128 && hd >= 64;
   const bool wide = (size_t)tiles * n_q * meta.n_seqs >= 512;  // enough workgroups to fill the chip with 4 wavefronts each
-#define GO(HD, NWV, DS) attention_mfma_kernel<HD, NWV, DS><<<dim3(tiles * DS, n_q, meta.n_seqs), NWV * 64, 0, st>>>(q, kcache, vcache, slot_stride, head_stride, meta, out, out_tiled, n_q, n_kv)
+#define GO(HD, NWV, DS) attention_mfma_kernel<HD, NWV, DS><<<dim3(tiles * DS, n_q, meta.n_seqs), NWV * 64, 0, st>>>(q, kcache, vcache, slot_stride, head_stride, meta, out, out_pair, n_q, n_kv)
   if (hd == 32) { if (wide) GO(32, 4, 1); else GO(32, 8, 1); }
   else if (hd == 64) { if (narrow) GO(64, 8, 2); else if (wide) GO(64, 4, 1); else GO(64, 8, 1); }
   else { if (narrow) GO(128, 8, 4); else if (wide) GO(128, 4, 1); else GO(128, 8, 1); }

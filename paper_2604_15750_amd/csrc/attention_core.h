@@ -1,10 +1,12 @@
-// Block-vs-prefix attention on the matrix cores for the bf16 KV cache: the work of one workgroup on one
+// Block-vs-prefix attention on the matrix cores for a bf16 model's KV cache: the work of one workgroup on one
 // (16-query tile, head, sequence), as a device function of its own so that it can be placed inside another kernel.
 // (Running it in the tail of the QKV GEMM of a narrow pass, in the workgroup that finishes a head last, was measured: the
 // fused launch took 37 us against 23 + 9 us for the two launches, because the tail is a serial chain of memory round trips.)
 //
-// The bf16 KV cache is kept per (slot, kv head) in matrix-core fragment tiles (kv_k_index /
-// kv_v_index), so a wavefront fetches a K operand (16 keys x 32 dims) or a V^T operand
+// The KV cache of a bf16 model holds IEEE half (f16_t in common.h: Q, K, V and the unnormalised probabilities are the
+// matrix-core operands here, and with bf16's 8 mantissa bits their rounding is the largest single part of a deep model's
+// logit error; half has the same size and matrix-core rate).  It is kept per (slot, kv head) in matrix-core fragment tiles
+// (kv_k_index / kv_v_index), so a wavefront fetches a K operand (16 keys x 32 dims) or a V^T operand
 // (16 dims x 32 keys) as 64 consecutive 16-byte pieces.  The NWV wavefronts of the workgroup take
 // every NWV-th block of 32 keys with their own online-softmax state and are merged through LDS.
 // The K and V fragments of a wavefront's next block are in flight while the current one is
@@ -21,39 +23,39 @@ struct AttnLds {  // merge buffers of one workgroup (HD / DS of the head's dims)
 };
 
 // q: row-major [rows, n_q * HD]; kt / vt: the (slot, kv head) region of the tiled cache; rows [row0, row_end) x head `head`
-// against keys [0, n_keys); out: activation layout [rows, n_q * HD] (out_tiled) or row-major.  Called by every thread of
-// a workgroup of NWV wavefronts.
+// against keys [0, n_keys); out: the pair-of-planes activation layout [rows, n_q * HD] (out_pair: hi = bf16(o),
+// lo = bf16(o - hi), the O projection's input) or row-major bf16.  Called by every thread of a workgroup of NWV wavefronts.
 // DS > 1: the workgroup produces only dims [dpart * HD / DS, (dpart + 1) * HD / DS) of the output: it reads all of K (the
 // scores and the softmax are computed by each of the DS workgroups of a head, identically) but only its share of V.  What
 // bounds a narrow pass is what one compute unit can pull through its L2 (about 50 GB/s), and K and V of a head are its whole
 // traffic: four workgroups per head move 5/8 of it each, with nothing to merge.
 template <int HD, int NWV, int DS = 1>
-__device__ inline void attention_tile(const bf16_t* __restrict__ q, const bf16_t* __restrict__ kregion, const bf16_t* __restrict__ vregion,
-                                      int row0, int row_end, int n_keys, int head, int n_q, bf16_t* __restrict__ out, bool out_tiled,
+__device__ inline void attention_tile(const f16_t* __restrict__ q, const f16_t* __restrict__ kregion, const f16_t* __restrict__ vregion,
+                                      int row0, int row_end, int n_keys, int head, int n_q, bf16_t* __restrict__ out, bool out_pair,
                                       AttnLds<HD, NWV, DS>& L, int dpart = 0) {
   constexpr int KS = HD / 32, DT = HD / 16 / DS, HDP = HD / DS;
   static_assert(HDP * 16 >= NWV * 64, "every thread finishes at least one dim");
   constexpr float NEG_BIG = -3.0e38f;
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, g = lane >> 4, c = lane & 15;
   const float scale = rsqrtf((float)HD);
-  const bf16x8 zero8 = {0, 0, 0, 0, 0, 0, 0, 0};
+  const f16x8 zero8 = {0, 0, 0, 0, 0, 0, 0, 0};
 
-  bf16x8 qf[KS];
+  f16x8 qf[KS];
   {
     const int r = row0 + c;
 #pragma unroll
     for (int t = 0; t < KS; ++t)
-      qf[t] = r < row_end ? *(const bf16x8*)(q + (size_t)r * n_q * HD + (size_t)head * HD + 32 * t + 8 * g) : zero8;
+      qf[t] = r < row_end ? *(const f16x8*)(q + (size_t)r * n_q * HD + (size_t)head * HD + 32 * t + 8 * g) : zero8;
   }
-  const bf16x8* kt = (const bf16x8*)kregion + lane;
-  const bf16x8* vt = (const bf16x8*)vregion + lane;
+  const f16x8* kt = (const f16x8*)kregion + lane;
+  const f16x8* vt = (const f16x8*)vregion + lane;
   float m = NEG_BIG, l = 0.f;
   f32x4 o[DT];
 #pragma unroll
   for (int dt = 0; dt < DT; ++dt) o[dt] = f32x4{0.f, 0.f, 0.f, 0.f};
 
   const int nblk = (n_keys + 31) >> 5;
-  bf16x8 kf[2][2 * KS], vf[2][DT];
+  f16x8 kf[2][2 * KS], vf[2][DT];
   auto load = [&](int buf, int blk) {  // blk may lie beyond the keys: nothing is fetched then
     const bool ok = blk < nblk;
 #pragma unroll
@@ -65,8 +67,8 @@ __device__ inline void attention_tile(const bf16_t* __restrict__ q, const bf16_t
     f32x4 s0 = {0.f, 0.f, 0.f, 0.f}, s1 = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
     for (int t = 0; t < KS; ++t) {
-      s0 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(kf[buf][t], qf[t], s0, 0, 0, 0);
-      s1 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(kf[buf][KS + t], qf[t], s1, 0, 0, 0);
+      s0 = __builtin_amdgcn_mfma_f32_16x16x32_f16(kf[buf][t], qf[t], s0, 0, 0, 0);
+      s1 = __builtin_amdgcn_mfma_f32_16x16x32_f16(kf[buf][KS + t], qf[t], s1, 0, 0, 0);
     }
     // lane holds, for query c, keys blk*32 + 4g + i (s0) and + 16 (s1)
     const int key0 = blk * 32 + 4 * g;
@@ -96,11 +98,11 @@ __device__ inline void attention_tile(const bf16_t* __restrict__ q, const bf16_t
     ps += __shfl_xor(ps, 32, 64);
     l = l * corr + ps;
     m = mn;
-    const bf16x8 pb = {(bf16_t)pv[0], (bf16_t)pv[1], (bf16_t)pv[2], (bf16_t)pv[3], (bf16_t)pv[4], (bf16_t)pv[5], (bf16_t)pv[6], (bf16_t)pv[7]};
+    const f16x8 pb = {(f16_t)pv[0], (f16_t)pv[1], (f16_t)pv[2], (f16_t)pv[3], (f16_t)pv[4], (f16_t)pv[5], (f16_t)pv[6], (f16_t)pv[7]};  // in [0, 1]
 #pragma unroll
     for (int dt = 0; dt < DT; ++dt) {
       o[dt] *= corr;
-      o[dt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(vf[buf][dt], pb, o[dt], 0, 0, 0);
+      o[dt] = __builtin_amdgcn_mfma_f32_16x16x32_f16(vf[buf][dt], pb, o[dt], 0, 0, 0);
     }
   };
   load(0, wave);
@@ -135,8 +137,15 @@ __device__ inline void attention_tile(const bf16_t* __restrict__ q, const bf16_t
 #pragma unroll
       for (int wv = 0; wv < NWV; ++wv) acc += w[wv] * L.so[wv][d][qi];
       const int col = head * HD + dpart * HDP + d;
-      const size_t idx = out_tiled ? tile_index(r, col, width) : (size_t)r * width + col;
-      out[idx] = (bf16_t)(acc / Lsum);
+      const float v = acc / Lsum;
+      const bf16_t hi = (bf16_t)v;
+      if (out_pair) {
+        const size_t idx = tile_index_pair(r, col, width, 0);
+        out[idx] = hi;
+        out[idx + 512] = (bf16_t)(v - (float)hi);
+      } else {
+        out[(size_t)r * width + col] = hi;
+      }
     }
   }
   __syncthreads();  // the merge buffers may be reused

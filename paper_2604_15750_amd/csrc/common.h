@@ -10,6 +10,11 @@ typedef __bf16 bf16_t;
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef __bf16 bf16x4 __attribute__((ext_vector_type(4)));
 typedef float f32x4 __attribute__((ext_vector_type(4)));
+// IEEE half: the storage type of a bf16 model's attention operands (Q, the KV cache, the unnormalised probabilities).  Same
+// bytes and matrix-core rate as bf16 with three more mantissa bits; values beyond +-65504 saturate (to_f16_sat).
+typedef _Float16 f16_t;
+typedef _Float16 f16x8 __attribute__((ext_vector_type(8)));
+typedef _Float16 f16x4 __attribute__((ext_vector_type(4)));
 
 #define DLM_WAVE 64
 
@@ -27,6 +32,14 @@ int dlm_fail(int code, const char* fmt, ...);
 // instruction per tile, so a wavefront fetches an operand as 64 consecutive 16-byte pieces.
 __host__ __device__ inline size_t tile_index(int m, int k, int K) {
   return ((size_t)(m >> 4) * (size_t)(K >> 5) + (size_t)(k >> 5)) * 512 + (size_t)(((m & 15) + 16 * ((k & 31) >> 3)) * 8 + (k & 7));
+}
+// The inputs of the two projections that feed the fp32 residual stream (O and down: the attention output and the gated FFN
+// activation) are kept as a PAIR of bf16 planes, hi = bf16(v) and lo = bf16(v - hi), together about 16 mantissa bits: rounding
+// them to one bf16 is, with the attention operands, what carries most of a deep model's logit error.  The two planes of a
+// fragment tile are adjacent (2 KiB per tile: hi then lo), and the GEMM multiplies each weight fragment with both.
+constexpr int PAIR_PLANES = 2;
+__host__ __device__ inline size_t tile_index_pair(int m, int k, int K, int plane) {
+  return ((size_t)(m >> 4) * (size_t)(K >> 5) + (size_t)(k >> 5)) * 1024 + (size_t)plane * 512 + (size_t)(((m & 15) + 16 * ((k & 31) >> 3)) * 8 + (k & 7));
 }
 
 // bf16 KV cache of one (slot, kv head): K in tiles of 16 positions x 32 dims (A operand of S^T = K Q^T), V in tiles of 16 dims x 32
@@ -50,6 +63,8 @@ template <> struct Act<bf16_t> {
 
 __device__ inline float to_f32(float x) { return x; }
 __device__ inline float to_f32(bf16_t x) { return (float)x; }
+__device__ inline float to_f32(f16_t x) { return (float)x; }
+__device__ inline f16_t to_f16_sat(float x) { return (f16_t)__builtin_amdgcn_fmed3f(x, -65504.f, 65504.f); }
 template <typename T> __device__ inline T from_f32(float x);
 template <> __device__ inline float from_f32<float>(float x) { return x; }
 template <> __device__ inline bf16_t from_f32<bf16_t>(float x) { return (bf16_t)x; }
@@ -132,10 +147,10 @@ void launch_pack_weight(const bf16_t* w, bf16_t* out, int N, int K, int perm, in
 // at (((s G + g) W + w) ct + r) KiB, G = N / (16 ct): what all workgroups read at the same step is one run of memory, and the
 // chip's reads at any moment are one moving window instead of thousands of separate streams.
 void launch_pack_weight_steps(const bf16_t* w, bf16_t* out, int N, int K, int ct, int perm, int perm_param, hipStream_t st);
-int gemm_bf16_steps_ct(int N, int K);  // ct of that layout for (N, K), 0 if the kernel that serves 16 rows has none
-int gemm_mid_steps_ct(int N, int K);   // ... if the mid kernel serves (N, K) at up to 16 rows without a K split, else 0
+int gemm_bf16_steps_ct(int N, int K, int kind);  // ct of that layout for (N, K) under epilogue `kind`, 0 if the kernel that serves 16 rows has none
+int gemm_mid_steps_ct(int N, int K, int kind);   // ... if the mid kernel serves (N, K) at up to 16 rows without a K split, else 0
 void launch_pack_act(const bf16_t* x, bf16_t* out, int M, int K, hipStream_t st);  // row-major -> fragment tiles (rows padded to 16 with zeros)
-int gemm_bf16_splits(int M, int N, int K);         // partial tiles [splits][M][N] the launch of this shape needs in GemmEpi::part (1: none)
+int gemm_bf16_splits(int M, int N, int K, int kind);  // partial tiles [splits][M][N] the launch of this shape and epilogue needs in GemmEpi::part (1: none)
 int gemm_bf16_ssq_chunks(int M, int N, int K);     // chunks per row of the sums of squares an EPI_RESID launch of this shape writes
 int gemm_bf16_counters(int max_rows, int max_n);   // ticket counters a state needs in GemmEpi::counters (zero-initialised, self-resetting)
 int gemm_tiled_counters(int max_rows, int max_n);
@@ -159,13 +174,13 @@ struct GemmEpi {
   // EPI_QKV (weights packed with PERM_ROTARY)
   const int32_t *row_pos, *row_slot;
   const float *rope_cos, *rope_sin;
-  bf16_t *q, *kcache, *vcache;
+  f16_t *q, *kcache, *vcache;  // IEEE half (see f16_t)
   size_t slot_stride, head_stride;
   int n_q, n_kv, hd;
-  // EPI_SWIGLU (weights packed with PERM_GATED)
+  // EPI_SWIGLU (weights packed with PERM_GATED): act is written as a pair of planes (tile_index_pair)
   bf16_t* act;
   int ffn;
-  // EPI_RESID: h += y; x = h * gain (fragment tiles); ssq_out[m][gemm_bf16_ssq_chunks(M, N, K)] = each column tile's share of sum h^2
+  // EPI_RESID (the GEMM's input xt is a pair of planes): h += y; x = h * gain (fragment tiles, one plane); ssq_out[m][gemm_bf16_ssq_chunks(M, N, K)] = each column tile's share of sum h^2
   float* h;
   const float* gain;
   bf16_t* x;
@@ -201,16 +216,16 @@ void launch_gemm_bf16(const bf16_t* xt, const bf16_t* wt, int M, int N, int K, c
 void launch_gemm_skinny(const bf16_t* xt, const bf16_t* wt, int pr, int M, int N, int K, const GemmEpi& e, hipStream_t st);  // M <= GEMM_SKINNY_MAX_ROWS
 void launch_gemm_tiled(const bf16_t* xt, const bf16_t* wt, int M, int N, int K, const GemmEpi& e, hipStream_t st);
 #define GEMM_MID_MAX_ROWS 160  // 65 .. this many rows: the mid kernel (all rows in one workgroup, wavefronts split K)
-#define GEMM_MID_MAX_ROWS_NARROW 256  // ... for matrices of at most 8192 columns
-int gemm_mid_splits(int M, int N, int K);
+#define GEMM_MID_MAX_ROWS_NARROW 256  // ... for matrices of at most 8192 columns (EPI_RESID, whose X is a pair of planes: GEMM_MID_MAX_ROWS)
+int gemm_mid_splits(int M, int N, int K, int kind);
 int gemm_mid_ssq_chunks(int M, int N, int K);
-bool gemm_mid_fills_chip(int M, int N, int K);  // its column groups are a whole number of rounds over the compute units, without a K split
+bool gemm_mid_fills_chip(int M, int N, int K, int kind);  // its column groups are a whole number of rounds over the compute units, without a K split
 int gemm_mid_counters(int max_n);
 void gemm_mid_set_target(int wgs);  // tuning: workgroups the K split aims at
 void launch_gemm_mid(const bf16_t* xt, const bf16_t* wt, int M, int N, int K, const GemmEpi& e, hipStream_t st);  // M <= GEMM_MID_MAX_ROWS(_NARROW); narrow matrices from 17 rows
 #define GEMM_MACRO_MIN_ROWS_NARROW 256  // more rows than this: the macro-tile kernel whatever the width
 int gemm_macro_ssq_chunks(int M, int N);
-int gemm_macro_splits(int M, int N, int K);
+int gemm_macro_splits(int M, int N, int K, int kind);
 int gemm_macro_counters(int max_rows, int max_n);
 void gemm_macro_set_target(int wgs);  // tuning: workgroups the K split aims at
 void launch_gemm_macro(const bf16_t* xt, const bf16_t* wt, int M, int N, int K, const GemmEpi& e, hipStream_t st);
@@ -239,7 +254,13 @@ void launch_rope_kv(const float* part, int splits, const float* ssq, int d, floa
 template <typename T>
 void launch_attention(const T* q, const T* kcache, const T* vcache, size_t slot_stride, size_t head_stride, const AttnMeta& meta, T* out,
                       bool out_tiled, int rows, int max_seq_rows, int n_q, int n_kv, int hd, hipStream_t st);
-void launch_pack_kv(const bf16_t* k, const bf16_t* v, bf16_t* kt, bf16_t* vt, int T, int n_kv, int hd, size_t head_stride, hipStream_t st);
+// bf16 models: q and the KV cache hold IEEE half; out_pair: the output goes to the pair-of-planes activation layout [rows, n_q*hd]
+// (the O projection's input), else row-major bf16
+void launch_attention_f16(const f16_t* q, const f16_t* kcache, const f16_t* vcache, size_t slot_stride, size_t head_stride, const AttnMeta& meta,
+                          bf16_t* out, bool out_pair, int rows, int max_seq_rows, int n_q, int n_kv, int hd, hipStream_t st);
+// test helper of dlm_attention: K, V [T, n_kv, hd] row-major bf16 -> the tiled half-precision cache layout of one slot; q -> half
+void launch_pack_kv(const bf16_t* k, const bf16_t* v, f16_t* kt, f16_t* vt, int T, int n_kv, int hd, size_t head_stride, hipStream_t st);
+void launch_to_f16(const bf16_t* src, f16_t* dst, size_t n, hipStream_t st);
 
 struct StatsOut {
   float *max_logit, *lse, *entropy, *kl, *conf;

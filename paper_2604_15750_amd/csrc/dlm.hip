@@ -215,8 +215,9 @@ extern "C" int dlm_model_create(const dlm_config* cfg, const dlm_weights* w, voi
   // unless the environment says DLM_W_STEPS=0.  They are an optimisation: a matrix whose copy does not fit goes without.
   if (rc == DLM_OK && dt == DLM_BF16 && !(getenv("DLM_W_STEPS") && atoi(getenv("DLM_W_STEPS")) == 0)) {
     const int shape[4][4] = {{qkv, d, PERM_ROTARY, cfg->head_dim}, {d, qd, PERM_NONE, 0}, {2 * cfg->d_ffn, d, PERM_GATED, cfg->d_ffn}, {d, cfg->d_ffn, PERM_NONE, 0}};
+    const int kinds[4] = {EPI_QKV, EPI_RESID, EPI_SWIGLU, EPI_RESID};
     for (int k = 0; k < 4; ++k) {
-      m->steps_ct[k] = gemm_bf16_steps_ct(shape[k][0], shape[k][1]);
+      m->steps_ct[k] = gemm_bf16_steps_ct(shape[k][0], shape[k][1], kinds[k]);
       if (!m->steps_ct[k]) continue;
       m->w_steps[k] = std::vector<DevBuf>(L);
       for (int l = 0; l < L; ++l) {
@@ -258,12 +259,12 @@ extern "C" int dlm_state_create(const dlm_model* m, int max_seqs, int max_seq_le
   s->layer_stride = s->slot_stride * max_seqs;
   // split-K workspace: the largest [splits][rows][N] over the four per-layer GEMMs
   size_t pe = 0;
-  const int shapes[4][2] = {{qkv, c.d_model}, {c.d_model, qd}, {2 * c.d_ffn, c.d_model}, {c.d_model, c.d_ffn}};
+  const int shapes[4][3] = {{qkv, c.d_model, EPI_QKV}, {c.d_model, qd, EPI_RESID}, {2 * c.d_ffn, c.d_model, EPI_SWIGLU}, {c.d_model, c.d_ffn, EPI_RESID}};
   for (auto& sh : shapes) {
     int maxsp = 1;
     if (c.dtype == DLM_BF16)
       for (int mt = 1; mt <= (max_rows + 15) / 16; ++mt) {  // the split count depends on the rows only through their 16-row tiles
-        const int sp = gemm_bf16_splits(mt * 16 < max_rows ? mt * 16 : max_rows, sh[0], sh[1]);
+        const int sp = gemm_bf16_splits(mt * 16 < max_rows ? mt * 16 : max_rows, sh[0], sh[1], sh[2]);
         if (sp > maxsp) maxsp = sp;
       }
     size_t e = (size_t)maxsp * max_rows * sh[0];
@@ -280,8 +281,10 @@ extern "C" int dlm_state_create(const dlm_model* m, int max_seqs, int max_seq_le
   A(s->prev_lse, (size_t)max_seqs * 2 * look * 4);
   A(s->h, (size_t)max_rows * c.d_model * 4);
   A(s->x, (size_t)s->max_rows_pad * xw * es);
-  A(s->x2, (size_t)s->max_rows_pad * xw * es);
-  A(s->act, (size_t)s->max_rows_pad * c.d_ffn * es);
+  // a bf16 model keeps the inputs of the O and down projections as pairs of planes (tile_index_pair)
+  const size_t planes = c.dtype == DLM_BF16 ? PAIR_PLANES : 1;
+  A(s->x2, (size_t)s->max_rows_pad * xw * es * planes);
+  A(s->act, (size_t)s->max_rows_pad * c.d_ffn * es * planes);
   A(s->q, (size_t)max_rows * qd * es);
   A(s->part, pe * 4);
   size_t stats_bytes = stats_workspace_bytes(max_rows);
@@ -308,8 +311,8 @@ extern "C" int dlm_state_create(const dlm_model* m, int max_seqs, int max_seq_le
     hipError_t e = hipMemset(s->x.p, 0, (size_t)s->max_rows_pad * xw * es);
     if (e == hipSuccess) e = hipMemset(s->kcache.p, 0, s->layer_stride * c.n_layers * es);
     if (e == hipSuccess) e = hipMemset(s->vcache.p, 0, s->layer_stride * c.n_layers * es);
-    if (e == hipSuccess) e = hipMemset(s->x2.p, 0, (size_t)s->max_rows_pad * xw * es);
-    if (e == hipSuccess) e = hipMemset(s->act.p, 0, (size_t)s->max_rows_pad * c.d_ffn * es);
+    if (e == hipSuccess) e = hipMemset(s->x2.p, 0, (size_t)s->max_rows_pad * xw * es * planes);
+    if (e == hipSuccess) e = hipMemset(s->act.p, 0, (size_t)s->max_rows_pad * c.d_ffn * es * planes);
     if (e == hipSuccess) e = hipMemset(s->counters.p, 0, (size_t)n_counters * 4);
     if (e != hipSuccess) rc = dlm_fail(DLM_EHIP, "dlm_state_create: hipMemset: %s", hipGetErrorString(e));
   }
@@ -437,7 +440,8 @@ int run_step_bf16(dlm_state* s, const dlm_step_desc* d, const SeqMeta& meta, con
   RowTables t{(int32_t*)s->row_seq.p, (int32_t*)s->row_pos.p, (int32_t*)s->row_tok.p, (int32_t*)s->row_slot.p, (float*)s->rope_cos.p, (float*)s->rope_sin.p,
               (int64_t*)s->prev_row.p, (int64_t*)s->save_row.p};
   float* h = (float*)s->h.p;
-  T *x = (T*)s->x.p, *x2 = (T*)s->x2.p, *act = (T*)s->act.p, *q = (T*)s->q.p;
+  T *x = (T*)s->x.p, *x2 = (T*)s->x2.p, *act = (T*)s->act.p;
+  f16_t* q = (f16_t*)s->q.p;  // Q and the KV cache hold IEEE half (common.h)
   float* ssq = (float*)s->ssq.p;
   Profile& pf = s->prof;
   GemmEpi base;
@@ -446,9 +450,9 @@ int run_step_bf16(dlm_state* s, const dlm_step_desc* d, const SeqMeta& meta, con
   base.counters = (int*)s->counters.p;
   // every layer GEMM of this pass must fit the partial-tile workspace the state was created with
   {
-    const int shapes[4][2] = {{qd + 2 * nkv * hd, dm}, {dm, qd}, {2 * ffn, dm}, {dm, ffn}};
+    const int shapes[4][3] = {{qd + 2 * nkv * hd, dm, EPI_QKV}, {dm, qd, EPI_RESID}, {2 * ffn, dm, EPI_SWIGLU}, {dm, ffn, EPI_RESID}};
     for (auto& sh : shapes)
-      if ((size_t)gemm_bf16_splits(rows, sh[0], sh[1]) * rows * sh[0] > s->part_elems)
+      if ((size_t)gemm_bf16_splits(rows, sh[0], sh[1], sh[2]) * rows * sh[0] > s->part_elems)
         return dlm_fail(DLM_ECAPACITY, "dlm_step: split-K workspace too small for %d rows x %d columns", rows, sh[0]);
   }
   auto gemm = [&](int cls, const T* a, const void* w, int N, int K, const GemmEpi& e) {
@@ -463,8 +467,8 @@ int run_step_bf16(dlm_state* s, const dlm_step_desc* d, const SeqMeta& meta, con
   // chunks of the row sums of squares the next consumer reads: the embedding's, then those of the GEMM that produced them
   int nch = norm_chunks(dm);
   for (int l = 0; l < c.n_layers; ++l) {
-    T* kc = (T*)s->kcache.p + s->layer_stride * l;
-    T* vc = (T*)s->vcache.p + s->layer_stride * l;
+    f16_t* kc = (f16_t*)s->kcache.p + s->layer_stride * l;
+    f16_t* vc = (f16_t*)s->vcache.p + s->layer_stride * l;
     {
       GemmEpi e = base;
       e.kind = EPI_QKV;
@@ -476,7 +480,7 @@ int run_step_bf16(dlm_state* s, const dlm_step_desc* d, const SeqMeta& meta, con
       gemm(PC_QKV, x, m->wqkv[l].p, qd + 2 * nkv * hd, dm, e);
     }
     { ProfScope ps(pf, st, PC_ATTENTION);
-      launch_attention<T>(q, kc, vc, s->slot_stride, s->head_stride, am, x2, true, rows, max_seq_rows, nq, nkv, hd, st); }
+      launch_attention_f16(q, kc, vc, s->slot_stride, s->head_stride, am, x2, true, rows, max_seq_rows, nq, nkv, hd, st); }
     {
       GemmEpi e = base;
       e.kind = EPI_RESID;
@@ -704,7 +708,7 @@ extern "C" int dlm_gemm_nt(const void* x, const void* w, void* y, int M, int N, 
   const size_t mp = (size_t)(M + 15) / 16 * 16;
   const int n_counters = gemm_bf16_counters(M, N);
   const size_t tiled_bytes = ((mp * K + (size_t)N * K) * 2 + 15) / 16 * 16;
-  const size_t part_bytes = (size_t)gemm_bf16_splits(M, N, K) * M * N * 4;
+  const size_t part_bytes = (size_t)gemm_bf16_splits(M, N, K, EPI_SUM) * M * N * 4;
   void* ws = nullptr;
   if (hipMalloc(&ws, tiled_bytes + part_bytes + (size_t)n_counters * 4) != hipSuccess) { (void)hipGetLastError(); return dlm_fail(DLM_ENOMEM, "dlm_gemm_nt: workspace allocation failed"); }
   bf16_t* xt = (bf16_t*)ws;
@@ -712,7 +716,7 @@ extern "C" int dlm_gemm_nt(const void* x, const void* w, void* y, int M, int N, 
   float* part = (float*)((char*)ws + tiled_bytes);
   launch_pack_act((const bf16_t*)x, xt, M, K, st);
   launch_pack_weight((const bf16_t*)w, wt, N, K, PERM_NONE, 0, st);
-  const int splits = gemm_bf16_splits(M, N, K);
+  const int splits = gemm_bf16_splits(M, N, K, EPI_SUM);
   GemmEpi ge;
   memset(&ge, 0, sizeof ge);
   ge.out_bf16 = (bf16_t*)y;
@@ -743,15 +747,18 @@ extern "C" int dlm_attention(const void* q, const void* k, const void* v, void* 
     launch_attention<float>((const float*)q, (const float*)k, (const float*)v, 0, 0, am, (float*)out, false, A, A, n_q, n_kv, head_dim, st);
     return DLM_OK;
   }
-  // bf16: re-tile K and V into the cache layout first (test helper: allocates and synchronises)
+  // bf16: K and V re-tiled into the half-precision cache layout, q converted to half (test helper: allocates and synchronises)
   const size_t head_stride = (size_t)((T + 31) / 32 * 32) * head_dim, bytes = head_stride * n_kv * 2;
+  const size_t q_elems = (size_t)A * n_q * head_dim, q_bytes = (q_elems * 2 + 255) / 256 * 256;
   void* ws = nullptr;
-  if (hipMalloc(&ws, 2 * bytes) != hipSuccess) { (void)hipGetLastError(); return dlm_fail(DLM_ENOMEM, "dlm_attention: workspace allocation failed"); }
-  bf16_t* kt = (bf16_t*)ws;
-  bf16_t* vt = kt + head_stride * n_kv;
+  if (hipMalloc(&ws, 2 * bytes + q_bytes) != hipSuccess) { (void)hipGetLastError(); return dlm_fail(DLM_ENOMEM, "dlm_attention: workspace allocation failed"); }
+  f16_t* kt = (f16_t*)ws;
+  f16_t* vt = kt + head_stride * n_kv;
+  f16_t* qh = vt + head_stride * n_kv;
   hipError_t e = hipMemsetAsync(ws, 0, 2 * bytes, st);
   launch_pack_kv((const bf16_t*)k, (const bf16_t*)v, kt, vt, T, n_kv, head_dim, head_stride, st);
-  launch_attention<bf16_t>((const bf16_t*)q, kt, vt, 0, head_stride, am, (bf16_t*)out, false, A, A, n_q, n_kv, head_dim, st);
+  launch_to_f16((const bf16_t*)q, qh, q_elems, st);
+  launch_attention_f16(qh, kt, vt, 0, head_stride, am, (bf16_t*)out, false, A, A, n_q, n_kv, head_dim, st);
   if (e == hipSuccess) e = hipStreamSynchronize(st);
   (void)hipFree(ws);
   if (e != hipSuccess) return dlm_fail(DLM_EHIP, "dlm_attention: %s", hipGetErrorString(e));

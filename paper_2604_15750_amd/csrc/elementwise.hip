@@ -151,20 +151,11 @@ __global__ void rope_kv_kernel(const float* __restrict__ part, int splits, size_
   const bool is_k = head < n_q + n_kv;
   const int kvh = is_k ? head - n_q : head - n_q - n_kv;
   T* base = (is_k ? kcache : vcache) + (size_t)meta.slot[t.row_seq[r]] * slot_stride;
-  if (sizeof(T) == 4) {  // fp32 cache: row-major [pos][n_kv*hd]
-    T* dst = base + (size_t)pos * n_kv * hd + (size_t)kvh * hd;
-    dst[i] = from_f32<T>(a);
-    dst[i + half] = from_f32<T>(b);
-  } else {               // bf16 cache: fragment tiles per kv head
-    T* dst = base + (size_t)kvh * head_stride;
-    if (is_k) {
-      dst[kv_k_index(pos, i, hd)] = from_f32<T>(a);
-      dst[kv_k_index(pos, i + half, hd)] = from_f32<T>(b);
-    } else {
-      dst[kv_v_index(pos, i, hd)] = from_f32<T>(a);
-      dst[kv_v_index(pos, i + half, hd)] = from_f32<T>(b);
-    }
-  }
+  // fp32 cache: row-major [pos][n_kv*hd] (this kernel serves the fp32 model; a bf16 model writes its tiled half-precision
+  // cache from the QKV GEMM's epilogue)
+  T* dst = base + (size_t)pos * n_kv * hd + (size_t)kvh * hd;
+  dst[i] = from_f32<T>(a);
+  dst[i + half] = from_f32<T>(b);
 }
 
 }  // namespace
@@ -197,11 +188,10 @@ void launch_rope_kv(const float* part, int splits, const float* ssq, int d, floa
                                              meta, q, kcache, vcache, slot_stride, head_stride, n_q, n_kv, hd);
 }
 
-#define INST(T)                                                                                                                      \
-  template void launch_embed_norm<T>(const T*, const int32_t*, const RowTables&, const float*, float*, T*, float*, int, int, int, hipStream_t); \
-  template void launch_reduce_residual_norm<T>(const float*, int, float*, const float*, T*, float*, int, int, hipStream_t);             \
-  template void launch_silu_mul<T>(const float*, int, const float*, int, float, T*, int, int, hipStream_t);                             \
-  template void launch_rope_kv<T>(const float*, int, const float*, int, float, const RowTables&, const SeqMeta&, T*, T*, T*, size_t,    \
-                                  size_t, int, int, int, int, hipStream_t);
-INST(float)
-INST(bf16_t)
+// the row-wise glue kernels serve the fp32 model; a bf16 model runs them in its GEMM epilogues and uses only the embedding here
+template void launch_embed_norm<float>(const float*, const int32_t*, const RowTables&, const float*, float*, float*, float*, int, int, int, hipStream_t);
+template void launch_embed_norm<bf16_t>(const bf16_t*, const int32_t*, const RowTables&, const float*, float*, bf16_t*, float*, int, int, int, hipStream_t);
+template void launch_reduce_residual_norm<float>(const float*, int, float*, const float*, float*, float*, int, int, hipStream_t);
+template void launch_silu_mul<float>(const float*, int, const float*, int, float, float*, int, int, hipStream_t);
+template void launch_rope_kv<float>(const float*, int, const float*, int, float, const RowTables&, const SeqMeta&, float*, float*, float*, size_t,
+                                    size_t, int, int, int, int, hipStream_t);

@@ -84,16 +84,18 @@ int choose_kernel(int M, int N, int K, int kind) {
   if (kind == EPI_STATS) return KERNEL_TILED;  // only the tiled kernel has that epilogue (the caller keeps to GEMM_STATS_MAX_ROWS rows)
   const int pr = weight_pack_rows(N);
   const bool whole_groups = N % (16 * pr) == 0;
+  const bool pair = kind == EPI_RESID;  // X is a pair of planes: twice the X fragments in the mid kernel's registers
   if (M <= GEMM_SKINNY_MAX_ROWS && kind != EPI_DIRECT && whole_groups) {
-    if (pr == 2 && (M > 16 || gemm_mid_fills_chip(M, N, K))) return KERNEL_MID;
+    if (pr == 2 && (M > 16 || gemm_mid_fills_chip(M, N, K, kind))) return KERNEL_MID;
     if (pr == 1 && M > 16 && K >= 8192) return KERNEL_MID;
     // a narrow matrix with a few more than 256 column tiles: the skinny kernel's one-tile workgroups would run a second,
     // nearly empty round over the compute units; 32-column groups fit in one
     if (pr == 1 && M <= 16 && (N >> 4) > 256 && (N >> 4) <= 384) return KERNEL_MID;
     return KERNEL_SKINNY;
   }
-  if (M > GEMM_SKINNY_MAX_ROWS && M <= (pr == 1 ? GEMM_MID_MAX_ROWS_NARROW : GEMM_MID_MAX_ROWS) && whole_groups) return KERNEL_MID;
-  if (M > GEMM_MACRO_MIN_ROWS_NARROW || (M > GEMM_SKINNY_MAX_ROWS && N > 8192)) return KERNEL_MACRO;
+  if (M > GEMM_SKINNY_MAX_ROWS && M <= (pr == 1 && !pair ? GEMM_MID_MAX_ROWS_NARROW : GEMM_MID_MAX_ROWS) && whole_groups) return KERNEL_MID;
+  // EPI_RESID has no instantiation of the tiled kernel (which stages one plane of X): what the mid kernel does not take goes to the macro kernel
+  if (M > GEMM_MACRO_MIN_ROWS_NARROW || (M > GEMM_SKINNY_MAX_ROWS && N > 8192) || pair) return KERNEL_MACRO;
   return KERNEL_TILED;
 }
 
@@ -105,9 +107,9 @@ void launch_pack_weight(const bf16_t* w, bf16_t* out, int N, int K, int perm, in
 void launch_pack_weight_steps(const bf16_t* w, bf16_t* out, int N, int K, int ct, int perm, int perm_param, hipStream_t st) {
   pack_weight_steps_kernel<<<2048, 256, 0, st>>>((const bf16x8*)w, (bf16x8*)out, N, K, ct, ct == 1 ? 8 : 4, perm, perm_param);
 }
-int gemm_bf16_steps_ct(int N, int K) {
-  switch (choose_kernel(16, N, K, EPI_SUM)) {
-    case KERNEL_MID: return gemm_mid_steps_ct(N, K);
+int gemm_bf16_steps_ct(int N, int K, int kind) {
+  switch (choose_kernel(16, N, K, kind)) {
+    case KERNEL_MID: return gemm_mid_steps_ct(N, K, kind);
     case KERNEL_SKINNY: {  // one column tile and 8 wavefronts per workgroup, or a pair of tiles and 4
       const int pr = weight_pack_rows(N);
       return ((K >> 5) % (pr == 1 ? 8 : 4) == 0 && N % (16 * pr) == 0) ? pr : 0;
@@ -119,10 +121,10 @@ void launch_pack_act(const bf16_t* x, bf16_t* out, int M, int K, hipStream_t st)
   pack_act_kernel<<<512, 256, 0, st>>>((const bf16x8*)x, (bf16x8*)out, M, K);
 }
 
-int gemm_bf16_splits(int M, int N, int K) {
-  switch (choose_kernel(M, N, K, EPI_SUM)) {
-    case KERNEL_MID: return gemm_mid_splits(M, N, K);
-    case KERNEL_MACRO: return gemm_macro_splits(M, N, K);
+int gemm_bf16_splits(int M, int N, int K, int kind) {
+  switch (choose_kernel(M, N, K, kind)) {
+    case KERNEL_MID: return gemm_mid_splits(M, N, K, kind);
+    case KERNEL_MACRO: return gemm_macro_splits(M, N, K, kind);
     case KERNEL_TILED: return gemm_tiled_splits(M, N, K);
     default: return 1;
   }

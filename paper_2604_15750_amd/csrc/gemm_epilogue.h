@@ -5,6 +5,12 @@
 #include "common.h"
 
 __device__ inline bf16x4 to_bf16x4(f32x4 v) { return bf16x4{(bf16_t)v[0], (bf16_t)v[1], (bf16_t)v[2], (bf16_t)v[3]}; }
+__device__ inline f16x4 to_f16x4_sat(f32x4 v) { return f16x4{to_f16_sat(v[0]), to_f16_sat(v[1]), to_f16_sat(v[2]), to_f16_sat(v[3])}; }
+__device__ inline f32x4 widen4(bf16x4 v) { return f32x4{(float)v[0], (float)v[1], (float)v[2], (float)v[3]}; }
+
+// Planes of the GEMM's input X: the EPI_RESID GEMMs (O and down) read a pair (hi, lo) per fragment tile, the others one.
+template <int EPI>
+struct XPlanes { static constexpr int value = EPI == EPI_RESID ? PAIR_PLANES : 1; };
 
 // 1/rms of rows [m_lo, m_lo + rows) from the producer's partial sums of squares into s_rinv, by the whole workgroup of NT
 // threads: sixteen lanes per row, each adding every sixteenth chunk in ascending order, then a fixed butterfly
@@ -76,20 +82,20 @@ __device__ inline void finish_qkv(const GemmEpi& e, int m, int nc, int gp, f32x4
     a = ra;
     b = rb;
   }
-  const bf16x4 ab = to_bf16x4(a), bb = to_bf16x4(b);
+  const f16x4 ab = to_f16x4_sat(a), bb = to_f16x4_sat(b);
   if (head < e.n_q) {
-    bf16_t* dst = e.q + (size_t)m * e.n_q * hd + (size_t)head * hd;
-    *(bf16x4*)(dst + i) = ab;
-    *(bf16x4*)(dst + i + half) = bb;
+    f16_t* dst = e.q + (size_t)m * e.n_q * hd + (size_t)head * hd;
+    *(f16x4*)(dst + i) = ab;
+    *(f16x4*)(dst + i + half) = bb;
     return;
   }
   const bool is_k = head < e.n_q + e.n_kv;
   const int kvh = is_k ? head - e.n_q : head - e.n_q - e.n_kv;
   const int pos = e.row_pos[m];
-  bf16_t* dst = (is_k ? e.kcache : e.vcache) + (size_t)e.row_slot[m] * e.slot_stride + (size_t)kvh * e.head_stride;
+  f16_t* dst = (is_k ? e.kcache : e.vcache) + (size_t)e.row_slot[m] * e.slot_stride + (size_t)kvh * e.head_stride;
   if (is_k) {  // four consecutive dims share a lane slot of the K tiling
-    *(bf16x4*)(dst + kv_k_index(pos, i, hd)) = ab;
-    *(bf16x4*)(dst + kv_k_index(pos, i + half, hd)) = bb;
+    *(f16x4*)(dst + kv_k_index(pos, i, hd)) = ab;
+    *(f16x4*)(dst + kv_k_index(pos, i + half, hd)) = bb;
   } else {
 #pragma unroll
     for (int j = 0; j < 4; ++j) {
@@ -101,10 +107,13 @@ __device__ inline void finish_qkv(const GemmEpi& e, int m, int nc, int gp, f32x4
 
 // gate = packed columns nc+4gp .. +3, up = the same + 8: output columns 8 (nc/16) + 4gp .. +3 (weights packed with PERM_GATED)
 __device__ inline void finish_swiglu(const GemmEpi& e, int m, int nc, int gp, f32x4 g, f32x4 u) {
-  bf16x4 o;
+  f32x4 a;
 #pragma unroll
-  for (int t = 0; t < 4; ++t) o[t] = (bf16_t)(g[t] / (1.f + __expf(-g[t])) * u[t]);
-  *(bf16x4*)(e.act + tile_index(m, 8 * (nc >> 4) + 4 * gp, e.ffn)) = o;
+  for (int t = 0; t < 4; ++t) a[t] = g[t] / (1.f + __expf(-g[t])) * u[t];
+  const bf16x4 hi = to_bf16x4(a), lo = to_bf16x4(a - widen4(hi));  // the down projection's input: a pair of planes
+  const size_t o = tile_index_pair(m, 8 * (nc >> 4) + 4 * gp, e.ffn, 0);
+  *(bf16x4*)(e.act + o) = hi;
+  *(bf16x4*)(e.act + o + 512) = lo;
 }
 
 // residual add and next norm's x for columns n .. n+3 of row m; returns the four columns' share of sum h^2

@@ -35,25 +35,28 @@ __device__ inline __amdgpu_buffer_rsrc_t part_rsrc(const float* base) {
 #define GLOBAL_PTR(p) ((const void __attribute__((address_space(1)))*)(p))
 #define LDS_PTR(p) ((void __attribute__((address_space(3)))*)(p))
 
-template <int WM, int WN>
+// XP: planes of X (the EPI_RESID GEMMs read a pair per fragment tile)
+template <int WM, int WN, int XP = 1>
 struct MacroShape {
-  static constexpr int AF = 2 * WM, BF = 2 * WN;  // X (row) and W (column) fragments of a stage
+  static constexpr int AT = 2 * WM;                // row tiles of the workgroup
+  static constexpr int AF = AT * XP, BF = 2 * WN;  // X (row tiles x planes) and W (column) fragments of a stage
   static constexpr int NFR = AF + BF;
   static constexpr int LPS = NFR / 4;              // direct-to-LDS loads per wavefront and stage
   static constexpr int STAGE = NFR * 1024;
   static constexpr int S = 131072 / STAGE > 8 ? 8 : 131072 / STAGE;  // stages: at most 128 KiB
-  static constexpr int LDS_BYTES = S * STAGE + AF * 16 * 4 * 3;      // + 1/rms of the rows, two partial sums of squares per row
+  static constexpr int LDS_BYTES = S * STAGE + AT * 16 * 4 * 3;      // + 1/rms of the rows, two partial sums of squares per row
 };
 
 template <int WM, int WN, int PR, int EPI>
 __global__ __launch_bounds__(TPB) void gemm_macro_kernel(const bf16x8* __restrict__ xt, const bf16x8* __restrict__ wt, int M, int N, int K,
                                                          int nblocks, int mblocks, int splits, int kt_per_split, GemmEpi e) {
-  typedef MacroShape<WM, WN> SH;
-  constexpr int AF = SH::AF, BF = SH::BF, LPS = SH::LPS, STAGE = SH::STAGE, S = SH::S;
+  constexpr int XP = XPlanes<EPI>::value;
+  typedef MacroShape<WM, WN, XP> SH;
+  constexpr int AT = SH::AT, AF = SH::AF, BF = SH::BF, LPS = SH::LPS, STAGE = SH::STAGE, S = SH::S;
   static_assert(AF % 4 == 0 && BF % 4 == 0 && S >= 4 && (S - 2) * LPS < 64, "pipeline shape");
   extern __shared__ __align__(16) unsigned char lds[];
-  float* s_rinv = (float*)(lds + S * STAGE);  // [AF * 16]
-  float* s_ssq = s_rinv + AF * 16;            // [2][AF * 16]
+  float* s_rinv = (float*)(lds + S * STAGE);  // [AT * 16]
+  float* s_ssq = s_rinv + AT * 16;            // [2][AT * 16]
 
   // workgroup id -> (column block, K split, row block): ids congruent mod 8 share an XCD
   int q = blockIdx.x >> 3;
@@ -67,9 +70,10 @@ __global__ __launch_bounds__(TPB) void gemm_macro_kernel(const bf16x8* __restric
   const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int wm = wave >> 1, wn = wave & 1;
   const int KT = K >> 5, MTILES = (M + 15) >> 4, NT = N >> 4;
-  const int mt0 = rb * AF, nt0 = cb * BF;
+  const int mt0 = rb * AT, nt0 = cb * BF;
 
-  // stage kt % S <- k-tile kt: fragment f (f < AF: X row tile mt0 + f, else W column tile nt0 + f - AF) is moved by wavefront f % 4
+  // stage kt % S <- k-tile kt: fragment f (f < AF: plane f % XP of X row tile mt0 + f / XP, else W column tile nt0 + f - AF) is
+  // moved by wavefront f % 4
   const int kb = split * kt_per_split, nk = min(KT, kb + kt_per_split) - kb;  // this workgroup's k-tiles: kb .. kb + nk - 1
   auto issue = [&](int kt) {
     const int t = kb + min(kt, nk - 1);
@@ -79,8 +83,8 @@ __global__ __launch_bounds__(TPB) void gemm_macro_kernel(const bf16x8* __restric
       const int f = i * 4 + wave;
       const bf16x8* src;
       if (i < AF / 4) {
-        const int mt = min(mt0 + f, MTILES - 1);
-        src = xt + ((size_t)mt * KT + t) * 64 + lane;
+        const int mt = min(mt0 + f / XP, MTILES - 1);
+        src = xt + (((size_t)mt * KT + t) * XP + f % XP) * 64 + lane;
       } else {
         const int nt = min(nt0 + f - AF, NT - 1);
         src = PR == 2 ? wt + (((size_t)(nt >> 1) * KT + t) * 2 + (nt & 1)) * 64 + lane : wt + ((size_t)nt * KT + t) * 64 + lane;
@@ -94,11 +98,11 @@ __global__ __launch_bounds__(TPB) void gemm_macro_kernel(const bf16x8* __restric
   for (int j = 0; j < WN; ++j)
 #pragma unroll
     for (int i = 0; i < WM; ++i) acc[j][i] = f32x4{0.f, 0.f, 0.f, 0.f};
-  bf16x8 xf[2][WM], wf[2][WN];
+  bf16x8 xf[2][WM * XP], wf[2][WN];
   auto read_frags = [&](int buf, int kt) {
     const bf16x8* st = (const bf16x8*)(lds + (kt % S) * STAGE) + lane;
 #pragma unroll
-    for (int i = 0; i < WM; ++i) xf[buf][i] = st[(wm * WM + i) * 64];
+    for (int i = 0; i < WM * XP; ++i) xf[buf][i] = st[(wm * WM * XP + i) * 64];
 #pragma unroll
     for (int j = 0; j < WN; ++j) wf[buf][j] = st[(AF + wn * WN + j) * 64];
   };
@@ -106,7 +110,7 @@ __global__ __launch_bounds__(TPB) void gemm_macro_kernel(const bf16x8* __restric
 #pragma unroll
     for (int j = 0; j < WN; ++j)
 #pragma unroll
-      for (int i = 0; i < WM; ++i) acc[j][i] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(wf[buf][j], xf[buf][i], acc[j][i], 0, 0, 0);
+      for (int i = 0; i < WM * XP; ++i) acc[j][i / XP] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(wf[buf][j], xf[buf][i], acc[j][i / XP], 0, 0, 0);
   };
 
 #pragma unroll
@@ -178,7 +182,7 @@ __global__ __launch_bounds__(TPB) void gemm_macro_kernel(const bf16x8* __restric
   }
 
   // ---- epilogue
-  if (EPI != EPI_RESID) block_rinv<TPB>(e.rs, m_lo, max(0, min(M, m_lo + AF * 16) - m_lo), s_rinv);
+  if (EPI != EPI_RESID) block_rinv<TPB>(e.rs, m_lo, max(0, min(M, m_lo + AT * 16) - m_lo), s_rinv);
   __syncthreads();
   // The accumulators leave the registers through LDS (each wavefront its own region, half of its column tiles at a time), so
   // that the epilogue runs as a loop over fragments instead of 64 unrolled copies with every accumulator live.
@@ -208,10 +212,10 @@ __global__ __launch_bounds__(TPB) void gemm_macro_kernel(const bf16x8* __restric
   if (EPI == EPI_RESID) {  // the workgroup's share of sum h^2 per row: its two column halves in order
     if (g == 0)
 #pragma unroll
-      for (int i = 0; i < WM; ++i) s_ssq[wn * AF * 16 + (wm * WM + i) * 16 + ml] = ssq[i];
+      for (int i = 0; i < WM; ++i) s_ssq[wn * AT * 16 + (wm * WM + i) * 16 + ml] = ssq[i];
     __syncthreads();
     const int m = m_lo + tid;
-    if (tid < AF * 16 && m < M) e.ssq_out[(size_t)m * nblocks + cb] = s_ssq[tid] + s_ssq[AF * 16 + tid];
+    if (tid < AT * 16 && m < M) e.ssq_out[(size_t)m * nblocks + cb] = s_ssq[tid] + s_ssq[AT * 16 + tid];
   }
 }
 
@@ -223,12 +227,13 @@ struct MacroPlan {
 // charged for their heavier LDS traffic
 int g_macro_wgs = 256;  // workgroups a K split aims at
 
-MacroPlan macro_plan(int M, int N, int K, bool may_split) {
+MacroPlan macro_plan(int M, int N, int K, bool may_split, int kind) {
   const int cand[3][2] = {{4, 8}, {4, 4}, {6, 8}};
   const double penalty[3] = {1.0, 1.25, 0.9};
   MacroPlan best{4, 8, 1, 1};
   double best_cost = 1e300;
-  for (int c = 0; c < 3; ++c) {
+  const int ncand = kind == EPI_RESID ? 2 : 3;  // X as a pair of planes: a 192-row tile's stages no longer fit LDS four deep
+  for (int c = 0; c < ncand; ++c) {
     const int bm = 32 * cand[c][0], bn = 32 * cand[c][1];
     const int mb = (M + bm - 1) / bm, nb = (N + bn - 1) / bn;
     const int rounds = (mb * nb + 255) / 256;
@@ -248,7 +253,7 @@ MacroPlan macro_plan(int M, int N, int K, bool may_split) {
 
 template <int WM, int WN, int PR, int EPI>
 void launch_one(const bf16_t* xt, const bf16_t* wt, int M, int N, int K, const MacroPlan& p, const GemmEpi& e, hipStream_t st) {
-  typedef MacroShape<WM, WN> SH;
+  typedef MacroShape<WM, WN, XPlanes<EPI>::value> SH;
   static bool configured = false;  // raise the dynamic LDS limit of this instantiation once
   if (!configured) {
     (void)hipFuncSetAttribute((const void*)gemm_macro_kernel<WM, WN, PR, EPI>, hipFuncAttributeMaxDynamicSharedMemorySize, SH::LDS_BYTES);
@@ -261,7 +266,7 @@ void launch_one(const bf16_t* xt, const bf16_t* wt, int M, int N, int K, const M
 
 template <int PR, int EPI>
 void launch_shape(const bf16_t* xt, const bf16_t* wt, int M, int N, int K, const MacroPlan& p, const GemmEpi& e, hipStream_t st) {
-  if (p.wm == 6) launch_one<6, 8, PR, EPI>(xt, wt, M, N, K, p, e, st);
+  if (p.wm == 6) { if constexpr (EPI != EPI_RESID) launch_one<6, 8, PR, EPI>(xt, wt, M, N, K, p, e, st); }
   else if (p.wn == 8) launch_one<4, 8, PR, EPI>(xt, wt, M, N, K, p, e, st);
   else launch_one<4, 4, PR, EPI>(xt, wt, M, N, K, p, e, st);
 }
@@ -274,13 +279,13 @@ void launch_epi(const bf16_t* xt, const bf16_t* wt, int M, int N, int K, const M
 
 }  // namespace
 
-int gemm_macro_ssq_chunks(int M, int N) { return macro_plan(M, N, 32, false).nblocks; }
-int gemm_macro_splits(int M, int N, int K) { return macro_plan(M, N, K, true).splits; }
+int gemm_macro_ssq_chunks(int M, int N) { return macro_plan(M, N, 32, false, EPI_RESID).nblocks; }
+int gemm_macro_splits(int M, int N, int K, int kind) { return macro_plan(M, N, K, true, kind).splits; }
 int gemm_macro_counters(int max_rows, int max_n) { return ((max_n + 127) / 128) * ((max_rows + 127) / 128); }  // 128 x 128 tiles are the smallest
 void gemm_macro_set_target(int wgs) { g_macro_wgs = wgs; }
 
 void launch_gemm_macro(const bf16_t* xt, const bf16_t* wt, int M, int N, int K, const GemmEpi& e, hipStream_t st) {
-  const MacroPlan p = macro_plan(M, N, K, e.kind != EPI_DIRECT);  // EPI_DIRECT has no workspace
+  const MacroPlan p = macro_plan(M, N, K, e.kind != EPI_DIRECT, e.kind);  // EPI_DIRECT has no workspace
   switch (e.kind) {
     case EPI_QKV: launch_epi<EPI_QKV>(xt, wt, M, N, K, p, e, st); break;
     case EPI_SWIGLU: launch_epi<EPI_SWIGLU>(xt, wt, M, N, K, p, e, st); break;

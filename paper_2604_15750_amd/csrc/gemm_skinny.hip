@@ -35,12 +35,13 @@ __global__ __launch_bounds__(NWV * 64) void gemm_skinny_kernel(const bf16x8* __r
   const size_t wstride = steps ? (size_t)gridDim.x * NWV * R * 64 : R * 64;
   const int tsub = steps ? t_begin : 0;
 
+  constexpr int XP = XPlanes<EPI>::value;  // planes of X: a fragment tile of the EPI_RESID GEMMs' input is a pair (hi, lo), 2 KiB
   f32x4 acc[R][MT];
 #pragma unroll
   for (int r = 0; r < R; ++r)
 #pragma unroll
     for (int j = 0; j < MT; ++j) acc[r][j] = f32x4{0.f, 0.f, 0.f, 0.f};
-  bf16x8 wreg[2][D][R], xreg[2][D][MT];
+  bf16x8 wreg[2][D][R], xreg[2][D][MT * XP];
 
   auto load = [&](int buf, int tb) {
 #pragma unroll
@@ -50,7 +51,10 @@ __global__ __launch_bounds__(NWV * 64) void gemm_skinny_kernel(const bf16x8* __r
 #pragma unroll
       for (int r = 0; r < R; ++r) wreg[buf][i][r] = ok ? wbase[(size_t)(t - tsub) * wstride + r * 64] : zero8;
 #pragma unroll
-      for (int j = 0; j < MT; ++j) xreg[buf][i][j] = (ok && j < MTILES) ? xt[((size_t)j * KT + t) * 64 + (j == MTILES - 1 ? xlane_last : lane)] : zero8;
+      for (int j = 0; j < MT; ++j)
+#pragma unroll
+        for (int p = 0; p < XP; ++p)
+          xreg[buf][i][j * XP + p] = (ok && j < MTILES) ? xt[(((size_t)j * KT + t) * XP + p) * 64 + (j == MTILES - 1 ? xlane_last : lane)] : zero8;
     }
   };
   auto compute = [&](int buf) {
@@ -59,7 +63,9 @@ __global__ __launch_bounds__(NWV * 64) void gemm_skinny_kernel(const bf16x8* __r
 #pragma unroll
       for (int j = 0; j < MT; ++j)
 #pragma unroll
-        for (int r = 0; r < R; ++r) acc[r][j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(wreg[buf][i][r], xreg[buf][i][j], acc[r][j], 0, 0, 0);
+        for (int p = 0; p < XP; ++p)
+#pragma unroll
+          for (int r = 0; r < R; ++r) acc[r][j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(wreg[buf][i][r], xreg[buf][i][j * XP + p], acc[r][j], 0, 0, 0);
   };
 
   load(0, t_begin);
@@ -95,14 +101,16 @@ __global__ __launch_bounds__(NWV * 64) void gemm_skinny_kernel(const bf16x8* __r
   }
 }
 
-// batch depth: 8 KiB of W in flight per wavefront for up to 32 rows, half of that beyond (the X fragments take the registers);
-// the step-major copy reads best with batches of four (measured: deeper batches add queueing, not bandwidth)
+// batch depth: 8 KiB of W in flight per wavefront for up to 32 rows (of X fragments: 16 when X is a pair of planes), half of
+// that beyond (the X fragments take the registers); the step-major copy reads best with batches of four (measured: deeper
+// batches add queueing, not bandwidth)
 template <int MT, int EPI>
 void launch_skinny(const bf16_t* xt, const bf16_t* wt, int pr, int M, int N, int K, const GemmEpi& e, hipStream_t st) {
-  if (pr == 1 && e.w_steps) DLM_LAUNCH((gemm_skinny_kernel<MT, 1, 8, 4, EPI, true>), N / 16, 512, 0, st, (const bf16x8*)xt, (const bf16x8*)wt, M, N, K, e);
-  else if (pr == 1) DLM_LAUNCH((gemm_skinny_kernel<MT, 1, 8, (MT <= 2 ? 8 : 4), EPI>), N / 16, 512, 0, st, (const bf16x8*)xt, (const bf16x8*)wt, M, N, K, e);
-  else if (e.w_steps) DLM_LAUNCH((gemm_skinny_kernel<MT, 2, 4, (MT <= 2 ? 4 : 2), EPI, true>), N / 32, 256, 0, st, (const bf16x8*)xt, (const bf16x8*)wt, M, N, K, e);
-  else DLM_LAUNCH((gemm_skinny_kernel<MT, 2, 4, (MT <= 2 ? 4 : 2), EPI>), N / 32, 256, 0, st, (const bf16x8*)xt, (const bf16x8*)wt, M, N, K, e);
+  constexpr int XF = MT * XPlanes<EPI>::value;  // X fragments per k-tile
+  if (pr == 1 && e.w_steps) DLM_LAUNCH((gemm_skinny_kernel<MT, 1, 8, (XF <= 4 ? 4 : 2), EPI, true>), N / 16, 512, 0, st, (const bf16x8*)xt, (const bf16x8*)wt, M, N, K, e);
+  else if (pr == 1) DLM_LAUNCH((gemm_skinny_kernel<MT, 1, 8, (XF <= 2 ? 8 : XF <= 4 ? 4 : 2), EPI>), N / 16, 512, 0, st, (const bf16x8*)xt, (const bf16x8*)wt, M, N, K, e);
+  else if (e.w_steps) DLM_LAUNCH((gemm_skinny_kernel<MT, 2, 4, (XF <= 2 ? 4 : 2), EPI, true>), N / 32, 256, 0, st, (const bf16x8*)xt, (const bf16x8*)wt, M, N, K, e);
+  else DLM_LAUNCH((gemm_skinny_kernel<MT, 2, 4, (XF <= 2 ? 4 : 2), EPI>), N / 32, 256, 0, st, (const bf16x8*)xt, (const bf16x8*)wt, M, N, K, e);
 }
 
 template <int EPI>

@@ -359,7 +359,7 @@ void launch_gemm_tiled(const bf16_t* xt, const bf16_t* wt, int M, int N, int K, 
     case EPI_STATS: launch_stats(xt, wt, M, N, K, p, e, st); break;
     case EPI_QKV: launch_epi<EPI_QKV>(xt, wt, M, N, K, p, e, st); break;
     case EPI_SWIGLU: launch_epi<EPI_SWIGLU>(xt, wt, M, N, K, p, e, st); break;
-    case EPI_RESID: launch_epi<EPI_RESID>(xt, wt, M, N, K, p, e, st); break;
+    // (EPI_RESID, whose X is a pair of planes, is never sent here: choose_kernel in gemm_bf16.hip)
     default: launch_epi<EPI_SUM>(xt, wt, M, N, K, p, e, st); break;
   }
 }

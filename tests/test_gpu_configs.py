@@ -2,7 +2,8 @@
 launch shapes, against the oracle.
 
 The oracle needs about a minute for two passes through 32 layers of an 8B-shaped model, so only
-configuration 1 is also run at full depth (its first two passes); each configuration is run as a
+configurations 1 and 2 are also run at full depth (the first passes, up to the first boundary pass for
+configuration 1); each configuration is run as a
 depth-reduced twin (same widths, heads, vocabulary, prompt and block sizes; 2 layers) and the oracle
 decodes the first passes of it: the prefill pass (prompt + look-ahead rows, the widest launch), the
 in-block denoising passes of the first block and the first boundary pass.  Every pass is fed to the
@@ -92,28 +93,43 @@ def _bf16_dataflow(cfg, W, tokens, device):
 
 def test_full_depth_first_passes(device):
     """Configuration 1 at its full size (32 layers, 15 GB of bf16 weights): the prefill pass (384 rows, the launch
-    configuration of the benchmark's first pass) and the first in-block denoising pass (8 rows: the skinny kernels the
-    benchmark spends its time in), every logit and statistic against the oracle run at full depth on the host.
+    configuration of the benchmark's first pass), the in-block denoising passes of the first block (8 rows: the kernels the
+    benchmark spends its time in) and the first boundary pass (136 rows, KL rows against the retained prefill logits), every
+    logit and statistic against the oracle run at full depth on the host, at the benchmark spec's tolerance: 2e-2 of
+    max(row maximum, sigma_logit) for the worst logit of every row.
 
-    Rounding the activations to bf16 between the GEMMs perturbs a random-init network of this depth by about 2 per cent of
-    the logits' root mean square (the depth-reduced twins above stay near 1e-2 of the row maximum), whoever does the
-    arithmetic: the same dataflow in exact fp32 torch operations is as far from the oracle.  At full depth the bound is
-    therefore 4e-2 of the row maximum for the worst element, 3e-2 for a row's relative L2 error, and the kernels may be no
-    further from the oracle than 1.15 times that reference."""
+    What makes that bound reachable at this depth is where the kernels keep more than bf16's 8 mantissa bits: the attention
+    operands (Q, K, V, probabilities) in IEEE half and the inputs of the O and down projections as bf16 pairs.  The same pass
+    in exact fp32 torch operations with every activation rounded to bf16 between the GEMMs is printed beside it, as
+    information: that dataflow is about 2.3e-2 (relative L2 per row) from the oracle, whoever does the arithmetic."""
     cfg, _, P, N, lmax = inputs.WORKLOADS["llada8b_p256_g256"]
     W = inputs.make_weights(cfg, seed=0, device=device)
     prompt = inputs.make_prompts(cfg, 1, P)[0]
     st = []
-    r = replay(cfg, W, prompt, N, dict(SCALED, l_max=lmax), device, logit_tol=4e-2, max_passes=2, stats_out=st)
+    r = replay(cfg, W, prompt, N, dict(SCALED, l_max=lmax), device, logit_tol=2e-2, max_passes=12, stats_out=st, stop_after="boundary")
     kinds = [t["kind"] for t in r["trace"] if t["op"] == "pass"]
-    assert kinds == ["prefill", "inblock"]
-    assert r["rms"] <= 3e-2, st
+    assert kinds[0] == "prefill" and kinds[-1] == "boundary" and "inblock" in kinds, kinds
+    assert r["boundaries"] == 1 and r["worst"] <= 2e-2
+    assert r["rms"] <= 1.6e-2, st  # a row's relative L2 error: well inside what the worst-element bound needs
     pre = [t for t in r["trace"] if t["op"] == "pass"][0]
     ref = pre["logits"]
     emu = _bf16_dataflow(cfg, W, pre["tokens"], device)
     emu_rms = float((np.sqrt(np.mean((emu - ref) ** 2, -1)) / np.sqrt(np.mean(ref ** 2, -1))).max())
-    assert st[0]["rms"] <= 1.15 * emu_rms + 1e-3, (st[0], emu_rms)
-    print("full depth:", st, "bf16 dataflow in fp32 torch operations:", emu_rms)
+    print("full depth:", kinds, st, "all-bf16 dataflow in fp32 torch operations (information):", emu_rms)
+
+
+def test_full_depth_grouped_query_first_passes(device):
+    """Configuration 2 at its full size (Dream-7B shape: 28 layers, 28 query / 4 kv heads, FFN 18944, vocabulary 152064):
+    the prefill pass (512 + 128 = 640 rows) and the first in-block pass (8 rows against 512 cached keys), every logit and
+    statistic against the oracle at full depth, at the benchmark spec's tolerance."""
+    cfg, _, P, N, lmax = inputs.WORKLOADS["dream7b_p512_g256"]
+    W = inputs.make_weights(cfg, seed=0, device=device)
+    prompt = inputs.make_prompts(cfg, 1, P)[0]
+    st = []
+    r = replay(cfg, W, prompt, N, dict(SCALED, l_max=lmax), device, logit_tol=2e-2, max_passes=2, stats_out=st)
+    kinds = [t["kind"] for t in r["trace"] if t["op"] == "pass"]
+    assert kinds == ["prefill", "inblock"] and r["worst"] <= 2e-2
+    print("full depth, grouped-query shape:", st)
 
 
 def test_batch16_twin_first_iterations(device):

@@ -40,12 +40,12 @@ def _f32(prm):
     return out
 
 
-def replay(cfg, W_dev, prompt, N, prm, device, logit_tol, max_passes=None, stats_out=None):
+def replay(cfg, W_dev, prompt, N, prm, device, logit_tol, max_passes=None, stats_out=None, stop_after=None):
     prm = _f32(prm)
     P, END, lmax, mask = len(prompt), len(prompt) + N, prm["l_max"], cfg["mask_id"]
     Wn = inputs.weights_to_numpy(W_dev)
     trace = []
-    o_decode.decode_full(cfg, Wn, prompt, N, prm, trace, max_passes=max_passes)
+    o_decode.decode_full(cfg, Wn, prompt, N, prm, trace, max_passes=max_passes, stop_after=stop_after)
     model = api.Model(cfg, W_dev)
     look = min(2 * lmax, N)
     max_rows = max(P + look, lmax + look)
