@@ -132,44 +132,233 @@ def test_full_depth_grouped_query_first_passes(device):
     print("full depth, grouped-query shape:", st)
 
 
-def test_batch16_twin_first_iterations(device):
-    """Config 4: 16 sequences packed into shared launches (8 prefill spans of 384 rows per launch, then 16 ragged
-    blocks per launch); sampled sequences are compared pass by pass with the oracle decoding them alone."""
+def _widened(Wn):
+    """The bf16 weights widened to fp64 once (exactly, by the oracle's own routine) instead of on every use: the oracle then
+    spends its time on the arithmetic, and many passes of a depth-reduced twin fit a test."""
+    return {k: [o_fwd.widen(t) for t in v] if isinstance(v, list) else o_fwd.widen(v) for k, v in Wn.items()}
+
+
+def _compare_pass(out, r0, rows, ref_logits, mask, prev_gpu, klf, klc, tol):
+    """One sequence's rows [r0, r0 + rows) of a launch against the oracle: every logit within tol of max(row maximum,
+    sigma_logit); statistics stage-isolated (the oracle's statistics of the GPU's own logits) at 1e-5; KL rows against the
+    oracle's KL of the GPU's own current and retained logits.  Returns (worst relative logit error, the GPU's logits fp64)."""
+    from oracle import stats as o_stats
+    z = o_fwd.widen(inputs.tensor_to_numpy(out.logits[r0: r0 + rows]))
+    scale = np.maximum(np.abs(ref_logits).max(-1, keepdims=True), SIGMA_LOGIT)
+    err = float((np.abs(z - ref_logits) / scale).max())
+    assert err <= tol, err
+    st = o_stats.vocab_stats(z, mask)
+    got = {k: getattr(out, k)[r0: r0 + rows].cpu().numpy() for k in ("max_logit", "lse", "entropy", "conf", "argmax", "kl")}
+    for key in ("max_logit", "lse", "entropy", "conf"):
+        assert (np.abs(got[key] - st[key]) <= 1e-5 * np.maximum(1.0, np.abs(st[key]))).all(), key
+    assert (got["argmax"] == st["argmax"]).all()
+    kl_ref, spread = np.zeros(rows), np.zeros(rows)
+    if klc:
+        kst = o_stats.vocab_stats(z[klf: klf + klc], mask, prev_gpu)
+        kl_ref[klf: klf + klc] = kst["kl"]
+        logp, _, _ = o_stats.log_softmax_masked(z[klf: klf + klc], mask)
+        logq, _, _ = o_stats.log_softmax_masked(prev_gpu, mask)
+        fin = lambda a: np.where(np.isfinite(a), a, 0.0)
+        spread[klf: klf + klc] = np.sum(np.exp(logp) * np.abs(fin(logp) - fin(logq)), -1)
+    assert (np.abs(got["kl"] - kl_ref) <= 1e-5 * np.maximum(1.0, np.abs(kl_ref)) + 1e-5 * spread).all()
+    return err, z
+
+
+def test_long_context_late_passes(device):
+    """Configuration 3 (prompt 1024 + generation 1024, L_max 128) late in its decode, on the depth-reduced twin: passes whose
+    key counts run from 1784 to the full 2048 positions - a 1912-row prefill, in-block passes of 128 and 8 rows, a 384-row
+    boundary pass over 2040 keys with 128 KL rows, and the last boundary pass of the sequence - teacher-forced with the same
+    tokens on both sides and compared row by row with the oracle's forward pass, statistics and KL."""
+    cfg, _, P, N, lmax = _twin("llada8b_p1024_g1024")
+    T, mask, V = P + N, cfg["mask_id"], cfg["vocab"]
+    W = inputs.make_weights(cfg, seed=0, device=device)
+    Wn = _widened(inputs.weights_to_numpy(W))
+    model = api.Model(cfg, W)
+    del W
+    rng = np.random.default_rng(3)
+    y = np.full(T, mask, dtype=np.int64)
+    F0 = 1656
+    y[:F0] = rng.integers(0, V - 1, F0)
+    look = 2 * lmax
+    state = api.State(model, 1, T, F0 + look, look)
+    out = api.StepOutputs(F0 + look, V, model.torch_dtype, device)
+    tokens = torch.empty(T, dtype=torch.int32, device=device)
+    cache = o_fwd.KVCache(cfg)
+    prev = None  # (first position, GPU logits) retained by the last prefill / boundary pass
+    worst, keys_seen = 0.0, []
+
+    def run(kind, s0, rows, commit):
+        nonlocal prev, worst
+        klf = klc = svf = svc = 0
+        if kind == "prefill":
+            svf, svc = commit, rows - commit
+        elif kind == "boundary":
+            klf, klc = commit, min(lmax, T - (s0 + commit))
+            svf, svc = commit, rows - commit
+        tokens.copy_(torch.from_numpy(y.astype(np.int32)))
+        api.dlm_step(state, tokens, out, [0, rows], [s0], [commit], [s0], kl_first=[klf], kl_count=[klc], save_first=[svf], save_count=[svc])
+        torch.cuda.synchronize()
+        ref = o_fwd.forward_span(cfg, Wn, cache, y[s0: s0 + rows], s0, commit)
+        zp = prev[1][s0 + klf - prev[0]: s0 + klf - prev[0] + klc] if klc else None
+        err, z = _compare_pass(out, 0, rows, ref, mask, zp, klf, klc, 2e-2)
+        worst = max(worst, err)
+        keys_seen.append(s0 + rows)
+        if svc:
+            prev = (s0 + svf, z[svf: svf + svc])
+        assert state.kv_len(0) == s0 + commit
+
+    run("prefill", 0, F0 + look, F0)                      # 1912 rows; look-ahead [1656, 1912) retained
+    y[F0: F0 + 40] = rng.integers(0, V - 1, 40)           # the block [1656, 1784) partly decoded
+    run("inblock", F0, lmax, 0)                           # 128 rows against 1656 cached keys
+    y[F0: F0 + lmax] = rng.integers(0, V - 1, lmax)       # block finished
+    run("boundary", F0, lmax + look, lmax)                # 384 rows, 2040 keys; KL rows [1784, 1912)
+    F1 = F0 + lmax
+    y[F1 + 3] = int(rng.integers(0, V - 1))
+    run("inblock", F1, 8, 0)                              # 8 rows against 1784 cached keys
+    y[F1: F1 + 50] = rng.integers(0, V - 1, 50)
+    run("inblock", F1, lmax, 0)                           # 128 rows, 1912 keys
+    y[F1: F1 + lmax] = rng.integers(0, V - 1, lmax)
+    run("boundary", F1, lmax + (T - F1 - lmax), lmax)     # the last boundary pass: 264 rows up to position 2048
+    assert max(keys_seen) == T and min(keys_seen[1:]) >= 1784
+    print("keys per pass", keys_seen, "worst relative logit error", worst)
+    state.close()
+    model.close()
+
+
+def test_batch16_packed_replay(device):
+    """Config 4: 16 independent sequences (prompt 256, generation 512, L_max 64) of the depth-reduced twin.  The oracle decodes
+    the first passes of every sequence alone; the HIP path is fed the oracle's tokens (teacher-forced: a low-margin selection
+    cannot make the two sides diverge) with the k-th pass of EVERY sequence packed into shared launches - two launches of
+    eight 384-row prefill spans, then launches that mix sequences on boundary passes (KL rows, retained rows, commits) with
+    sequences on in-block passes of ragged lengths.  Every pass of every sequence is compared (logits, statistics, KL), and
+    block_boundary / select_parallel run packed on the GPU's own statistics must take the oracle rule's decisions."""
+    from oracle import boundary as o_boundary, select as o_select
     cfg, B, P, N, lmax = _twin("llada8b_b16_p256_g512")
     prm = _f32(dict(SCALED, l_max=lmax))
+    T, mask, look, iters = P + N, cfg["mask_id"], 2 * lmax, 4
     W = inputs.make_weights(cfg, seed=0, device=device)
-    Wn = inputs.weights_to_numpy(W)
+    Wn = _widened(inputs.weights_to_numpy(W))
     prompts = inputs.make_prompts(cfg, B, P)
     model = api.Model(cfg, W)
     del W
-    dec = Decoder(model, B, P, N, prm, device)
-    dec.load(prompts)
-    trace = []
-    iters = 3
-    for _ in range(iters):
-        dec.iterate(trace)
-    torch.cuda.synchronize()
-    assert dec.launches == 2 + (iters - 1) and max(dec.rows_log) == 8 * (P + 2 * lmax)  # really packed
-    compared = 0
-    for b in (0, 7, 15):
-        ref = []
-        o_decode.decode_full(cfg, Wn, prompts[b], N, prm, ref, max_passes=iters)
-        ref = [t for t in ref if t["op"] == "pass"]
-        got = [t for t in trace if t["op"] == "pass" and t["seq"] == b]
-        assert len(got) == len(ref) == iters
-        for k, (g, r) in enumerate(zip(got, ref)):
-            # a selection whose margin is below the logit tolerance may legitimately differ from the oracle's; from
-            # then on the two decode different token sequences, so only passes that read the same tokens are compared
-            if g["span_start"] != r["span_start"] or g["rows"] != len(r["tokens"]) or (g["tokens"] != r["tokens"]).any():
-                break
-            assert g["kind"] == r["kind"]
-            z = o_fwd.widen(inputs.tensor_to_numpy(g["logits"]))
-            scale = np.maximum(np.abs(r["logits"]).max(-1, keepdims=True), SIGMA_LOGIT)
-            err = (np.abs(z - r["logits"]) / scale).max()
-            assert err <= 2e-2, (b, k, err)
-            compared += 1
-    assert compared >= 5, compared  # the three prefill spans always, and most of the later passes
-    dec.close()
+    traces = []
+    for b in range(B):
+        tr = []
+        o_decode.decode_full(cfg, Wn, prompts[b], N, prm, tr, max_passes=iters)
+        traces.append(tr)
+    max_rows = 8 * (P + look)
+    state = api.State(model, B, T, max_rows, look)
+    out = api.StepOutputs(max_rows, cfg["vocab"], model.torch_dtype, device)
+    tokens = torch.full((B, T), mask, dtype=torch.int32, device=device)
+    sel = torch.zeros(max_rows, dtype=torch.uint8, device=device)
+    nsel = torch.zeros(B, dtype=torch.int32, device=device)
+    L_dev = torch.zeros(B, dtype=torch.int32, device=device)
+    mg = torch.zeros(B, dtype=torch.float32, device=device)
+    prev = [None] * B
+    compared, mixed_launches, worst = 0, 0, 0.0
+    # per sequence: its records grouped by pass (a pass record followed by the decisions taken on it)
+    per_pass = []
+    for tr in traces:
+        groups = []
+        pending = []  # decisions recorded before the pass they belong to come after it in the trace: select follows its pass,
+        for rec in tr:  # but the prefill's / boundary's records are [pass, (boundary), select]
+            if rec["op"] == "pass":
+                groups.append(dict(p=rec, boundary=None, select=None))
+            elif rec["op"] == "boundary":
+                groups[-1]["boundary"] = rec
+            elif groups:
+                if groups[-1]["select"] is None:
+                    groups[-1]["select"] = rec
+        per_pass.append(groups[:iters])
+    assert all(len(g) == iters for g in per_pass)
+    for k in range(iters):
+        todo = list(range(B))
+        while todo:
+            group, rows_total = [], 0
+            while todo and rows_total + len(per_pass[todo[0]][k]["p"]["tokens"]) <= max_rows:
+                b = todo.pop(0)
+                group.append(b)
+                rows_total += len(per_pass[b][k]["p"]["tokens"])
+            row_off, desc = [0], dict(span=[], commit=[], klf=[], klc=[], svf=[], svc=[])
+            for b in group:
+                rec = per_pass[b][k]["p"]
+                s0, rows, commit = rec["span_start"], len(rec["tokens"]), rec["commit_len"]
+                tokens[b, s0: s0 + rows] = torch.from_numpy(rec["tokens"].astype(np.int32)).to(device)
+                klf = klc = svf = svc = 0
+                if rec["kind"] == "prefill":
+                    svf, svc = P, rows - P
+                elif rec["kind"] == "boundary":
+                    klf, klc = commit, min(lmax, T - (s0 + commit))
+                    svf, svc = commit, rows - commit
+                row_off.append(row_off[-1] + rows)
+                for key, v in zip(("span", "commit", "klf", "klc", "svf", "svc"), (s0, commit, klf, klc, svf, svc)):
+                    desc[key].append(v)
+            kinds = {per_pass[b][k]["p"]["kind"] for b in group}
+            mixed_launches += len(kinds) > 1
+            api.dlm_step(state, tokens, out, row_off, desc["span"], desc["commit"], [b * T + s for b, s in zip(group, desc["span"])], slot=group,
+                         kl_first=desc["klf"], kl_count=desc["klc"], save_first=desc["svf"], save_count=desc["svc"])
+            torch.cuda.synchronize()
+            zs = {}
+            for i, b in enumerate(group):
+                rec = per_pass[b][k]["p"]
+                s0, rows = desc["span"][i], row_off[i + 1] - row_off[i]
+                klf, klc = desc["klf"][i], desc["klc"][i]
+                zp = prev[b][1][s0 + klf - prev[b][0]: s0 + klf - prev[b][0] + klc] if klc else None
+                err, z = _compare_pass(out, row_off[i], rows, rec["logits"], mask, zp, klf, klc, 2e-2)
+                worst = max(worst, err)
+                zs[b] = z
+                if desc["svc"][i]:
+                    prev[b] = (s0 + desc["svf"][i], z[desc["svf"][i]: desc["svf"][i] + desc["svc"][i]])
+                compared += 1
+            # DepGA-Block, packed over the sequences of this launch that have just finished a block (or the prompt)
+            bnd = [i for i, b in enumerate(group) if per_pass[b][k]["p"]["kind"] != "inblock"]
+            if bnd:
+                starts, lens, cold = [], [], []
+                for i in bnd:
+                    b = group[i]
+                    if per_pass[b][k]["p"]["kind"] == "prefill":
+                        starts.append(row_off[i] + P); lens.append(min(lmax, N)); cold.append(1)
+                    else:
+                        starts.append(row_off[i] + desc["klf"][i]); lens.append(desc["klc"][i]); cold.append(0)
+                api.block_boundary(out.kl, out.entropy, starts, lens, L_dev, prm["lam"], prm["l_min"], prm["smooth_radius"], prm["norm_mode"],
+                                   prm["rule"], cold=cold, margin_out=mg)
+                torch.cuda.synchronize()
+                Ls = L_dev[: len(bnd)].cpu().numpy()
+                for j, i in enumerate(bnd):
+                    b = group[i]
+                    kl = out.kl[starts[j]: starts[j] + lens[j]].cpu().numpy().astype(np.float64)
+                    H = out.entropy[starts[j]: starts[j] + lens[j]].cpu().numpy().astype(np.float64)
+                    Lr, _, mr = o_boundary.block_boundary(kl, H, prm["lam"], prm["l_min"], prm["smooth_radius"], prm["norm_mode"], prm["rule"],
+                                                          cold_start=bool(cold[j]))
+                    if cold[j] or mr > 1e-4:
+                        assert int(Ls[j]) == Lr, (b, k, int(Ls[j]), Lr, mr)
+            # CAP-Decoding, packed over every sequence of the launch, on the block the oracle's trace names
+            row_start, tok_start, blen = [], [], []
+            for i, b in enumerate(group):
+                srec = per_pass[b][k]["select"]
+                row_start.append(row_off[i] + srec["F"] - desc["span"][i]); tok_start.append(b * T + srec["F"]); blen.append(srec["L"])
+            before = tokens.clone()
+            api.select_parallel(out.logits, out.lse, out.conf, out.argmax, tokens, row_start, tok_start, blen, mask, prm["tau_low"],
+                                prm["tau_high"], prm["gamma"], prm.get("mode", 0), sel, nsel, apply_tokens=True, margin_out=mg)
+            torch.cuda.synchronize()
+            for i, b in enumerate(group):
+                srec = per_pass[b][k]["select"]
+                F, L, r0 = srec["F"], srec["L"], row_start[i]
+                elig = before[b, F: F + L].cpu().numpy() == mask
+                assert (elig == srec["eligible"]).all()
+                zb = zs[b][r0 - row_off[i]: r0 - row_off[i] + L]
+                g = {kk: getattr(out, kk)[r0: r0 + L].cpu().numpy() for kk in ("lse", "conf", "argmax")}
+                ref_sel, mr = o_select.select_parallel(zb, g["lse"], g["conf"], g["argmax"], elig, prm["tau_low"], prm["tau_high"], prm["gamma"],
+                                                       prm.get("mode", 0))
+                got_sel = sel[r0: r0 + L].cpu().numpy().astype(bool)
+                assert got_sel.sum() >= 1 and not (got_sel & ~elig).any()
+                if mr > 1e-5:
+                    assert (got_sel == ref_sel).all() and int(nsel[i]) == ref_sel.sum(), (b, k, mr)
+                    after = tokens[b, F: F + L].cpu().numpy()
+                    assert (after == np.where(ref_sel, g["argmax"], before[b, F: F + L].cpu().numpy())).all()  # Eq. 2
+    assert compared == B * iters and mixed_launches >= 1, (compared, mixed_launches)
+    print("passes compared", compared, "launches mixing pass kinds", mixed_launches, "worst relative logit error", worst)
+    state.close()
     model.close()
 
 
