@@ -108,45 +108,71 @@ def micro_vocab_stats(args):
                       "roofline": {"bound": "hbm", "achieved": gbs, "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": gbs / HBM_PEAK_GBS}}))
 
 
-def cpu_baseline(cfg, W_host, prompt, prm, sample_layers):
-    """The oracle, as it stands, on a bounded sample: prefill + the first in-block pass of the same
-    workload through the first `sample_layers` layers and the LM head; the in-block pass time is
-    extrapolated linearly in depth to the full model.  Returns tokens/s of in-block decoding."""
-    from oracle import forward as ofw, select as osel, stats as ost
+def cpu_baseline(cfg, W_host, prompt, prm, sample_layers, n_gen, gpu_pass_counts):
+    """The oracle, as it stands, on a bounded sample of the same workload: the prefill pass, two in-block denoising passes
+    of the first block and the first boundary pass (with their statistics, selection and boundary decision), through the
+    first `sample_layers` layers and the LM head.  Each pass time is scaled linearly in depth to the full model (the LM head,
+    timed alone, is not scaled), and the time of a whole decode is extrapolated as sum over pass kinds of (passes of that
+    kind in the GPU's decode) x (sampled time of that kind).  Returns decoded tokens/s of that extrapolated decode."""
+    from oracle import boundary as obd, forward as ofw, select as osel, stats as ost
     from paper_2604_15750_amd import inputs
     import threadpoolctl
 
     twin = inputs.with_depth(cfg, sample_layers)
     mask, P = cfg["mask_id"], len(prompt)
-    look = min(2 * prm["l_max"], 256)
+    lmax = prm["l_max"]
+    look = min(2 * lmax, n_gen)
     cache = ofw.KVCache(twin)
-    y = np.concatenate([prompt, np.full(look, mask, dtype=np.int64)])
+    y = np.concatenate([prompt, np.full(n_gen, mask, dtype=np.int64)])
+    times = {}
+
+    def select(z, blk_tokens):
+        st = ost.vocab_stats(z, mask)
+        sel, _ = osel.select_parallel(z, st["lse"], st["conf"], st["argmax"], blk_tokens == mask, prm["tau_low"], prm["tau_high"],
+                                      prm["gamma"], prm["mode"])
+        return sel, st["argmax"]
+
     t0 = time.perf_counter()
-    z = ofw.forward_span(twin, W_host, cache, y, 0, P)
-    t_prefill = time.perf_counter() - t0
-    L = prm["l_min"]
-    blk = y[P: P + L].copy()
-    st = ost.vocab_stats(z[P: P + L], mask)
-    sel, _ = osel.select_parallel(z[P: P + L], st["lse"], st["conf"], st["argmax"], blk == mask, prm["tau_low"], prm["tau_high"],
-                                  prm["gamma"], prm["mode"])
-    blk[sel] = st["argmax"][sel]
-    # in-block pass, timed in two parts so that depth can be extrapolated
+    z = ofw.forward_span(twin, W_host, cache, y[: P + look], 0, P)
+    prev_z = z[P:]
+    L = min(prm["l_min"], n_gen)
+    sel, am = select(z[P: P + L], y[P: P + L])
+    y[P: P + L][sel] = am[sel]
+    times["prefill"] = time.perf_counter() - t0
+    t_in = []
+    for _ in range(2):  # two in-block passes (the second one's tokens follow from the first one's selection)
+        t0 = time.perf_counter()
+        zb = ofw.forward_span(twin, W_host, cache, y[P: P + L], P, 0)
+        sel, am = select(zb, y[P: P + L])
+        y[P: P + L][sel] = am[sel]
+        t_in.append(time.perf_counter() - t0)
+    times["inblock"] = sum(t_in) / len(t_in)
+    y[P: P + L] = np.where(y[P: P + L] == mask, 0, y[P: P + L])  # finish the block (any tokens: only the time is sampled)
+    R = n_gen - L
+    Lk, Wn = min(2 * lmax, R), min(lmax, R)
     t0 = time.perf_counter()
-    zb = ofw.forward_span(twin, W_host, cache, blk, P, 0)
-    st = ost.vocab_stats(zb, mask)
-    sel2, _ = osel.select_parallel(zb, st["lse"], st["conf"], st["argmax"], blk == mask, prm["tau_low"], prm["tau_high"], prm["gamma"],
-                                   prm["mode"])
-    t_pass = time.perf_counter() - t0
-    t0 = time.perf_counter()
+    zbd = ofw.forward_span(twin, W_host, cache, y[P: P + L + Lk], P, L)
+    st = ost.vocab_stats(zbd[L: L + Wn], mask, z_prev=prev_z[L: L + Wn])
+    Lnext, _, _ = obd.block_boundary(st["kl"], st["entropy"], prm["lam"], prm["l_min"], prm["smooth_radius"], prm["norm_mode"], prm["rule"])
+    select(zbd[L: L + Lnext], y[P + L: P + L + Lnext])
+    times["boundary"] = time.perf_counter() - t0
     head_only = inputs.with_depth(cfg, 0)
-    ofw.forward_span(head_only, W_host, ofw.KVCache(head_only), blk, 0, 0)
-    t_head = time.perf_counter() - t0
-    t_full = (t_pass - t_head) * cfg["n_layers"] / sample_layers + t_head
+    t_head = {}
+    for kind, rows in (("prefill", P + look), ("inblock", L), ("boundary", L + Lk)):
+        t0 = time.perf_counter()
+        ofw.forward_span(head_only, W_host, ofw.KVCache(head_only), y[:rows], 0, 0)
+        t_head[kind] = time.perf_counter() - t0
+    full = {k: (times[k] - t_head[k]) * cfg["n_layers"] / sample_layers + t_head[k] for k in times}
+    decode_s = sum(gpu_pass_counts[k] * full[k] for k in full)
     threads = max([p.get("num_threads", 1) for p in threadpoolctl.threadpool_info()] or [1])
-    return dict(value=float(sel2.sum()) / t_full, unit="tokens/s", cores=int(threads), kind="oracle",
-                sample=f"prefill ({P}+{look} rows, {t_prefill:.1f} s) then one in-block denoising pass ({L} rows, kv {P}) with statistics "
-                       f"and selection, through {sample_layers} of {cfg['n_layers']} layers + LM head ({t_pass:.2f} s, head {t_head:.2f} s); "
-                       f"layer time scaled to {cfg['n_layers']} layers: {t_full:.2f} s per pass, {int(sel2.sum())} token(s) per pass")
+    sampled_s = sum(times.values()) + times["inblock"] + sum(t_head.values())
+    return dict(value=n_gen / decode_s, unit="tokens/s", cores=int(threads), kind="oracle",
+                sample=f"prefill ({P}+{look} rows, {times['prefill']:.1f} s), two in-block passes ({L} rows, {times['inblock']:.1f} s each) and the first "
+                       f"boundary pass ({L}+{Lk} rows, {times['boundary']:.1f} s) with statistics and decisions, through {sample_layers} of "
+                       f"{cfg['n_layers']} layers + LM head ({sampled_s:.0f} s of host time in all); layer time scaled to {cfg['n_layers']} layers "
+                       f"({full['prefill']:.1f} / {full['inblock']:.1f} / {full['boundary']:.1f} s per pass) and a decode extrapolated as "
+                       f"{gpu_pass_counts['prefill']} prefill + {gpu_pass_counts['inblock']} in-block + {gpu_pass_counts['boundary']} boundary passes "
+                       f"(the GPU decode's pass counts): {decode_s:.0f} s per {n_gen} tokens")
 
 
 def main():
@@ -170,6 +196,8 @@ def main():
                     help="time one kernel alone instead of the decode (peaks: a plain HBM read and a matrix-core loop, what the GPU achieves)")
     ap.add_argument("--rows", type=int, default=3072, help="--micro: rows of the pass (3072 = 16 sequences x 192 rows, the widest batched pass)")
     ap.add_argument("--prev", type=int, default=1, help="--micro vocab_stats: 1 = every row is a KL row (reads the retained logits too)")
+    ap.add_argument("--extras", type=int, default=1, choices=[0, 1],
+                    help="1 (default workload only): also time the scaled-threshold decode and the batched workload on the same model")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="also run out = in + 1 over 1 GiB three times (a kernel of known HBM traffic, to scale rocprofv3's FETCH_SIZE / WRITE_SIZE)")
     args = ap.parse_args()
@@ -244,15 +272,27 @@ def main():
     shapes = gemm_shapes(cfg)
 
     def class_roofline(cls, ms, launches):
+        """Achieved rate of a GEMM class over all its launches of one decode, against the roof that bounds it: each launch
+        is charged max(algorithmic bytes / HBM peak, flops / bf16 matrix-core peak); the class is "hbm" bound when the byte
+        term is the larger share of that floor, else "mfma", and achieved / peak are quoted in that roof's unit."""
         by = fl = 0
+        t_hbm = t_mfma = floor = 0.0
         for rows in rows_hist:
             b_, f_ = gemm_algorithmic(cfg, cls, rows)
-            by += b_ * shapes[cls][2]
-            fl += f_ * shapes[cls][2]
-        gbs = by / (ms * 1e-3) / 1e9
-        return {"bound": "hbm", "achieved": gbs, "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": gbs / HBM_PEAK_GBS,
-                "avg_launch_us": ms * 1e3 / max(launches, 1), "launches": launches, "bytes_per_launch": by / max(launches, 1),
-                "mfma_tflops": fl / (ms * 1e-3) / 1e12}
+            n = shapes[cls][2]
+            by += b_ * n
+            fl += f_ * n
+            tb, tf = b_ / (HBM_PEAK_GBS * 1e9), f_ / (MFMA_BF16_PEAK_TFLOPS * 1e12)
+            t_hbm += n * tb
+            t_mfma += n * tf
+            floor += n * max(tb, tf)
+        gbs, tfl = by / (ms * 1e-3) / 1e9, fl / (ms * 1e-3) / 1e12
+        common = {"avg_launch_us": ms * 1e3 / max(launches, 1), "launches": launches, "bytes_per_launch": by / max(launches, 1),
+                  "flops_per_launch": fl / max(launches, 1), "hbm_GBs": gbs, "mfma_tflops": tfl,
+                  "floor_frac": floor / (ms * 1e-3)}  # sum of the launches' roofline times / measured time
+        if t_hbm >= t_mfma:
+            return dict({"bound": "hbm", "achieved": gbs, "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": gbs / HBM_PEAK_GBS}, **common)
+        return dict({"bound": "mfma", "achieved": tfl, "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s", "frac": tfl / MFMA_BF16_PEAK_TFLOPS}, **common)
 
     roof = class_roofline(DOMINANT, dom_ms, dom_launches)
     roof["kernel"] = "gemm_mid_kernel / gemm_macro_kernel with the SwiGLU epilogue (gate/up GEMM, every launch of one decode)"
@@ -262,8 +302,8 @@ def main():
     probe_buf = torch.empty(2 << 30, dtype=torch.uint8, device=dev)
     achievable = {"hbm_read_GBs": api.probe_hbm_read(probe_buf, reps=10), "mfma_bf16_TFLOPs": api.probe_mfma_bf16(reps=5)}
     del probe_buf
-    roof["achievable_peak"] = achievable["hbm_read_GBs"]
-    roof["frac_of_achievable"] = roof["achieved"] / achievable["hbm_read_GBs"]
+    roof["achievable_peak"] = achievable["hbm_read_GBs"] if roof["bound"] == "hbm" else achievable["mfma_bf16_TFLOPs"]
+    roof["frac_of_achievable"] = roof["achieved"] / roof["achievable_peak"]
     others = {cls: class_roofline(cls, *prof[cls]) for cls in GEMM_CLASSES}
     # attention against the HBM time of its K/V reads (cached prefix + the span's own rows, every layer); vocabulary statistics
     # against one read of the logits (plus the retained logits on KL rows)
@@ -307,8 +347,39 @@ def main():
         for _ in range(3):
             torch.add(src, 1, out=dst)  # an elementwise kernel (CUDAFunctor_add) that reads 1 GiB and writes 1 GiB
         torch.cuda.synchronize()
+    pass_counts = dict(dec.kind_counts)  # of the last decode (every decode of a workload takes the same passes)
+    out["pass_counts"] = pass_counts
+    dec.close()
+    if args.extras and args.workload == "llada8b_p256_g256" and not args.layers:
+        # Beside the headline (paper thresholds: a random-init model commits one token per pass), on the same model: the same
+        # workload with the thresholds scaled into such a model's confidence range (CAP-Decoding then commits several tokens
+        # per pass), and the batched workload (16 sequences, ragged blocks packed per launch: the matrix-core-bound regime).
+        def one(name, B2, P2, N2, lmax2, prm2, steps):
+            d2 = Decoder(model, B2, P2, N2, prm2, dev)
+            pr2 = inputs.make_prompts(cfg, B2, P2)
+            d2.run(pr2)
+            torch.cuda.synchronize()
+            t1 = time.perf_counter()
+            for _ in range(steps):
+                r2 = d2.run(pr2)
+            torch.cuda.synchronize()
+            dt = (time.perf_counter() - t1) / steps
+            fl_ms = sum(pass_floor_us(cfg, rows_l, kv_l) for rows_l, kv_l in d2.pass_log) * 1e-3
+            res2 = {"workload": name, "tokens_per_s": B2 * N2 / dt, "ms_per_decode": dt * 1e3, "nfe": sum(r2["nfe"]) / B2,
+                    "tokens_per_pass": B2 * N2 / sum(r2["nfe"]), "launches_per_decode": r2["launches"], "denoise_step_ms": dt * 1e3 / r2["launches"],
+                    "mean_rows_per_launch": float(np.mean(d2.rows_log)), "decode_floor_frac": fl_ms / (dt * 1e3)}
+            d2.close()
+            return res2
+        scaled = dict(prm, **inputs.SCALED_THRESHOLDS)
+        for k in ("lam", "tau_low", "tau_high", "gamma"):
+            scaled[k] = float(np.float32(scaled[k]))
+        out["scaled_thresholds"] = one("llada8b_p256_g256, thresholds scaled to a random-init model (lambda 0.9, tau 0.04/0.25, gamma -36)",
+                                       B, P, N, lmax, scaled, max(1, min(args.steps, 3)))
+        _, B4, P4, N4, lmax4 = inputs.WORKLOADS["llada8b_b16_p256_g512"]
+        out["batched"] = one("llada8b_b16_p256_g512 (paper thresholds)", B4, P4, N4, lmax4, dict(prm, l_max=lmax4), 1)
+    model.close()
     if not args.no_cpu:
-        out["cpu_baseline"] = cpu_baseline(cfg, W_host, prompts[0], prm, min(args.cpu_layers, cfg["n_layers"]))
+        out["cpu_baseline"] = cpu_baseline(cfg, W_host, prompts[0], prm, min(args.cpu_layers, cfg["n_layers"]), N, pass_counts)
     print(json.dumps(out))
 
 

@@ -66,6 +66,7 @@ class Decoder:
         self.kl_rows = 0    # rows compared with their retained distribution (Eq. 3), all launches together
         self.stat_log = []  # per launch: (rows, rows compared with or retained as a previous-step distribution)
         self.step_events = []  # (rows, start, end) events around every dlm_step launch when time_steps is set
+        self.kind_counts = dict(prefill=0, inblock=0, boundary=0)  # passes of each kind, all sequences together
 
     def _plan(self, b):
         """(span_start, rows, commit, kl_first, kl_count, save_first, save_count) of sequence b's next pass."""
@@ -125,6 +126,7 @@ class Decoder:
         self.stat_log.append((row_off[-1], sum(plans[b][4] + plans[b][6] for b in group)))
         for b in group:
             self.nfe[b] += 1
+            self.kind_counts[self.phase[b]] += 1
         # block-boundary decisions for the sequences that just finished a block (or the prompt)
         bnd = [i for i, b in enumerate(group) if self.phase[b] != "inblock"]
         if bnd and self.fixed:

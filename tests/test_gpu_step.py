@@ -421,3 +421,27 @@ def test_statistics_from_the_lm_head_epilogue(device, L):
         assert (got["argmax"] == st["argmax"]).all() and (got["kl"] == 0).all()
     assert (a["max_logit"] == b["max_logit"]).all()
     model.close()
+
+
+def test_sweep_harness_reports_the_oracles_counts(device):
+    """The hyper-parameter / strategy sweep harness (App. B; the comparison methods of Sec. 5.1) on the tiny fp32 model: the NFE,
+    tokens per pass and number of blocks it reports for each setting are the oracle's whole decode of the same setting."""
+    from paper_2604_15750_amd import sweep
+    cfg = inputs.TINY
+    W = _weights(cfg, 0, device)
+    Wn = inputs.weights_to_numpy(W)
+    model = api.Model(cfg, W)
+    P = 64
+    prompts = inputs.make_prompts(cfg, 1, P)
+    base = dict(inputs.PAPER_PARAMS, l_max=32, lam=0.9, tau_low=0.05, tau_high=0.3, gamma=-14.0)
+    settings = [("DepCap", base, 64), ("DepCap, lambda 1.2", dict(base, lam=1.2), 64), ("confidence threshold, block 16", dict(base, fixed_block=16, mode=1, tau_high=0.2), 64),
+                ("vanilla, block 32", dict(base, fixed_block=32, mode=2), 64), ("DepCap, L_gen 40", base, 40), ("DepCap, gamma -10", dict(base, gamma=-10.0), 64)]
+    seen = set()
+    for name, prm, n_gen in settings:
+        got = sweep.run(model, cfg, 1, P, n_gen, prm, device, prompts)
+        ref = o_decode.decode_full(cfg, Wn, prompts[0], n_gen, _f32(prm))
+        assert got["nfe"] == ref["nfe"] and got["blocks"] == len(ref["blocks"]), (name, got, ref["nfe"], ref["blocks"])
+        assert abs(got["tokens_per_pass"] - n_gen / ref["nfe"]) < 1e-12 and got["tokens_per_s"] > 0
+        seen.add((got["nfe"], got["blocks"]))
+    assert len(seen) >= 4  # the settings really decode differently
+    model.close()
