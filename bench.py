@@ -89,7 +89,10 @@ def micro_vocab_stats(args):
     zs = [mk() for _ in range(nb)]
     ps = [mk() for _ in range(nb)] if with_prev else None
     ws = torch.empty(api.lib().dlm_vocab_stats_workspace(rows), dtype=torch.uint8, device=dev)
-    run = lambda i: api.dlm_vocab_stats(zs[i % nb], V - 1, prev=ps[i % nb] if ps else None, workspace=ws)
+    # KL rows: the retained logits come with their log-sum-exp, as in dlm_step (an earlier pass computed it as that row's lse);
+    # --prev 2 leaves it out and has the kernel recompute it from the retained logits in the same pass
+    pl = [api.dlm_vocab_stats(p, V - 1, workspace=ws)["lse"] for p in ps] if (ps and args.prev == 1) else None
+    run = lambda i: api.dlm_vocab_stats(zs[i % nb], V - 1, prev=ps[i % nb] if ps else None, workspace=ws, prev_lse=pl[i % nb] if pl else None)
     for i in range(args.warmup + 2):
         run(i)
     torch.cuda.synchronize()
@@ -103,7 +106,7 @@ def micro_vocab_stats(args):
     us = a.elapsed_time(b) * 1e3 / iters
     by = rows * V * 2 * (2 if with_prev else 1)
     gbs = by / (us * 1e-6) / 1e9
-    print(json.dumps({"micro": "vocab_stats", "rows": rows, "vocab": V, "kl_rows": with_prev, "launches": iters, "avg_launch_us": us,
+    print(json.dumps({"micro": "vocab_stats", "rows": rows, "vocab": V, "kl_rows": with_prev, "prev_lse": "given" if pl else ("recomputed" if with_prev else None), "launches": iters, "avg_launch_us": us,
                       "bytes_per_launch": by,
                       "roofline": {"bound": "hbm", "achieved": gbs, "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": gbs / HBM_PEAK_GBS}}))
 
@@ -195,7 +198,7 @@ def main():
     ap.add_argument("--micro", default="", choices=["", "vocab_stats", "peaks"],
                     help="time one kernel alone instead of the decode (peaks: a plain HBM read and a matrix-core loop, what the GPU achieves)")
     ap.add_argument("--rows", type=int, default=3072, help="--micro: rows of the pass (3072 = 16 sequences x 192 rows, the widest batched pass)")
-    ap.add_argument("--prev", type=int, default=1, help="--micro vocab_stats: 1 = every row is a KL row (reads the retained logits too)")
+    ap.add_argument("--prev", type=int, default=1, help="--micro vocab_stats: 1 = every row is a KL row (reads the retained logits too; their log-sum-exp is given, as in dlm_step), 2 = the same with that log-sum-exp recomputed in the pass, 0 = no KL rows")
     ap.add_argument("--extras", type=int, default=1, choices=[0, 1],
                     help="1 (default workload only): also time the scaled-threshold decode and the batched workload on the same model")
     ap.add_argument("--copy-calibration", action="store_true",

@@ -201,11 +201,13 @@ int select_parallel(const void* logits, int vocab, int dtype, const float* lse, 
 /* ---- components of dlm_step, exported for isolated tests and measurement --------------------- */
 
 /* The vocabulary reduction of dlm_step on its own.  logits DEVICE [rows, vocab]; prev (nullable)
- * DEVICE [rows, vocab] of the same dtype gives kl per row (else kl = 0).  Same outputs and
+ * DEVICE [rows, vocab] of the same dtype gives kl per row (else kl = 0); prev_lse (nullable) DEVICE
+ * [rows] fp32: the log-sum-exp of each prev row as an earlier call returned it in `lse` (dlm_step
+ * keeps it with the retained logits); NULL: recomputed from prev in the same pass.  Same outputs and
  * definitions as dlm_step.  workspace: DEVICE scratch of at least dlm_vocab_stats_workspace(rows)
  * bytes.  Errors: DLM_EINVAL, DLM_ECAPACITY (rows < 1, workspace too small). */
 size_t dlm_vocab_stats_workspace(int rows);
-int dlm_vocab_stats(const void* logits, const void* prev, int rows, int vocab, int dtype, int mask_id,
+int dlm_vocab_stats(const void* logits, const void* prev, const float* prev_lse, int rows, int vocab, int dtype, int mask_id,
                     float* max_logit, float* lse, float* entropy, float* kl, float* conf,
                     int32_t* argmax, void* workspace, size_t workspace_bytes, void* stream);
 
@@ -216,7 +218,7 @@ int dlm_vocab_stats(const void* logits, const void* prev, int rows, int vocab, i
  * hipFree or other allocating call is made.  Limit: rows <= 4096 (DLM_ECAPACITY beyond; use dlm_vocab_stats there).
  * All calls on one GPU share the array: calls that overlap on one GPU (different streams, different threads) race;
  * calls on one stream are ordered and safe.  Errors: DLM_EINVAL, DLM_ECAPACITY, DLM_EHIP (address resolution failed). */
-int dlm_vocab_stats_static(const void* logits, const void* prev, int rows, int vocab, int dtype, int mask_id,
+int dlm_vocab_stats_static(const void* logits, const void* prev, const float* prev_lse, int rows, int vocab, int dtype, int mask_id,
                            float* max_logit, float* lse, float* entropy, float* kl, float* conf, int32_t* argmax,
                            void* stream);
 

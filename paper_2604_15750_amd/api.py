@@ -83,9 +83,9 @@ def lib():
         L.select_parallel.argtypes = [C.c_void_p, C.c_int, C.c_int, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, _I32P, _I32P, _I32P,
                                       C.c_int, C.c_int, C.POINTER(dlm_select_params), C.c_int, C.c_void_p, C.c_void_p, C.c_void_p,
                                       C.c_void_p]
-        L.dlm_vocab_stats.argtypes = [C.c_void_p, C.c_void_p, C.c_int, C.c_int, C.c_int, C.c_int] + [C.c_void_p] * 7 + \
+        L.dlm_vocab_stats.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_int, C.c_int, C.c_int, C.c_int] + [C.c_void_p] * 7 + \
                                      [C.c_size_t, C.c_void_p]
-        L.dlm_vocab_stats_static.argtypes = [C.c_void_p, C.c_void_p, C.c_int, C.c_int, C.c_int, C.c_int] + [C.c_void_p] * 7
+        L.dlm_vocab_stats_static.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_int, C.c_int, C.c_int, C.c_int] + [C.c_void_p] * 7
         L.dlm_gemm_nt.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_int, C.c_int, C.c_int, C.c_int, C.c_void_p]
         L.dlm_attention.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p] + [C.c_int] * 6 + [C.c_void_p]
         L.dlm_state_fuse_stats.argtypes = [C.c_void_p, C.c_int]
@@ -235,20 +235,20 @@ def select_parallel(logits, lse, conf, argmax, tokens, row_start, tok_start, blo
                                  int(apply_tokens), _ptr(selected_out), _ptr(n_selected_out), _ptr(margin_out), _stream()))
 
 
-def dlm_vocab_stats(logits, mask_id, prev=None, workspace=None):
+def dlm_vocab_stats(logits, mask_id, prev=None, workspace=None, prev_lse=None):
     rows, vocab = logits.shape
     dev = logits.device
     f = lambda: torch.empty(rows, dtype=torch.float32, device=dev)
     out = dict(max_logit=f(), lse=f(), entropy=f(), kl=f(), conf=f(), argmax=torch.empty(rows, dtype=torch.int32, device=dev))
     if workspace is None:
         workspace = torch.empty(lib().dlm_vocab_stats_workspace(rows), dtype=torch.uint8, device=dev)
-    _check(lib().dlm_vocab_stats(_ptr(logits), _ptr(prev), rows, vocab, dtype_code(logits), mask_id, _ptr(out["max_logit"]),
+    _check(lib().dlm_vocab_stats(_ptr(logits), _ptr(prev), _ptr(prev_lse), rows, vocab, dtype_code(logits), mask_id, _ptr(out["max_logit"]),
                                  _ptr(out["lse"]), _ptr(out["entropy"]), _ptr(out["kl"]), _ptr(out["conf"]), _ptr(out["argmax"]),
                                  _ptr(workspace), workspace.numel(), _stream()))
     return out
 
 
-def dlm_vocab_stats_static(logits, mask_id, prev=None, out=None):
+def dlm_vocab_stats_static(logits, mask_id, prev=None, out=None, prev_lse=None):
     """dlm_vocab_stats_static: the partial states live in the library's file-scope scratch.  `out`: a dict of preallocated
     output tensors as dlm_vocab_stats returns (so that the call allocates nothing at all); None: new ones."""
     rows, vocab = logits.shape
@@ -256,7 +256,7 @@ def dlm_vocab_stats_static(logits, mask_id, prev=None, out=None):
     if out is None:
         f = lambda: torch.empty(rows, dtype=torch.float32, device=dev)
         out = dict(max_logit=f(), lse=f(), entropy=f(), kl=f(), conf=f(), argmax=torch.empty(rows, dtype=torch.int32, device=dev))
-    _check(lib().dlm_vocab_stats_static(_ptr(logits), _ptr(prev), rows, vocab, dtype_code(logits), mask_id, _ptr(out["max_logit"]),
+    _check(lib().dlm_vocab_stats_static(_ptr(logits), _ptr(prev), _ptr(prev_lse), rows, vocab, dtype_code(logits), mask_id, _ptr(out["max_logit"]),
                                         _ptr(out["lse"]), _ptr(out["entropy"]), _ptr(out["kl"]), _ptr(out["conf"]), _ptr(out["argmax"]),
                                         _stream()))
     return out

@@ -661,7 +661,7 @@ extern "C" int select_parallel(const void* logits, int vocab, int dtype, const f
 // ---- component entry points ----------------------------------------------------------------------
 extern "C" size_t dlm_vocab_stats_workspace(int rows) { return rows > 0 ? stats_workspace_bytes(rows) : 0; }
 
-extern "C" int dlm_vocab_stats(const void* logits, const void* prev, int rows, int vocab, int dtype, int mask_id, float* max_logit,
+extern "C" int dlm_vocab_stats(const void* logits, const void* prev, const float* prev_lse, int rows, int vocab, int dtype, int mask_id, float* max_logit,
                                float* lse, float* entropy, float* kl, float* conf, int32_t* argmax, void* workspace,
                                size_t workspace_bytes, void* stream) {
   REQUIRE(logits && max_logit && lse && entropy && kl && conf && argmax && workspace, DLM_EINVAL, "dlm_vocab_stats: null argument");
@@ -670,7 +670,7 @@ extern "C" int dlm_vocab_stats(const void* logits, const void* prev, int rows, i
   REQUIRE(workspace_bytes >= stats_workspace_bytes(rows), DLM_ECAPACITY, "dlm_vocab_stats: workspace of %zu bytes < %zu", workspace_bytes,
           stats_workspace_bytes(rows));
   REQUIRE(vocab >= 2 && mask_id >= 0 && mask_id < vocab, DLM_EINVAL, "dlm_vocab_stats: vocab/mask_id");
-  StatsRows sr{nullptr, nullptr, prev, nullptr, nullptr, nullptr};  // prev without a row table: row r pairs with row r
+  StatsRows sr{nullptr, nullptr, prev, nullptr, prev ? prev_lse : nullptr, nullptr};  // prev without a row table: row r pairs with row r
   StatsOut so{max_logit, lse, entropy, kl, conf, argmax};
   hipStream_t st = (hipStream_t)stream;
   if (dtype == DLM_BF16) launch_vocab_stats<bf16_t>((const bf16_t*)logits, rows, vocab, mask_id, sr, so, workspace, st);
@@ -678,7 +678,7 @@ extern "C" int dlm_vocab_stats(const void* logits, const void* prev, int rows, i
   return DLM_OK;
 }
 
-extern "C" int dlm_vocab_stats_static(const void* logits, const void* prev, int rows, int vocab, int dtype, int mask_id, float* max_logit,
+extern "C" int dlm_vocab_stats_static(const void* logits, const void* prev, const float* prev_lse, int rows, int vocab, int dtype, int mask_id, float* max_logit,
                                       float* lse, float* entropy, float* kl, float* conf, int32_t* argmax, void* stream) {
   REQUIRE(logits && max_logit && lse && entropy && kl && conf && argmax, DLM_EINVAL, "dlm_vocab_stats_static: null argument");
   REQUIRE(dtype == DLM_F32 || dtype == DLM_BF16, DLM_EINVAL, "dlm_vocab_stats_static: dtype %d", dtype);
@@ -690,7 +690,7 @@ extern "C" int dlm_vocab_stats_static(const void* logits, const void* prev, int 
   const int rc = scratch_address(&ws);
   if (rc != DLM_OK) return rc;
   // every partial state the merge reads is written by this call's first kernel: nothing has to start at zero
-  StatsRows sr{nullptr, nullptr, prev, nullptr, nullptr, nullptr};
+  StatsRows sr{nullptr, nullptr, prev, nullptr, prev ? prev_lse : nullptr, nullptr};
   StatsOut so{max_logit, lse, entropy, kl, conf, argmax};
   hipStream_t st = (hipStream_t)stream;
   if (dtype == DLM_BF16) launch_vocab_stats<bf16_t>((const bf16_t*)logits, rows, vocab, mask_id, sr, so, ws, st);

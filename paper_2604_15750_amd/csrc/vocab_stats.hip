@@ -9,89 +9,101 @@
 namespace {
 
 constexpr int TPB = 256;
-// the 64 lane states of a wavefront -> one (valid in every lane): all lanes move to the wavefront's maximum first, then the sums are
-// plain butterflies in a fixed order (deterministic), which costs one exp per lane instead of four per butterfly step
-__device__ inline Part part_wave_reduce(const Part& p) {
-  Part r;
-  r.m = wave_max(p.m);
-  const float d = p.m - r.m, a = __expf(d);
-  r.s = wave_sum(a * p.s);
-  r.t = wave_sum(a * (p.t + d * p.s));
-  r.w = wave_sum(a * p.w);
-  r.bv = p.bv;
-  r.bi = p.bi;
-#pragma unroll
-  for (int o = 32; o > 0; o >>= 1) {
-    const float ov = __shfl_xor(r.bv, o, 64);
-    const int oi = __shfl_xor(r.bi, o, 64);
-    if (ov > r.bv || (ov == r.bv && oi < r.bi)) { r.bv = ov; r.bi = oi; }
-  }
-  r.pm = wave_max(p.pm);
-  r.ps = wave_sum(__expf(p.pm - r.pm) * p.ps);
-  return r;
-}
-
 template <typename T> struct Vec;
 template <> struct Vec<bf16_t> { static constexpr int N = 8; typedef bf16x8 type; };
 template <> struct Vec<float> { static constexpr int N = 4; typedef f32x4 type; };
 
 constexpr float LOG2E = 1.4426950408889634f, LN2 = 0.6931471805599453f;
 
-// Running state of one lane while it streams: like Part, but the exponent-weighted sum t2 = sum e^(z-m) (z-m) log2(e) is kept
-// in base-2 units so that an element costs a subtract and a multiply for the exponent, one exp2, one add and one fma (plus two for KL).
+// Running state of a wavefront while it streams its share of a row.  The reference of the exponentials is the maximum of
+// ALL the wavefront's elements so far (m, the same in every lane), not each lane's own: a new maximum then turns up a few
+// times per row instead of in some lane at nearly every step, so the rescaling and the search for the maximum's token id sit
+// in a wavefront-uniform branch that is almost never taken, and the common path is straight-line: per element a subtract and
+// a multiply for the exponent, one exp2, one add and one fma (two more for KL).  The exponent-weighted sum
+// t2 = sum e^(z-m) (z-m) log2(e) is kept in base-2 units.  bi = lowest token id of the maximum (elements are visited in
+// ascending id order within a lane, lanes of one load hold ascending ids, and a later element must be strictly greater).
 struct Run {
-  float m;  // running maximum
-  float s, t2, w;
-  float bv;
-  int bi;
-  float pm, ps;
+  float m;          // uniform: running maximum (= the best logit)
+  int bi;           // uniform: its token id
+  float s, t2, w;   // per lane, relative to m
+  float pm, ps;     // previous-step row when its lse is not stored: uniform maximum, per-lane sum e^(z'-pm)
 };
 constexpr float RUN_MIN = -2.0e38f;  // start of the running maximum: (RUN_MIN - m) * log2(e) stays finite for real maxima m
-__device__ inline Run run_init() { return Run{RUN_MIN, 0.f, 0.f, 0.f, NEG_BIG, 0x7fffffff, NEG_BIG, 0.f}; }
-__device__ inline Part run_finish(const Run& r) { return Part{r.m, r.s, r.t2 * LN2, r.w, r.bv, r.bi, r.pm, r.ps}; }
+__device__ inline Run run_init() { return Run{RUN_MIN, 0x7fffffff, 0.f, 0.f, 0.f, RUN_MIN, 0.f}; }
 
-// absorb N consecutive logits (first token id = v0) into the state; element `skip` (the mask token; -1: none) is left out
-template <int N, bool KL, bool PREV_SUMS, bool SKIP>
-__device__ inline void absorb_impl(Run& p, const float (&z)[N], const float (&zp)[N], int v0, int skip_at) {
-  const int skip = SKIP ? skip_at : -1;  // compile-time "none" on the common path: no per-element tests
-  float vm = RUN_MIN;
+__device__ inline int wave_min_int(int v) {
 #pragma unroll
-  for (int i = 0; i < N; ++i)
-    if (i != skip) vm = fmaxf(vm, z[i]);
-  if (vm > p.m) {  // rare after the first few vectors: rescale the sums to the new maximum
-    const float d2 = (p.m - vm) * LOG2E, a = __builtin_amdgcn_exp2f(d2);
-    p.t2 = a * fmaf(d2, p.s, p.t2);
-    p.s *= a;
-    p.w *= a;
-    p.m = vm;
-#pragma unroll
-    for (int i = 0; i < N; ++i)
-      if (i != skip && z[i] > p.bv) { p.bv = z[i]; p.bi = v0 + i; }   // ascending ids + strict '>' keep the lowest id
-  }
-#pragma unroll
-  for (int i = 0; i < N; ++i) {
-    if (i == skip) continue;
-    const float d2 = (z[i] - p.m) * LOG2E, e = __builtin_amdgcn_exp2f(d2);  // the difference first: exact for nearby values
-    p.s += e;
-    p.t2 = fmaf(e, d2, p.t2);
-    if (KL) p.w = fmaf(e, z[i] - zp[i], p.w);
-  }
-  if (KL && PREV_SUMS) {
-    float pv = NEG_BIG;
-#pragma unroll
-    for (int i = 0; i < N; ++i)
-      if (i != skip) pv = fmaxf(pv, zp[i]);
-    if (pv > p.pm) { p.ps *= __expf(p.pm - pv); p.pm = pv; }
-#pragma unroll
-    for (int i = 0; i < N; ++i)
-      if (i != skip) p.ps += __expf(zp[i] - p.pm);
-  }
+  for (int o = 32; o > 0; o >>= 1) v = min(v, __shfl_xor(v, o, 64));
+  return v;
 }
 
-template <int N, bool KL, bool PREV_SUMS>
-__device__ inline void absorb(Run& p, const float (&z)[N], const float (&zp)[N], int v0, int skip = -1) {
-  if (skip < 0) absorb_impl<N, KL, PREV_SUMS, false>(p, z, zp, v0, -1);
-  else absorb_impl<N, KL, PREV_SUMS, true>(p, z, zp, v0, skip);
+// The 64 lane states -> the wavefront's Part (valid in every lane): the lanes share m, so the sums are plain butterflies in a
+// fixed order (deterministic).
+__device__ inline Part run_finish(const Run& r) {
+  Part p;
+  p.m = r.m;
+  p.s = wave_sum(r.s);
+  p.t = wave_sum(r.t2) * LN2;
+  p.w = wave_sum(r.w);
+  p.bv = r.m;
+  p.bi = r.bi;
+  p.pm = r.pm > RUN_MIN ? r.pm : NEG_BIG;
+  p.ps = wave_sum(r.ps);
+  return p;
+}
+
+// A new maximum somewhere in the wavefront (vm = each lane's maximum of its N elements, RUN_MIN if it has none): move the
+// reference.  Called by all 64 lanes together, from a wavefront-uniform branch.
+template <int N>
+__device__ inline void new_maximum(Run& p, const float (&z)[N], unsigned valid, float vm, int v0) {
+  const float wmax = wave_max(vm);
+  int cand = 0x7fffffff;
+#pragma unroll
+  for (int i = N - 1; i >= 0; --i)
+    if (((valid >> i) & 1u) && z[i] == wmax) cand = v0 + i;
+  const float d2 = (p.m - wmax) * LOG2E, a = __builtin_amdgcn_exp2f(d2);
+  p.t2 = a * fmaf(d2, p.s, p.t2);
+  p.s *= a;
+  p.w *= a;
+  p.m = wmax;
+  p.bi = wave_min_int(cand);
+}
+template <int N>
+__device__ inline void new_prev_maximum(Run& p, float vm) {
+  const float wmax = wave_max(vm);
+  p.ps *= __builtin_amdgcn_exp2f((p.pm - wmax) * LOG2E);
+  p.pm = wmax;
+}
+
+// Absorb N consecutive logits (first token id v0) of every lane; bit i of `valid` says that element i takes part (the mask
+// token and elements past the end do not).  ALL: every element of every lane is valid (the common path: no selects).
+// Called by all 64 lanes of a wavefront together.
+template <int N, bool KL, bool PREV_SUMS, bool ALL>
+__device__ inline void absorb(Run& p, const float (&z)[N], const float (&zp)[N], int v0, unsigned valid) {
+  float vm = RUN_MIN;
+#pragma unroll
+  for (int i = 0; i < N; ++i) vm = fmaxf(vm, (ALL || ((valid >> i) & 1u)) ? z[i] : RUN_MIN);
+  if (__builtin_amdgcn_ballot_w64(vm > p.m) != 0) new_maximum<N>(p, z, ALL ? 0xffffffffu : valid, vm, v0);
+#pragma unroll
+  for (int i = 0; i < N; ++i) {
+    const float d2 = (z[i] - p.m) * LOG2E;  // the difference first: exact for nearby values
+    float e = __builtin_amdgcn_exp2f(d2);
+    if (!ALL) e = ((valid >> i) & 1u) ? e : 0.f;
+    p.s += e;
+    p.t2 = fmaf(e, ALL ? d2 : (((valid >> i) & 1u) ? d2 : 0.f), p.t2);
+    if (KL) p.w = fmaf(e, ALL ? z[i] - zp[i] : (((valid >> i) & 1u) ? z[i] - zp[i] : 0.f), p.w);
+  }
+  if (KL && PREV_SUMS) {
+    float pv = RUN_MIN;
+#pragma unroll
+    for (int i = 0; i < N; ++i) pv = fmaxf(pv, (ALL || ((valid >> i) & 1u)) ? zp[i] : RUN_MIN);
+    if (__builtin_amdgcn_ballot_w64(pv > p.pm) != 0) new_prev_maximum<N>(p, pv);
+#pragma unroll
+    for (int i = 0; i < N; ++i) {
+      const float e = __builtin_amdgcn_exp2f((zp[i] - p.pm) * LOG2E);
+      p.ps += (ALL || ((valid >> i) & 1u)) ? e : 0.f;
+    }
+  }
 }
 
 __device__ inline void finalize(const Part& p, int row, bool has_prev, float prev_lse, const StatsOut& o, float* save_lse_slot) {
@@ -106,44 +118,63 @@ __device__ inline void finalize(const Part& p, int row, bool has_prev, float pre
   if (save_lse_slot) *save_lse_slot = lse;
 }
 
-// Work item (row, c): elements [c*chunk, (c+1)*chunk) of one row; a workgroup takes every gridDim.x-th item.
-// one lane's share of elements [lo, hi) of a row: U vectors (16 bytes each) in flight, then absorbed one after the other
+// One wavefront's share of elements [lo, hi) of a row (the workgroup walks them together: lane l of the workgroup takes the
+// l-th vector of every stride).  Whole trips of U vectors (16 bytes each) per lane are loaded together and absorbed one after
+// the other without a bounds or mask test; the trip that holds the mask token and the ragged last one take the path with
+// per-element validity.  Loop bounds are uniform in the workgroup: the absorb steps exchange values between lanes.
 template <typename T, bool VECTOR, bool KL, bool PREV_SUMS>
 __device__ inline void stream_chunk(Run& run, const T* __restrict__ z_row, const T* __restrict__ p_row, T* __restrict__ s_row, int lo,
                                     int hi, int mask_id) {
   constexpr int N = Vec<T>::N;
   typedef typename Vec<T>::type V;
   if (VECTOR) {
-    constexpr int U = 4;
-    for (int v0 = lo + threadIdx.x * N; v0 < hi; v0 += TPB * N * U) {
+    constexpr int U = 4, STRIDE = TPB * N, TRIP = U * STRIDE;
+    const int base = lo + threadIdx.x * N;
+    const int nfull = (hi - lo) / TRIP;
+    for (int t = 0; t * TRIP < hi - lo; ++t) {
+      const int t0 = lo + t * TRIP;  // first element of the trip (uniform)
+      const bool plain = t < nfull && !(mask_id >= t0 && mask_id < t0 + TRIP);
       V zv[U], pv[U];
+      if (plain) {
 #pragma unroll
-      for (int u = 0; u < U; ++u) {
-        const int v = v0 + u * TPB * N;
-        if (v < hi) {
-          zv[u] = *(const V*)(z_row + v);
-          if (KL) pv[u] = *(const V*)(p_row + v);
+        for (int u = 0; u < U; ++u) {
+          zv[u] = *(const V*)(z_row + base + t * TRIP + u * STRIDE);
+          if (KL) pv[u] = *(const V*)(p_row + base + t * TRIP + u * STRIDE);
         }
-      }
 #pragma unroll
-      for (int u = 0; u < U; ++u) {
-        const int v = v0 + u * TPB * N;
-        if (v >= hi) break;
-        float z[N], zp[N];
+        for (int u = 0; u < U; ++u) {
+          const int v = base + t * TRIP + u * STRIDE;
+          float z[N], zp[N];
 #pragma unroll
-        for (int i = 0; i < N; ++i) { z[i] = to_f32(zv[u][i]); zp[i] = KL ? to_f32(pv[u][i]) : 0.f; }
-        if (s_row) *(V*)(s_row + v) = zv[u];
-        const int skip = (mask_id >= v && mask_id < v + N) ? mask_id - v : -1;  // the mask token takes no part
-        absorb<N, KL, PREV_SUMS>(run, z, zp, v, skip);
+          for (int i = 0; i < N; ++i) { z[i] = to_f32(zv[u][i]); zp[i] = KL ? to_f32(pv[u][i]) : 0.f; }
+          if (s_row) *(V*)(s_row + v) = zv[u];
+          absorb<N, KL, PREV_SUMS, true>(run, z, zp, v, 0xffffffffu);
+        }
+      } else {
+#pragma unroll 1
+        for (int u = 0; u < U; ++u) {
+          const int v = base + t * TRIP + u * STRIDE;
+          if (t0 + u * STRIDE >= hi) break;  // uniform
+          const bool in = v < hi;            // vocab % N == 0 and lo % N == 0: a vector is inside or outside as a whole
+          float z[N], zp[N];
+          V a, b;
+          if (in) { a = *(const V*)(z_row + v); if (KL) b = *(const V*)(p_row + v); }
+#pragma unroll
+          for (int i = 0; i < N; ++i) { z[i] = in ? to_f32(a[i]) : 0.f; zp[i] = (KL && in) ? to_f32(b[i]) : 0.f; }
+          if (s_row && in) *(V*)(s_row + v) = a;
+          unsigned valid = in ? (1u << N) - 1u : 0u;
+          if (mask_id >= v && mask_id < v + N) valid &= ~(1u << (mask_id - v));  // the mask token takes no part
+          absorb<N, KL, PREV_SUMS, false>(run, z, zp, v, valid);
+        }
       }
     }
   } else {
-    for (int v = lo + threadIdx.x; v < hi; v += TPB) {
-      float z[1] = {to_f32(z_row[v])}, zp[1] = {0.f};
-      if (s_row) s_row[v] = z_row[v];
-      if (KL) zp[0] = to_f32(p_row[v]);
-      if (v == mask_id) continue;  // the mask token takes no part
-      absorb<1, KL, PREV_SUMS>(run, z, zp, v);
+    for (int v0 = lo; v0 < hi; v0 += TPB) {  // uniform bounds; a lane past the end or on the mask token feeds an invalid element
+      const int v = v0 + threadIdx.x;
+      const bool in = v < hi;
+      float z[1] = {in ? to_f32(z_row[v]) : 0.f}, zp[1] = {(KL && in) ? to_f32(p_row[v]) : 0.f};
+      if (s_row && in) s_row[v] = z_row[v];
+      absorb<1, KL, PREV_SUMS, false>(run, z, zp, v, (in && v != mask_id) ? 1u : 0u);
     }
   }
 }
@@ -169,8 +200,7 @@ __global__ __launch_bounds__(TPB) void vocab_stats_kernel(const T* __restrict__ 
   if (!kl) stream_chunk<T, VECTOR, false, false>(run, z_row, p_row, s_row, lo, hi, mask_id);
   else if (!prev_sums) stream_chunk<T, VECTOR, true, false>(run, z_row, p_row, s_row, lo, hi, mask_id);
   else stream_chunk<T, VECTOR, true, true>(run, z_row, p_row, s_row, lo, hi, mask_id);
-  Part p = run_finish(run);
-  p = part_wave_reduce(p);
+  const Part p = run_finish(run);
   if ((threadIdx.x & 63) == 0) sh[threadIdx.x >> 6] = p;
   __syncthreads();
   if (threadIdx.x == 0) {

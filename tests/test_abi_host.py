@@ -91,15 +91,15 @@ def test_model_and_component_argument_errors():
     assert L.dlm_state_create(None, 1, 1, 1, 1, C.byref(h)) == -1
     assert L.dlm_step(None, None, None) == -1
     assert L.dlm_state_reset(None, 0) == -1 and L.dlm_state_kv_len(None, 0) == -1
-    assert L.dlm_vocab_stats(None, None, 1, 8, 0, 7, one, one, one, one, one, one, one, 1 << 20, None) == -1
-    assert L.dlm_vocab_stats(one, None, 0, 8, 0, 7, one, one, one, one, one, one, one, 1 << 20, None) == -3
-    assert L.dlm_vocab_stats(one, None, 4, 8, 0, 7, one, one, one, one, one, one, one, 8, None) == -3 and "workspace" in _err()
-    assert L.dlm_vocab_stats(one, None, 4, 8, 0, 8, one, one, one, one, one, one, one, 1 << 20, None) == -1
+    assert L.dlm_vocab_stats(None, None, None, 1, 8, 0, 7, one, one, one, one, one, one, one, 1 << 20, None) == -1
+    assert L.dlm_vocab_stats(one, None, None, 0, 8, 0, 7, one, one, one, one, one, one, one, 1 << 20, None) == -3
+    assert L.dlm_vocab_stats(one, None, None, 4, 8, 0, 7, one, one, one, one, one, one, one, 8, None) == -3 and "workspace" in _err()
+    assert L.dlm_vocab_stats(one, None, None, 4, 8, 0, 8, one, one, one, one, one, one, one, 1 << 20, None) == -1
     # the entry point that allocates nothing: same checks, and a row limit set by its file-scope scratch
-    assert L.dlm_vocab_stats_static(None, None, 1, 8, 0, 7, one, one, one, one, one, one, None) == -1
-    assert L.dlm_vocab_stats_static(one, None, 0, 8, 0, 7, one, one, one, one, one, one, None) == -3
-    assert L.dlm_vocab_stats_static(one, None, 4097, 8, 0, 7, one, one, one, one, one, one, None) == -3 and "4096" in _err()
-    assert L.dlm_vocab_stats_static(one, None, 4, 8, 0, 8, one, one, one, one, one, one, None) == -1
+    assert L.dlm_vocab_stats_static(None, None, None, 1, 8, 0, 7, one, one, one, one, one, one, None) == -1
+    assert L.dlm_vocab_stats_static(one, None, None, 0, 8, 0, 7, one, one, one, one, one, one, None) == -3
+    assert L.dlm_vocab_stats_static(one, None, None, 4097, 8, 0, 7, one, one, one, one, one, one, None) == -3 and "4096" in _err()
+    assert L.dlm_vocab_stats_static(one, None, None, 4, 8, 0, 8, one, one, one, one, one, one, None) == -1
     assert L.dlm_gemm_nt(one, one, one, 4, 48, 64, 1, None) == -2
     assert L.dlm_gemm_nt(one, None, one, 4, 64, 64, 1, None) == -1
     assert L.dlm_attention(one, one, one, one, 4, 4, 4, 3, 32, 0, None) == -2

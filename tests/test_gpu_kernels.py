@@ -125,6 +125,11 @@ def test_vocab_stats(device, dt, rows, V, mask_id, with_prev):
     _check_stats(got, ref, z64, zp64, mask_id)
     if with_prev and rows > 1:
         assert abs(got["kl"][1].item()) <= 1e-6
+    if with_prev:  # the previous rows' log-sum-exp handed in (what dlm_step keeps with the retained logits) instead of recomputed
+        lse_prev = api.dlm_vocab_stats(zp.to(device), mask_id)["lse"]
+        got2 = api.dlm_vocab_stats(z.to(device), mask_id, zp.to(device), prev_lse=lse_prev)
+        torch.cuda.synchronize()
+        _check_stats(got2, ref, z64, zp64, mask_id)
 
 
 # ---- block_boundary ----------------------------------------------------------------------------------

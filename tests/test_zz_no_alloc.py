@@ -22,8 +22,9 @@ def test_static_scratch_matches_workspace_entry_point(device, dtype):
         z = (torch.randn(rows, V, generator=g) * 4).to(dtype).to(device)
         p = (z.float() + 0.3 * torch.randn(rows, V, generator=g).to(device)).to(dtype)
         outs = {k: torch.full((rows,), -7, dtype=torch.int32 if k == "argmax" else torch.float32, device=device) for k in KEYS}
-        got = api.dlm_vocab_stats_static(z, mask, prev=p, out=outs)
-        ref = api.dlm_vocab_stats(z, mask, prev=p)
+        lse_p = api.dlm_vocab_stats(p, mask)["lse"] if rows == 7 else None  # the second call also takes the previous rows' lse
+        got = api.dlm_vocab_stats_static(z, mask, prev=p, out=outs, prev_lse=lse_p)
+        ref = api.dlm_vocab_stats(z, mask, prev=p, prev_lse=lse_p)
         torch.cuda.synchronize()
         for k in KEYS:
             assert torch.equal(got[k], ref[k]), (rows, k)
