@@ -2,10 +2,11 @@
 // fp32 accumulation, epilogue fused.
 //
 // Beyond a few hundred rows the GEMMs leave the weight-streaming regime and are bound by the matrix
-// cores and by how often operands are re-read.  A workgroup of four wavefronts (2 x 2) owns a tile of
-// 32 WM rows x 32 WN columns (192 x 256, 128 x 256 or 128 x 128; the kernel is written for any WM, WN,
-// but with 256 x 256 the compiler no longer keeps 256 accumulators and two operand sets in registers
-// without spilling inside the loop) and walks K one k-tile (32) at a time:
+// cores and by how often operands are re-read.  A workgroup of NW wavefronts (NW / 2 x 2) owns a tile of
+// 8 NW WM rows x 32 WN columns: 256 x 256 with eight wavefronts (two per SIMD, 128 accumulator registers
+// each: what a compute unit fetches per product is half of what a 128 x 256 tile needs, and that fetch rate,
+// L2 / memory-side cache -> LDS, is what bounds the smaller tiles), or 192 x 256, 128 x 256, 128 x 128 with
+// four wavefronts where the larger tile would leave compute units idle; it walks K one k-tile (32) at a time:
 //   * both operands are already stored as 1 KiB matrix-core fragments (16 rows x 32 k), so a stage of
 //     the pipeline is just 2 WM + 2 WN fragments copied HBM/L2 -> LDS by direct-to-LDS loads (no
 //     registers, no LDS writes): 4 to 8 stages of 16 .. 28 KiB rotate through up to 128 KiB of LDS;
@@ -24,7 +25,6 @@
 
 namespace {
 
-constexpr int TPB = 256;
 
 typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
 constexpr int SC1 = 16;  // cache-policy bit of the raw-buffer builtins: device scope
@@ -36,24 +36,25 @@ __device__ inline __amdgpu_buffer_rsrc_t part_rsrc(const float* base) {
 #define LDS_PTR(p) ((void __attribute__((address_space(3)))*)(p))
 
 // XP: planes of X (the EPI_RESID GEMMs read a pair per fragment tile)
-template <int WM, int WN, int XP = 1>
+template <int WM, int WN, int XP = 1, int NW = 4>
 struct MacroShape {
-  static constexpr int AT = 2 * WM;                // row tiles of the workgroup
+  static constexpr int TPB = NW * 64;
+  static constexpr int AT = (NW / 2) * WM;         // row tiles of the workgroup
   static constexpr int AF = AT * XP, BF = 2 * WN;  // X (row tiles x planes) and W (column) fragments of a stage
   static constexpr int NFR = AF + BF;
-  static constexpr int LPS = NFR / 4;              // direct-to-LDS loads per wavefront and stage
+  static constexpr int LPS = (NFR + NW - 1) / NW;  // direct-to-LDS loads per wavefront and stage (surplus ones repeat the last fragment)
   static constexpr int STAGE = NFR * 1024;
-  static constexpr int S = 131072 / STAGE > 8 ? 8 : 131072 / STAGE;  // stages: at most 128 KiB
+  static constexpr int S = 131072 / STAGE > 8 ? 8 : 131072 / STAGE;  // stages: at most 128 KiB (of the 160 KiB of a compute unit)
   static constexpr int LDS_BYTES = S * STAGE + AT * 16 * 4 * 3;      // + 1/rms of the rows, two partial sums of squares per row
 };
 
-template <int WM, int WN, int PR, int EPI>
-__global__ __launch_bounds__(TPB) void gemm_macro_kernel(const bf16x8* __restrict__ xt, const bf16x8* __restrict__ wt, int M, int N, int K,
-                                                         int nblocks, int mblocks, int splits, int kt_per_split, GemmEpi e) {
+template <int WM, int WN, int PR, int EPI, int NW = 4>
+__global__ __launch_bounds__(NW * 64) void gemm_macro_kernel(const bf16x8* __restrict__ xt, const bf16x8* __restrict__ wt, int M, int N, int K,
+                                                             int nblocks, int mblocks, int splits, int kt_per_split, GemmEpi e) {
   constexpr int XP = XPlanes<EPI>::value;
-  typedef MacroShape<WM, WN, XP> SH;
-  constexpr int AT = SH::AT, AF = SH::AF, BF = SH::BF, LPS = SH::LPS, STAGE = SH::STAGE, S = SH::S;
-  static_assert(AF % 4 == 0 && BF % 4 == 0 && S >= 4 && (S - 2) * LPS < 64, "pipeline shape");
+  typedef MacroShape<WM, WN, XP, NW> SH;
+  constexpr int TPB = SH::TPB, AT = SH::AT, AF = SH::AF, BF = SH::BF, LPS = SH::LPS, STAGE = SH::STAGE, S = SH::S;
+  static_assert(AF % NW == 0 && S >= 4 && (S - 2) * LPS < 64, "pipeline shape");
   extern __shared__ __align__(16) unsigned char lds[];
   float* s_rinv = (float*)(lds + S * STAGE);  // [AT * 16]
   float* s_ssq = s_rinv + AT * 16;            // [2][AT * 16]
@@ -73,21 +74,24 @@ __global__ __launch_bounds__(TPB) void gemm_macro_kernel(const bf16x8* __restric
   const int mt0 = rb * AT, nt0 = cb * BF;
 
   // stage kt % S <- k-tile kt: fragment f (f < AF: plane f % XP of X row tile mt0 + f / XP, else W column tile nt0 + f - AF) is
-  // moved by wavefront f % 4
+  // moved by wavefront f % NW
   const int kb = split * kt_per_split, nk = min(KT, kb + kt_per_split) - kb;  // this workgroup's k-tiles: kb .. kb + nk - 1
   auto issue = [&](int kt) {
     const int t = kb + min(kt, nk - 1);
     unsigned char* base = lds + (kt % S) * STAGE;
 #pragma unroll
     for (int i = 0; i < LPS; ++i) {
-      const int f = i * 4 + wave;
+      const int f = i * NW + wave;
       const bf16x8* src;
-      if (i < AF / 4) {
+      if (i < AF / NW) {
         const int mt = min(mt0 + f / XP, MTILES - 1);
         src = xt + (((size_t)mt * KT + t) * XP + f % XP) * 64 + lane;
       } else {
-        const int nt = min(nt0 + f - AF, NT - 1);
+        const int fw = min(f - AF, BF - 1);  // a wavefront without a fragment of its own in the last round moves the last one again
+        const int nt = min(nt0 + fw, NT - 1);
         src = PR == 2 ? wt + (((size_t)(nt >> 1) * KT + t) * 2 + (nt & 1)) * 64 + lane : wt + ((size_t)nt * KT + t) * 64 + lane;
+        __builtin_amdgcn_global_load_lds(GLOBAL_PTR(src), LDS_PTR(base + (AF + fw) * 1024), 16, 0, 0);
+        continue;
       }
       __builtin_amdgcn_global_load_lds(GLOBAL_PTR(src), LDS_PTR(base + f * 1024), 16, 0, 0);
     }
@@ -220,25 +224,33 @@ __global__ __launch_bounds__(TPB) void gemm_macro_kernel(const bf16x8* __restric
 }
 
 struct MacroPlan {
-  int wm, wn, nblocks, mblocks, splits, kps;
+  int wm, wn, nw, nblocks, mblocks, splits, kps;
 };
 
-// the tile with the least estimated time: rounds of workgroups over the chip x products per workgroup, the smaller tiles
-// charged for their heavier LDS traffic
+// the tile with the least estimated time: rounds of workgroups over the chip x products per workgroup, each tile charged
+// for what it fetches per product (measured: see penalty)
 int g_macro_wgs = 256;  // workgroups a K split aims at
+constexpr int NCAND = 5;
+// time of a round of workgroups over the chip / tile area, relative to 128 x 256 with four wavefronts (measured on the layer
+// matrices of an 8B model; the second row: X as a pair of planes)
+double g_macro_penalty[NCAND] = {0.76, 1.0, 1.25, 0.92, 0.83};
+double g_macro_penalty_pair[3] = {0.84, 1.0, 1.12};
 
 MacroPlan macro_plan(int M, int N, int K, bool may_split, int kind) {
-  const int cand[3][2] = {{4, 8}, {4, 4}, {6, 8}};
-  const double penalty[3] = {1.0, 1.25, 0.9};
-  MacroPlan best{4, 8, 1, 1};
+  // {WM, WN, wavefronts}: 256 x 256, 128 x 256, 128 x 128, 192 x 256, 256 x 192; when X is a pair of planes (EPI_RESID) the eight
+  // wavefronts take 128 x 256 (two row tiles each, both planes: the same fetch per product as 256 x 256 of single planes) and
+  // the 192-row tile is left out (its stages no longer fit LDS four deep)
+  const bool pair = kind == EPI_RESID;
+  const int cand[NCAND][3] = {{pair ? 2 : 4, 8, 8}, {4, 8, 4}, {4, 4, 4}, {6, 8, 4}, {4, 6, 8}};
+  MacroPlan best{4, 8, 4, 1, 1, 1, 0};
   double best_cost = 1e300;
-  const int ncand = kind == EPI_RESID ? 2 : 3;  // X as a pair of planes: a 192-row tile's stages no longer fit LDS four deep
+  const int ncand = pair ? 3 : NCAND;
   for (int c = 0; c < ncand; ++c) {
-    const int bm = 32 * cand[c][0], bn = 32 * cand[c][1];
+    const int bm = 8 * cand[c][2] * cand[c][0], bn = 32 * cand[c][1];
     const int mb = (M + bm - 1) / bm, nb = (N + bn - 1) / bn;
     const int rounds = (mb * nb + 255) / 256;
-    const double cost = (double)rounds * bm * bn * penalty[c];
-    if (cost < best_cost) { best_cost = cost; best = MacroPlan{cand[c][0], cand[c][1], nb, mb, 1, 0}; }
+    const double cost = (double)rounds * bm * bn * (pair ? g_macro_penalty_pair[c] : g_macro_penalty[c]);
+    if (cost < best_cost) { best_cost = cost; best = MacroPlan{cand[c][0], cand[c][1], cand[c][2], nb, mb, 1, 0}; }
   }
   // tiles that cover at most half of the chip (narrow matrices at a few hundred rows): split K until they cover it
   const int KT = K >> 5, wgs = best.nblocks * best.mblocks;
@@ -251,24 +263,27 @@ MacroPlan macro_plan(int M, int N, int K, bool may_split, int kind) {
   return best;
 }
 
-template <int WM, int WN, int PR, int EPI>
+template <int WM, int WN, int NW, int PR, int EPI>
 void launch_one(const bf16_t* xt, const bf16_t* wt, int M, int N, int K, const MacroPlan& p, const GemmEpi& e, hipStream_t st) {
-  typedef MacroShape<WM, WN, XPlanes<EPI>::value> SH;
+  typedef MacroShape<WM, WN, XPlanes<EPI>::value, NW> SH;
   static bool configured = false;  // raise the dynamic LDS limit of this instantiation once
   if (!configured) {
-    (void)hipFuncSetAttribute((const void*)gemm_macro_kernel<WM, WN, PR, EPI>, hipFuncAttributeMaxDynamicSharedMemorySize, SH::LDS_BYTES);
+    (void)hipFuncSetAttribute((const void*)gemm_macro_kernel<WM, WN, PR, EPI, NW>, hipFuncAttributeMaxDynamicSharedMemorySize, SH::LDS_BYTES);
     configured = true;
   }
   const int grid = (p.nblocks + 7) / 8 * 8 * p.mblocks * p.splits;
-  DLM_LAUNCH((gemm_macro_kernel<WM, WN, PR, EPI>), grid, TPB, SH::LDS_BYTES, st, (const bf16x8*)xt, (const bf16x8*)wt, M, N, K, p.nblocks, p.mblocks,
-             p.splits, p.kps, e);
+  DLM_LAUNCH((gemm_macro_kernel<WM, WN, PR, EPI, NW>), grid, SH::TPB, SH::LDS_BYTES, st, (const bf16x8*)xt, (const bf16x8*)wt, M, N, K, p.nblocks,
+             p.mblocks, p.splits, p.kps, e);
 }
 
 template <int PR, int EPI>
 void launch_shape(const bf16_t* xt, const bf16_t* wt, int M, int N, int K, const MacroPlan& p, const GemmEpi& e, hipStream_t st) {
-  if (p.wm == 6) { if constexpr (EPI != EPI_RESID) launch_one<6, 8, PR, EPI>(xt, wt, M, N, K, p, e, st); }
-  else if (p.wn == 8) launch_one<4, 8, PR, EPI>(xt, wt, M, N, K, p, e, st);
-  else launch_one<4, 4, PR, EPI>(xt, wt, M, N, K, p, e, st);
+  constexpr bool pair = EPI == EPI_RESID;
+  if (p.nw == 8 && p.wn == 6) { if constexpr (!pair) launch_one<4, 6, 8, PR, EPI>(xt, wt, M, N, K, p, e, st); }
+  else if (p.nw == 8) launch_one<(pair ? 2 : 4), 8, 8, PR, EPI>(xt, wt, M, N, K, p, e, st);
+  else if (p.wm == 6) { if constexpr (!pair) launch_one<6, 8, 4, PR, EPI>(xt, wt, M, N, K, p, e, st); }
+  else if (p.wn == 8) launch_one<4, 8, 4, PR, EPI>(xt, wt, M, N, K, p, e, st);
+  else launch_one<4, 4, 4, PR, EPI>(xt, wt, M, N, K, p, e, st);
 }
 
 template <int EPI>
@@ -283,6 +298,10 @@ int gemm_macro_ssq_chunks(int M, int N) { return macro_plan(M, N, 32, false, EPI
 int gemm_macro_splits(int M, int N, int K, int kind) { return macro_plan(M, N, K, true, kind).splits; }
 int gemm_macro_counters(int max_rows, int max_n) { return ((max_n + 127) / 128) * ((max_rows + 127) / 128); }  // 128 x 128 tiles are the smallest
 void gemm_macro_set_target(int wgs) { g_macro_wgs = wgs; }
+void gemm_macro_set_penalty(int tile, double p) {
+  if (tile >= 0 && tile < NCAND) g_macro_penalty[tile] = p;
+  if (tile >= 0 && tile < 3) g_macro_penalty_pair[tile] = p;
+}
 
 void launch_gemm_macro(const bf16_t* xt, const bf16_t* wt, int M, int N, int K, const GemmEpi& e, hipStream_t st) {
   const MacroPlan p = macro_plan(M, N, K, e.kind != EPI_DIRECT, e.kind);  // EPI_DIRECT has no workspace
