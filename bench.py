@@ -111,6 +111,58 @@ def micro_vocab_stats(args):
                       "roofline": {"bound": "hbm", "achieved": gbs, "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": gbs / HBM_PEAK_GBS}}))
 
 
+def micro_wide_pass(args):
+    """The matrix-core-bound regime on its own: one pass of dlm_step over 16 packed sequences of rows / 16 rows each (no cached
+    prefix: the shape of the batched workload's widest launches) through the full model, repeated; every GEMM class timed by
+    the start / end stamps of its own launches (dlm_profile_*).  Reports each class against max(bytes / HBM peak, flops / bf16
+    matrix-core peak).  Prints one JSON line."""
+    import torch
+    from paper_2604_15750_amd import api, inputs
+
+    dev = torch.device("cuda:0")
+    cfg = inputs.WORKLOADS[args.workload][0]
+    rows, nseq = args.rows, 16
+    per = rows // nseq
+    assert per * nseq == rows and per >= 1, "--rows must be a multiple of 16"
+    W = inputs.make_weights(cfg, seed=0, device=dev)
+    model = api.Model(cfg, W)
+    del W
+    torch.cuda.empty_cache()
+    state = api.State(model, nseq, per, rows, 0)
+    out = api.StepOutputs(rows, cfg["vocab"], model.torch_dtype, dev)
+    tokens = torch.from_numpy(inputs.make_prompts(cfg, nseq, per).astype(np.int32)).to(dev)
+    off = [b * per for b in range(nseq + 1)]
+    reps = max(args.steps, 1) * 2
+
+    def one():
+        for b in range(nseq):
+            state.reset(b)
+        api.dlm_step(state, tokens, out, off, [0] * nseq, [0] * nseq, [b * per for b in range(nseq)], slot=list(range(nseq)))
+
+    for _ in range(max(args.warmup, 1)):
+        one()
+    torch.cuda.synchronize()
+    state.profile_enable(list(GEMM_CLASSES))
+    state.profile_read(reset=True)
+    for _ in range(reps):
+        one()
+    torch.cuda.synchronize()
+    prof = state.profile_read(reset=True)
+    res = {}
+    for cls in GEMM_CLASSES:
+        ms, n = prof[cls]
+        by, fl = gemm_algorithmic(cfg, cls, rows)
+        us = ms * 1e3 / max(n, 1)
+        tfl, gbs = fl / (us * 1e-6) / 1e12, by / (us * 1e-6) / 1e9
+        bound = "mfma" if fl / (MFMA_BF16_PEAK_TFLOPS * 1e12) >= by / (HBM_PEAK_GBS * 1e9) else "hbm"
+        res[cls] = {"launches": n, "avg_launch_us": us, "bound": bound, "achieved": tfl if bound == "mfma" else gbs,
+                    "peak": MFMA_BF16_PEAK_TFLOPS if bound == "mfma" else HBM_PEAK_GBS, "unit": "TFLOP/s" if bound == "mfma" else "GB/s",
+                    "frac": tfl / MFMA_BF16_PEAK_TFLOPS if bound == "mfma" else gbs / HBM_PEAK_GBS}
+    print(json.dumps({"micro": "wide_pass", "workload": args.workload, "rows": rows, "sequences": nseq, "passes": reps, "gemm": res}))
+    state.close()
+    model.close()
+
+
 def cpu_baseline(cfg, W_host, prompt, prm, sample_layers, n_gen, gpu_pass_counts):
     """The oracle, as it stands, on a bounded sample of the same workload: the prefill pass, two in-block denoising passes
     of the first block and the first boundary pass (with their statistics, selection and boundary decision), through the
@@ -195,8 +247,9 @@ def main():
                          "epilogue (the default) or the streamed reduction every other pass uses")
     ap.add_argument("--weight-copies", type=int, default=1, choices=[0, 1],
                     help="0: no step-major second copies of the layer matrices (DLM_W_STEPS=0 for dlm_model_create)")
-    ap.add_argument("--micro", default="", choices=["", "vocab_stats", "peaks"],
-                    help="time one kernel alone instead of the decode (peaks: a plain HBM read and a matrix-core loop, what the GPU achieves)")
+    ap.add_argument("--micro", default="", choices=["", "vocab_stats", "peaks", "wide_pass"],
+                    help="time one kernel alone instead of the decode (peaks: a plain HBM read and a matrix-core loop, what the GPU achieves; "
+                         "wide_pass: one pass of --rows rows over 16 packed sequences, the matrix-core-bound regime, per GEMM class)")
     ap.add_argument("--rows", type=int, default=3072, help="--micro: rows of the pass (3072 = 16 sequences x 192 rows, the widest batched pass)")
     ap.add_argument("--prev", type=int, default=1, help="--micro vocab_stats: 1 = every row is a KL row (reads the retained logits too; their log-sum-exp is given, as in dlm_step), 2 = the same with that log-sum-exp recomputed in the pass, 0 = no KL rows")
     ap.add_argument("--extras", type=int, default=1, choices=[0, 1],
@@ -210,6 +263,9 @@ def main():
 
     if args.micro == "vocab_stats":
         micro_vocab_stats(args)
+        return
+    if args.micro == "wide_pass":
+        micro_wide_pass(args)
         return
     if args.micro == "peaks":
         import torch

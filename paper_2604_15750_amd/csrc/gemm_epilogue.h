@@ -40,6 +40,34 @@ __device__ inline void block_rinv(const RowScale& rs, int m_lo, int rows, float*
   }
 }
 
+// block_rinv for a workgroup of NT threads and at most ROWS rows with every load of a thread issued before the first is used
+// (one trip to memory): sixteen lanes per row, each adding every sixteenth chunk in ascending order, then the same fixed
+// butterfly.  Up to 64 chunks per row in one trip (what the wide-pass producers write); more fall back to block_rinv.
+template <int NT, int ROWS>
+__device__ inline void block_rinv_batched(const RowScale& rs, int m_lo, int rows, float* s_rinv) {
+  if (rs.ssq && rs.nch > 64) { block_rinv<NT>(rs, m_lo, rows, s_rinv); return; }
+  constexpr int RPT = (ROWS + NT / 16 - 1) / (NT / 16);  // rows per thread
+  const int sub = threadIdx.x & 15;
+  float v[RPT][4];
+#pragma unroll
+  for (int r = 0; r < RPT; ++r) {
+    const int row = (threadIdx.x >> 4) + r * (NT / 16);
+#pragma unroll
+    for (int k = 0; k < 4; ++k) {
+      const int c = sub + 16 * k;
+      v[r][k] = (rs.ssq && row < rows && c < rs.nch) ? rs.ssq[(size_t)(m_lo + row) * rs.nch + c] : 0.f;
+    }
+  }
+#pragma unroll
+  for (int r = 0; r < RPT; ++r) {
+    const int row = (threadIdx.x >> 4) + r * (NT / 16);
+    float ss = ((v[r][0] + v[r][1]) + v[r][2]) + v[r][3];
+#pragma unroll
+    for (int o = 8; o > 0; o >>= 1) ss += __shfl_xor(ss, o, 64);
+    if (sub == 0 && row < rows) s_rinv[row] = rs.ssq ? rsqrtf(ss * rs.inv_d + rs.eps) : 1.f;
+  }
+}
+
 // What an epilogue reads from memory besides the product, fetched ahead (at the start of the kernel, while the first weights
 // are in flight) for the fragment a wavefront finishes first, so that the end of a short kernel does not wait for a round
 // trip: EPI_RESID the four residual values and gains of the lane, EPI_QKV the lane's rotary cosines and sines.
@@ -97,10 +125,12 @@ __device__ inline void finish_qkv(const GemmEpi& e, int m, int nc, int gp, f32x4
     *(f16x4*)(dst + kv_k_index(pos, i, hd)) = ab;
     *(f16x4*)(dst + kv_k_index(pos, i + half, hd)) = bb;
   } else {
+    // dims i .. i+3 (i a multiple of 4) lie in one 16-dim tile: consecutive dims are 8 elements apart (kv_v_index)
+    const size_t va = kv_v_index(pos, i, hd), vb = kv_v_index(pos, i + half, hd);
 #pragma unroll
     for (int j = 0; j < 4; ++j) {
-      dst[kv_v_index(pos, i + j, hd)] = ab[j];
-      dst[kv_v_index(pos, i + half + j, hd)] = bb[j];
+      dst[va + 8 * j] = ab[j];
+      dst[vb + 8 * j] = bb[j];
     }
   }
 }
@@ -109,7 +139,7 @@ __device__ inline void finish_qkv(const GemmEpi& e, int m, int nc, int gp, f32x4
 __device__ inline void finish_swiglu(const GemmEpi& e, int m, int nc, int gp, f32x4 g, f32x4 u) {
   f32x4 a;
 #pragma unroll
-  for (int t = 0; t < 4; ++t) a[t] = g[t] / (1.f + __expf(-g[t])) * u[t];
+  for (int t = 0; t < 4; ++t) a[t] = g[t] * __builtin_amdgcn_rcpf(1.f + __expf(-g[t])) * u[t];  // (the hardware reciprocal: 1 ulp)
   const bf16x4 hi = to_bf16x4(a), lo = to_bf16x4(a - widen4(hi));  // the down projection's input: a pair of planes
   const size_t o = tile_index_pair(m, 8 * (nc >> 4) + 4 * gp, e.ffn, 0);
   *(bf16x4*)(e.act + o) = hi;

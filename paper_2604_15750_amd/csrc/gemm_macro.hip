@@ -117,6 +117,12 @@ __global__ __launch_bounds__(NW * 64) void gemm_macro_kernel(const bf16x8* __res
       for (int i = 0; i < WM * XP; ++i) acc[j][i / XP] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(wf[buf][j], xf[buf][i], acc[j][i / XP], 0, 0, 0);
   };
 
+  // 1/rms of the workgroup's input rows, needed only by the epilogue: fetched before the pipeline starts (its loads are counted
+  // by the compiler, the pipeline's by hand: the two must not be in flight together), all of a thread's loads in one trip;
+  // published to the other wavefronts by the loop's barriers
+  const int m_lo = mt0 * 16;
+  if (EPI != EPI_RESID) block_rinv_batched<TPB, AT * 16>(e.rs, m_lo, max(0, min(M, m_lo + AT * 16) - m_lo), s_rinv);
+
 #pragma unroll
   for (int s = 0; s < S - 1; ++s) issue(s);
   asm volatile("s_waitcnt vmcnt(%0)" ::"n"((S - 2) * LPS) : "memory");  // stage 0 has landed (this wavefront's share)
@@ -139,7 +145,6 @@ __global__ __launch_bounds__(NW * 64) void gemm_macro_kernel(const bf16x8* __res
   asm volatile("s_waitcnt vmcnt(0)" ::: "memory");  // the surplus loads of the last stages: LDS must be quiet before it is reused
 
   const int g = lane >> 4, ml = lane & 15;
-  const int m_lo = mt0 * 16;
   if (splits > 1) {
     // K split (narrow matrices at a few hundred rows, whose tiles alone cover half of the chip): partial tiles go to the fp32
     // workspace in the accumulator layout, written through to device scope; the workgroup that takes the tile's last ticket
@@ -186,7 +191,6 @@ __global__ __launch_bounds__(NW * 64) void gemm_macro_kernel(const bf16x8* __res
   }
 
   // ---- epilogue
-  if (EPI != EPI_RESID) block_rinv<TPB>(e.rs, m_lo, max(0, min(M, m_lo + AT * 16) - m_lo), s_rinv);
   __syncthreads();
   // The accumulators leave the registers through LDS (each wavefront its own region, half of its column tiles at a time), so
   // that the epilogue runs as a loop over fragments instead of 64 unrolled copies with every accumulator live.
@@ -197,19 +201,32 @@ __global__ __launch_bounds__(NW * 64) void gemm_macro_kernel(const bf16x8* __res
   for (int i = 0; i < WM; ++i) ssq[i] = 0.f;
 #pragma unroll
   for (int h = 0; h < 2; ++h) {
+    // what the fragments' epilogues read from memory (residual and gain; rotary cosines and sines) is fetched for up to twelve
+    // fragments per trip instead of one trip per fragment
 #pragma unroll
     for (int jj = 0; jj < HJ; ++jj)
 #pragma unroll
       for (int i = 0; i < WM; ++i) mine[(jj * WM + i) * 64] = acc[h * HJ + jj][i];
+    constexpr int IB = WM * HJ > 12 ? WM / 2 : WM;  // row tiles per trip: at most 12 fragments' worth of registers
 #pragma unroll
-    for (int i = 0; i < WM; ++i) {
-      const int rl = (wm * WM + i) * 16 + ml;
-      const float rinv = EPI == EPI_RESID ? 1.f : s_rinv[rl];
-#pragma unroll 1
-      for (int jj = 0; jj < HJ; ++jj) {
-        const int nt = nt0 + wn * WN + h * HJ + jj;
-        if (nt >= NT) break;  // uniform in the wavefront
-        ssq[i] += finish_frag<EPI>(e, M, N, m_lo + rl, nt * 16, g, mine[(jj * WM + i) * 64], rinv);
+    for (int i0 = 0; i0 < WM; i0 += IB) {
+      EpiAhead ah[IB][HJ];
+#pragma unroll
+      for (int i = 0; i < IB; ++i)
+#pragma unroll
+        for (int jj = 0; jj < HJ; ++jj) {
+          const int nt = nt0 + wn * WN + h * HJ + jj;
+          ah[i][jj] = (EPI == EPI_RESID || EPI == EPI_QKV) && nt < NT ? epi_ahead<EPI>(e, M, N, m_lo + (wm * WM + i0 + i) * 16 + ml, nt * 16, g) : epi_none();
+        }
+#pragma unroll
+      for (int i = 0; i < IB; ++i) {
+        const int rl = (wm * WM + i0 + i) * 16 + ml;
+        const float rinv = EPI == EPI_RESID ? 1.f : s_rinv[rl];
+#pragma unroll
+        for (int jj = 0; jj < HJ; ++jj) {
+          const int nt = nt0 + wn * WN + h * HJ + jj;
+          if (nt < NT) ssq[i0 + i] += finish_frag<EPI>(e, M, N, m_lo + rl, nt * 16, g, mine[(jj * WM + i0 + i) * 64], rinv, ah[i][jj]);  // uniform in the wavefront
+        }
       }
     }
   }
