@@ -91,7 +91,12 @@ def micro_vocab_stats(args):
     ws = torch.empty(api.lib().dlm_vocab_stats_workspace(rows), dtype=torch.uint8, device=dev)
     # KL rows: the retained logits come with their log-sum-exp, as in dlm_step (an earlier pass computed it as that row's lse);
     # --prev 2 leaves it out and has the kernel recompute it from the retained logits in the same pass
-    pl = [api.dlm_vocab_stats(p, V - 1, workspace=ws)["lse"] for p in ps] if (ps and args.prev == 1) else None
+    # (set-up, not the timed path: computed here with torch so that every launch of the kernel in a profile of this run is a KL launch)
+    def lse_of(p):
+        z = p.float()
+        z[:, V - 1] = float("-inf")
+        return torch.logsumexp(z, dim=-1)
+    pl = [lse_of(p) for p in ps] if (ps and args.prev == 1) else None
     run = lambda i: api.dlm_vocab_stats(zs[i % nb], V - 1, prev=ps[i % nb] if ps else None, workspace=ws, prev_lse=pl[i % nb] if pl else None)
     for i in range(args.warmup + 2):
         run(i)
