@@ -224,7 +224,7 @@ int gemm_mid_counters(int max_n);
 void gemm_mid_set_target(int wgs);  // tuning: workgroups the K split aims at
 void launch_gemm_mid(const bf16_t* xt, const bf16_t* wt, int M, int N, int K, const GemmEpi& e, hipStream_t st);  // M <= GEMM_MID_MAX_ROWS(_NARROW); narrow matrices from 17 rows
 #define GEMM_MACRO_MIN_ROWS_NARROW 256  // more rows than this: the macro-tile kernel whatever the width
-int gemm_macro_ssq_chunks(int M, int N);
+int gemm_macro_ssq_chunks(int M, int N, int K);
 int gemm_macro_splits(int M, int N, int K, int kind);
 int gemm_macro_counters(int max_rows, int max_n);
 void gemm_macro_set_target(int wgs);  // tuning: workgroups the K split aims at

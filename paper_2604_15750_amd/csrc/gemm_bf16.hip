@@ -133,7 +133,7 @@ int gemm_bf16_ssq_chunks(int M, int N, int K) {
   switch (choose_kernel(M, N, K, EPI_RESID)) {
     case KERNEL_SKINNY: return N >> 4;
     case KERNEL_MID: return gemm_mid_ssq_chunks(M, N, K);
-    case KERNEL_MACRO: return gemm_macro_ssq_chunks(M, N);
+    case KERNEL_MACRO: return gemm_macro_ssq_chunks(M, N, K);
     default: return gemm_tiled_ssq_chunks(M, N);
   }
 }

@@ -70,12 +70,14 @@ __device__ inline void block_rinv_batched(const RowScale& rs, int m_lo, int rows
 
 // What an epilogue reads from memory besides the product, fetched ahead (at the start of the kernel, while the first weights
 // are in flight) for the fragment a wavefront finishes first, so that the end of a short kernel does not wait for a round
-// trip: EPI_RESID the four residual values and gains of the lane, EPI_QKV the lane's rotary cosines and sines.
+// trip: EPI_RESID the four residual values and gains of the lane, EPI_QKV the lane's rotary cosines and sines and, for the
+// K and V heads, the row's position and cache slot.
 struct EpiAhead {
   f32x4 a, b;
   bool have;
+  int pos, slot;  // EPI_QKV, K and V heads: the row's position and cache slot (-1: not fetched)
 };
-__device__ inline EpiAhead epi_none() { return EpiAhead{f32x4{0.f, 0.f, 0.f, 0.f}, f32x4{0.f, 0.f, 0.f, 0.f}, false}; }
+__device__ inline EpiAhead epi_none() { return EpiAhead{f32x4{0.f, 0.f, 0.f, 0.f}, f32x4{0.f, 0.f, 0.f, 0.f}, false, -1, -1}; }
 template <int EPI>
 __device__ inline EpiAhead epi_ahead(const GemmEpi& e, int M, int N, int m, int nc, int g) {
   EpiAhead r = epi_none();
@@ -87,11 +89,18 @@ __device__ inline EpiAhead epi_ahead(const GemmEpi& e, int M, int N, int m, int 
     }
   } else if (EPI == EPI_QKV) {
     const int hd = e.hd, half = hd >> 1;
-    if (m < M && nc < N && g < 2 && nc / hd < e.n_q + e.n_kv) {
-      const int i = 8 * ((nc % hd) >> 4) + 4 * g;
-      r.a = *(const f32x4*)(e.rope_cos + (size_t)m * half + i);
-      r.b = *(const f32x4*)(e.rope_sin + (size_t)m * half + i);
-      r.have = true;
+    if (m < M && nc < N && g < 2) {
+      const int head = nc / hd;
+      if (head < e.n_q + e.n_kv) {
+        const int i = 8 * ((nc % hd) >> 4) + 4 * g;
+        r.a = *(const f32x4*)(e.rope_cos + (size_t)m * half + i);
+        r.b = *(const f32x4*)(e.rope_sin + (size_t)m * half + i);
+        r.have = true;
+      }
+      if (head >= e.n_q) {
+        r.pos = e.row_pos[m];
+        r.slot = e.row_slot[m];
+      }
     }
   }
   return r;
@@ -119,8 +128,10 @@ __device__ inline void finish_qkv(const GemmEpi& e, int m, int nc, int gp, f32x4
   }
   const bool is_k = head < e.n_q + e.n_kv;
   const int kvh = is_k ? head - e.n_q : head - e.n_q - e.n_kv;
-  const int pos = e.row_pos[m];
-  f16_t* dst = (is_k ? e.kcache : e.vcache) + (size_t)e.row_slot[m] * e.slot_stride + (size_t)kvh * e.head_stride;
+  // (a load here, between the stores of two fragments, has to wait for every store before it: the memory counter retires in order)
+  const int pos = ahead.pos >= 0 ? ahead.pos : e.row_pos[m];
+  const int slot = ahead.pos >= 0 ? ahead.slot : e.row_slot[m];
+  f16_t* dst = (is_k ? e.kcache : e.vcache) + (size_t)slot * e.slot_stride + (size_t)kvh * e.head_stride;
   if (is_k) {  // four consecutive dims share a lane slot of the K tiling
     *(f16x4*)(dst + kv_k_index(pos, i, hd)) = ab;
     *(f16x4*)(dst + kv_k_index(pos, i + half, hd)) = bb;

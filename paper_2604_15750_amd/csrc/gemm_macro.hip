@@ -9,14 +9,16 @@
 // four wavefronts where the larger tile would leave compute units idle; it walks K one k-tile (32) at a time:
 //   * both operands are already stored as 1 KiB matrix-core fragments (16 rows x 32 k), so a stage of
 //     the pipeline is just 2 WM + 2 WN fragments copied HBM/L2 -> LDS by direct-to-LDS loads (no
-//     registers, no LDS writes): 4 to 8 stages of 16 .. 28 KiB rotate through up to 128 KiB of LDS;
+//     registers, no LDS writes): 4 to 8 stages of 16 .. 32 KiB rotate through up to 128 KiB of LDS
+//     (3 stages in 74 KiB where two four-wavefront workgroups share a compute unit: macro_plan);
 //   * a wavefront owns WM x WN fragments of the output (fp32 accumulators, up to 256 registers), reads
 //     its WM + WN operand fragments of the NEXT k-tile from LDS into a second register set while the
-//     matrix cores work on the current one (WM WN products per WM + WN fragment reads);
+//     matrix cores work on the current one (WM WN products per WM + WN fragment reads); the order in
+//     which products, copies and reads are issued is fixed by hand (see step);
 //   * the accumulators reach the epilogue through LDS, half of a wavefront's column tiles at a time;
 //   * one barrier per k-tile; the waits on the direct-to-LDS loads are counted by hand (every stage is
 //     the same number of loads per wavefront; indices past the end are clamped, so the count never
-//     varies).
+//     varies), and so are the waits on the LDS reads (once per step, behind the products).
 // Workgroups that share columns (and so W) get ids congruent mod 8: they run on the same XCD and find
 // W in its L2 after the first reader; X is shared by every column block through the L2s and the
 // memory-side cache.  The product is computed transposed (W fragment = A operand) like the other
@@ -36,7 +38,7 @@ __device__ inline __amdgpu_buffer_rsrc_t part_rsrc(const float* base) {
 #define LDS_PTR(p) ((void __attribute__((address_space(3)))*)(p))
 
 // XP: planes of X (the EPI_RESID GEMMs read a pair per fragment tile)
-template <int WM, int WN, int XP = 1, int NW = 4>
+template <int WM, int WN, int XP = 1, int NW = 4, bool TWO = false>
 struct MacroShape {
   static constexpr int TPB = NW * 64;
   static constexpr int AT = (NW / 2) * WM;         // row tiles of the workgroup
@@ -44,17 +46,19 @@ struct MacroShape {
   static constexpr int NFR = AF + BF;
   static constexpr int LPS = (NFR + NW - 1) / NW;  // direct-to-LDS loads per wavefront and stage (surplus ones repeat the last fragment)
   static constexpr int STAGE = NFR * 1024;
-  static constexpr int S = 131072 / STAGE > 8 ? 8 : 131072 / STAGE;  // stages: at most 128 KiB (of the 160 KiB of a compute unit)
+  // TWO: two workgroups share a compute unit (three stages each; see macro_plan)
+  static constexpr int LDSB = TWO ? 75776 : 131072;
+  static constexpr int S = LDSB / STAGE > 8 ? 8 : LDSB / STAGE;  // stages: at most 128 KiB (of the 160 KiB of a compute unit)
   static constexpr int LDS_BYTES = S * STAGE + AT * 16 * 4 * 3;      // + 1/rms of the rows, two partial sums of squares per row
 };
 
-template <int WM, int WN, int PR, int EPI, int NW = 4>
-__global__ __launch_bounds__(NW * 64) void gemm_macro_kernel(const bf16x8* __restrict__ xt, const bf16x8* __restrict__ wt, int M, int N, int K,
-                                                             int nblocks, int mblocks, int splits, int kt_per_split, GemmEpi e) {
+template <int WM, int WN, int PR, int EPI, int NW = 4, bool TWO = false>
+__global__ __launch_bounds__(NW * 64, TWO ? 2 : 1) void gemm_macro_kernel(const bf16x8* __restrict__ xt, const bf16x8* __restrict__ wt, int M, int N,
+                                                                          int K, int nblocks, int mblocks, int splits, int kt_per_split, GemmEpi e) {
   constexpr int XP = XPlanes<EPI>::value;
-  typedef MacroShape<WM, WN, XP, NW> SH;
+  typedef MacroShape<WM, WN, XP, NW, TWO> SH;
   constexpr int TPB = SH::TPB, AT = SH::AT, AF = SH::AF, BF = SH::BF, LPS = SH::LPS, STAGE = SH::STAGE, S = SH::S;
-  static_assert(AF % NW == 0 && S >= 4 && (S - 2) * LPS < 64, "pipeline shape");
+  static_assert(AF % NW == 0 && S >= 3 && (S - 2) * LPS < 64, "pipeline shape");
   extern __shared__ __align__(16) unsigned char lds[];
   float* s_rinv = (float*)(lds + S * STAGE);  // [AT * 16]
   float* s_ssq = s_rinv + AT * 16;            // [2][AT * 16]
@@ -129,19 +133,46 @@ __global__ __launch_bounds__(NW * 64) void gemm_macro_kernel(const bf16x8* __res
   __builtin_amdgcn_s_barrier();
   asm volatile("" ::: "memory");
   read_frags(0, 0);
+  __builtin_amdgcn_s_waitcnt(0xc07f);  // lgkmcnt(0): as at the end of every step below
   // iteration kt: registers kt & 1 hold stage kt; stages kt + 1 .. kt + S - 2 are in flight
   auto step = [&](int buf, int kt) {
     asm volatile("s_waitcnt vmcnt(%0)" ::"n"((S - 3) * LPS) : "memory");  // stage kt + 1 has landed
     __builtin_amdgcn_s_barrier();  // ... for every wavefront, and every wavefront has finished with the buffer of stage kt - 1
     asm volatile("" ::: "memory");
+    __builtin_amdgcn_sched_barrier(0);
     issue(kt + S - 1);
     read_frags(buf ^ 1, kt + 1);
     multiply(buf);
+    // Issue order, fixed by hand: the products (which depend on registers only) start right behind the barrier, and the copies
+    // and the LDS reads of the next k-tile go out between them.  Left alone, the scheduler puts the reads next to their uses,
+    // and all wavefronts of a SIMD, which leave the barrier together, would issue their loads while its matrix core idles.
+    constexpr int NM = WN * WM * XP, RF = WM * XP + WN;
+    constexpr int OPS = 2 * (LPS + RF) <= NM ? 1 : 2;  // copies / reads per product: all of them go out in the first half of the products,
+                                                        // so that the last read has the second half's time to return
+#pragma unroll
+    for (int i = 0; i < LPS; i += OPS) {
+      __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);  // one product
+      __builtin_amdgcn_sched_group_barrier(0x010, OPS, 0);  // copies to LDS
+    }
+#pragma unroll
+    for (int i = 0; i < RF; i += OPS) {
+      __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+      __builtin_amdgcn_sched_group_barrier(0x100, OPS, 0);  // LDS reads
+    }
+    __builtin_amdgcn_sched_group_barrier(0x008, NM, 0);  // what is left of the products
+    __builtin_amdgcn_sched_barrier(0);
+    // The reads have had the products' time to complete.  Waiting here, not at their first use behind the next step's reads:
+    // the compiler counts the copies to LDS as possibly out of order on this counter and can only wait for everything.
+    __builtin_amdgcn_s_waitcnt(0xc07f);  // lgkmcnt(0)
   };
-  for (int kt = 0; kt < nk; kt += 2) {
+  // two k-tiles per trip, unconditionally: a fragment read that is used only behind a branch would be moved behind it, next to
+  // its use, and the matrix cores would wait for LDS
+  int kt = 0;
+  for (; kt + 1 < nk; kt += 2) {
     step(0, kt);
-    if (kt + 1 < nk) step(1, kt + 1);
+    step(1, kt + 1);
   }
+  if (kt < nk) step(0, kt);
   asm volatile("s_waitcnt vmcnt(0)" ::: "memory");  // the surplus loads of the last stages: LDS must be quiet before it is reused
 
   const int g = lane >> 4, ml = lane & 15;
@@ -242,6 +273,7 @@ __global__ __launch_bounds__(NW * 64) void gemm_macro_kernel(const bf16x8* __res
 
 struct MacroPlan {
   int wm, wn, nw, nblocks, mblocks, splits, kps;
+  bool two;  // two workgroups per compute unit (the three-stage variant of a four-wavefront tile)
 };
 
 // the tile with the least estimated time: rounds of workgroups over the chip x products per workgroup, each tile charged
@@ -249,9 +281,16 @@ struct MacroPlan {
 int g_macro_wgs = 256;  // workgroups a K split aims at
 constexpr int NCAND = 5;
 // time of a round of workgroups over the chip / tile area, relative to 128 x 256 with four wavefronts (measured on the layer
-// matrices of an 8B model; the second row: X as a pair of planes)
-double g_macro_penalty[NCAND] = {0.76, 1.0, 1.25, 0.92, 0.83};
+// matrices of an 8B model with random operand values; the second row: X as a pair of planes)
+double g_macro_penalty[NCAND] = {0.63, 1.0, 1.21, 0.86, 0.72};
 double g_macro_penalty_pair[3] = {0.84, 1.0, 1.12};
+// A four-wavefront tile of single planes that needs two or more rounds runs as two workgroups per compute unit, three stages
+// each: the pair hides each other's barriers, waits and output stores and takes 1.45 of one deep workgroup's time instead of 2;
+// the odd round's workgroups run at about the deep variant's pace (measured at 256 .. 2048 rows, operands of random values:
+// constant ones let the chip clock higher and flatter the large tiles).  Tiles of plane pairs,
+// bound by what they fetch, lose more from three stages than the sharing returns and stay as they are.
+double g_macro_shared_pair[NCAND] = {0, 1.45, 1.45, 0, 0}, g_macro_shared_single[NCAND] = {0, 1.15, 0.9, 0, 0};
+double g_macro_split_cost = 328.0;
 
 MacroPlan macro_plan(int M, int N, int K, bool may_split, int kind) {
   // {WM, WN, wavefronts}: 256 x 256, 128 x 256, 128 x 128, 192 x 256, 256 x 192; when X is a pair of planes (EPI_RESID) the eight
@@ -259,37 +298,40 @@ MacroPlan macro_plan(int M, int N, int K, bool may_split, int kind) {
   // the 192-row tile is left out (its stages no longer fit LDS four deep)
   const bool pair = kind == EPI_RESID;
   const int cand[NCAND][3] = {{pair ? 2 : 4, 8, 8}, {4, 8, 4}, {4, 4, 4}, {6, 8, 4}, {4, 6, 8}};
-  MacroPlan best{4, 8, 4, 1, 1, 1, 0};
+  MacroPlan best{4, 8, 4, 1, 1, 1, 0, false};
   double best_cost = 1e300;
-  const int ncand = pair ? 3 : NCAND;
+  const int ncand = pair ? 3 : NCAND, KT = K >> 5;
   for (int c = 0; c < ncand; ++c) {
     const int bm = 8 * cand[c][2] * cand[c][0], bn = 32 * cand[c][1];
-    const int mb = (M + bm - 1) / bm, nb = (N + bn - 1) / bn;
-    const int rounds = (mb * nb + 255) / 256;
-    const double cost = (double)rounds * bm * bn * (pair ? g_macro_penalty_pair[c] : g_macro_penalty[c]);
-    if (cost < best_cost) { best_cost = cost; best = MacroPlan{cand[c][0], cand[c][1], cand[c][2], nb, mb, 1, 0}; }
+    const int mb = (M + bm - 1) / bm, nb = (N + bn - 1) / bn, tiles = mb * nb;
+    // tiles that cover at most half of the chip (narrow matrices at a few hundred rows): split K until they cover it
+    int sp = may_split ? g_macro_wgs / tiles : 1;
+    if (sp > 4) sp = 4;
+    if (sp > KT / 32) sp = KT / 32;  // at least 32 k-tiles per workgroup: the pipeline is up to 8 stages deep
+    if (sp < 1) sp = 1;
+    const int kps = (KT + sp - 1) / sp;
+    sp = (KT + kps - 1) / kps;  // no empty split
+    const int rounds = (tiles * sp + 255) / 256;
+    const bool two = !pair && g_macro_shared_pair[c] > 0 && rounds >= 2;
+    const double turns = two ? (rounds / 2) * g_macro_shared_pair[c] + (rounds & 1) * g_macro_shared_single[c] : rounds;
+    // a split workgroup does 1 / sp of the products, and writes and re-reads partial tiles: about g_macro_split_cost columns of K each
+    const double share = 1.0 / sp + (sp > 1 ? g_macro_split_cost * sp / K : 0.0);
+    const double cost = turns * bm * bn * (pair ? g_macro_penalty_pair[c] : g_macro_penalty[c]) * share;
+    if (cost < best_cost) { best_cost = cost; best = MacroPlan{cand[c][0], cand[c][1], cand[c][2], nb, mb, sp, kps, two}; }
   }
-  // tiles that cover at most half of the chip (narrow matrices at a few hundred rows): split K until they cover it
-  const int KT = K >> 5, wgs = best.nblocks * best.mblocks;
-  int s = may_split ? g_macro_wgs / wgs : 1;
-  if (s > 4) s = 4;
-  if (s > KT / 32) s = KT / 32;  // at least 32 k-tiles per workgroup: the pipeline is up to 8 stages deep
-  if (s < 1) s = 1;
-  best.kps = (KT + s - 1) / s;
-  best.splits = (KT + best.kps - 1) / best.kps;  // no empty split
   return best;
 }
 
-template <int WM, int WN, int NW, int PR, int EPI>
+template <int WM, int WN, int NW, int PR, int EPI, bool TWO = false>
 void launch_one(const bf16_t* xt, const bf16_t* wt, int M, int N, int K, const MacroPlan& p, const GemmEpi& e, hipStream_t st) {
-  typedef MacroShape<WM, WN, XPlanes<EPI>::value, NW> SH;
+  typedef MacroShape<WM, WN, XPlanes<EPI>::value, NW, TWO> SH;
   static bool configured = false;  // raise the dynamic LDS limit of this instantiation once
   if (!configured) {
-    (void)hipFuncSetAttribute((const void*)gemm_macro_kernel<WM, WN, PR, EPI, NW>, hipFuncAttributeMaxDynamicSharedMemorySize, SH::LDS_BYTES);
+    (void)hipFuncSetAttribute((const void*)gemm_macro_kernel<WM, WN, PR, EPI, NW, TWO>, hipFuncAttributeMaxDynamicSharedMemorySize, SH::LDS_BYTES);
     configured = true;
   }
   const int grid = (p.nblocks + 7) / 8 * 8 * p.mblocks * p.splits;
-  DLM_LAUNCH((gemm_macro_kernel<WM, WN, PR, EPI, NW>), grid, SH::TPB, SH::LDS_BYTES, st, (const bf16x8*)xt, (const bf16x8*)wt, M, N, K, p.nblocks,
+  DLM_LAUNCH((gemm_macro_kernel<WM, WN, PR, EPI, NW, TWO>), grid, SH::TPB, SH::LDS_BYTES, st, (const bf16x8*)xt, (const bf16x8*)wt, M, N, K, p.nblocks,
              p.mblocks, p.splits, p.kps, e);
 }
 
@@ -299,6 +341,12 @@ void launch_shape(const bf16_t* xt, const bf16_t* wt, int M, int N, int K, const
   if (p.nw == 8 && p.wn == 6) { if constexpr (!pair) launch_one<4, 6, 8, PR, EPI>(xt, wt, M, N, K, p, e, st); }
   else if (p.nw == 8) launch_one<(pair ? 2 : 4), 8, 8, PR, EPI>(xt, wt, M, N, K, p, e, st);
   else if (p.wm == 6) { if constexpr (!pair) launch_one<6, 8, 4, PR, EPI>(xt, wt, M, N, K, p, e, st); }
+  else if (p.two) {
+    if constexpr (!pair) {
+      if (p.wn == 8) launch_one<4, 8, 4, PR, EPI, true>(xt, wt, M, N, K, p, e, st);
+      else launch_one<4, 4, 4, PR, EPI, true>(xt, wt, M, N, K, p, e, st);
+    }
+  }
   else if (p.wn == 8) launch_one<4, 8, 4, PR, EPI>(xt, wt, M, N, K, p, e, st);
   else launch_one<4, 4, 4, PR, EPI>(xt, wt, M, N, K, p, e, st);
 }
@@ -311,7 +359,7 @@ void launch_epi(const bf16_t* xt, const bf16_t* wt, int M, int N, int K, const M
 
 }  // namespace
 
-int gemm_macro_ssq_chunks(int M, int N) { return macro_plan(M, N, 32, false, EPI_RESID).nblocks; }
+int gemm_macro_ssq_chunks(int M, int N, int K) { return macro_plan(M, N, K, true, EPI_RESID).nblocks; }  // (the plan of the launch itself)
 int gemm_macro_splits(int M, int N, int K, int kind) { return macro_plan(M, N, K, true, kind).splits; }
 int gemm_macro_counters(int max_rows, int max_n) { return ((max_n + 127) / 128) * ((max_rows + 127) / 128); }  // 128 x 128 tiles are the smallest
 void gemm_macro_set_target(int wgs) { g_macro_wgs = wgs; }
