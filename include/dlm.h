@@ -19,7 +19,11 @@
  *   - `stream` is a hipStream_t passed as void* (NULL = the default stream).  All work is enqueued
  *     on it; outputs are valid once the caller has synchronised it.
  *   - the caller owns every buffer it passes; the library owns what *_create allocated.
- *   - dtype: DLM_F32 = IEEE binary32, DLM_BF16 = bfloat16; accumulation is always fp32.
+ *   - dtype: DLM_F32 = IEEE binary32, DLM_BF16 = bfloat16; accumulation is always fp32.  DLM_BF16 is what the caller's
+ *     weights, embeddings and logits are stored as.  Inside a pass the matrix cores are fed IEEE half: the layer weights are
+ *     converted once, by dlm_model_create (exactly, except that a weight below 2^-14 in magnitude keeps an absolute error of
+ *     at most 2^-25), and the activations the GEMMs and the attention read are rounded to half (11 significant bits, values
+ *     beyond +-65504 saturate) instead of bfloat16 (8 bits); the residual stream is fp32.
  */
 #ifndef DLM_H
 #define DLM_H
@@ -66,7 +70,7 @@ typedef struct dlm_model dlm_model;
 typedef struct dlm_state dlm_state;
 
 /* Copies the weights into library-owned device memory (bf16 matrices are re-tiled for the matrix
- * cores on `stream`).  The caller may release its own tensors once `stream` has been synchronised.
+ * cores, in IEEE half, on `stream`).  The caller may release its own tensors once `stream` has been synchronised.
  * bf16 layer matrices are kept twice where the kernel that serves passes of up to 16 to 64 rows has a
  * layout of its own for them (what all workgroups read at the same step adjacent in memory): the
  * model then takes up to twice its layer weights (30 GB for an 8B model).  A copy that does not fit

@@ -101,7 +101,7 @@ __global__ __launch_bounds__(256) void attention_kernel(const T* __restrict__ q,
 template <int HD, int NWV, int DS>
 __global__ __launch_bounds__(NWV * 64) void attention_mfma_kernel(const f16_t* __restrict__ q, const f16_t* __restrict__ kcache,
                                                                   const f16_t* __restrict__ vcache, size_t slot_stride, size_t head_stride,
-                                                                  AttnMeta meta, bf16_t* __restrict__ out, bool out_pair, int n_q, int n_kv) {
+                                                                  AttnMeta meta, op_t* __restrict__ out_tiles, bf16_t* __restrict__ out_rows, int n_q, int n_kv) {
   __shared__ AttnLds<HD, NWV, DS> L;
   const int b = blockIdx.z, head = blockIdx.y, tile = blockIdx.x / DS, dpart = blockIdx.x - tile * DS;
   const int row0 = meta.row_off[b] + tile * 16;
@@ -109,7 +109,7 @@ __global__ __launch_bounds__(NWV * 64) void attention_mfma_kernel(const f16_t* _
   if (row0 >= row_end) return;
   const int kvh = head / (n_q / n_kv);
   const size_t region = (size_t)meta.slot[b] * slot_stride + (size_t)kvh * head_stride;
-  attention_tile<HD, NWV, DS>(q, kcache + region, vcache + region, row0, row_end, meta.n_keys[b], head, n_q, out, out_pair, L, dpart);
+  attention_tile<HD, NWV, DS>(q, kcache + region, vcache + region, row0, row_end, meta.n_keys[b], head, n_q, out_tiles, out_rows, L, dpart);
 }
 
 // K [T, n_kv, hd] and V row-major bf16 -> the tiled half-precision cache layout of one slot (test helper for dlm_attention)
@@ -143,13 +143,13 @@ void launch_attention<float>(const float* q, const float* kcache, const float* v
 }
 
 void launch_attention_f16(const f16_t* q, const f16_t* kcache, const f16_t* vcache, size_t slot_stride, size_t head_stride, const AttnMeta& meta,
-                          bf16_t* out, bool out_pair, int rows, int max_seq_rows, int n_q, int n_kv, int hd, hipStream_t st) {
+                          op_t* out_tiles, bf16_t* out_rows, int rows, int max_seq_rows, int n_q, int n_kv, int hd, hipStream_t st) {
   const int tiles = (max_seq_rows + 15) / 16;
   // a narrow pass (few query tiles x heads): eight wavefronts per workgroup to shorten each wavefront's chain of dependent
   // loads, and the output dims of a head split over four workgroups (two for 64 dims) to spread its K / V traffic
   const bool narrow = (size_t)tiles * n_q * meta.n_seqs < 128 && hd >= 64;
   const bool wide = (size_t)tiles * n_q * meta.n_seqs >= 512;  // enough workgroups to fill the chip with 4 wavefronts each
-#define GO(HD, NWV, DS) attention_mfma_kernel<HD, NWV, DS><<<dim3(tiles * DS, n_q, meta.n_seqs), NWV * 64, 0, st>>>(q, kcache, vcache, slot_stride, head_stride, meta, out, out_pair, n_q, n_kv)
+#define GO(HD, NWV, DS) attention_mfma_kernel<HD, NWV, DS><<<dim3(tiles * DS, n_q, meta.n_seqs), NWV * 64, 0, st>>>(q, kcache, vcache, slot_stride, head_stride, meta, out_tiles, out_rows, n_q, n_kv)
   if (hd == 32) { if (wide) GO(32, 4, 1); else GO(32, 8, 1); }
   else if (hd == 64) { if (narrow) GO(64, 8, 2); else if (wide) GO(64, 4, 1); else GO(64, 8, 1); }
   else { if (narrow) GO(128, 8, 4); else if (wide) GO(128, 4, 1); else GO(128, 8, 1); }

@@ -23,15 +23,15 @@ struct AttnLds {  // merge buffers of one workgroup (HD / DS of the head's dims)
 };
 
 // q: row-major [rows, n_q * HD]; kt / vt: the (slot, kv head) region of the tiled cache; rows [row0, row_end) x head `head`
-// against keys [0, n_keys); out: the pair-of-planes activation layout [rows, n_q * HD] (out_pair: hi = bf16(o),
-// lo = bf16(o - hi), the O projection's input) or row-major bf16.  Called by every thread of a workgroup of NWV wavefronts.
+// against keys [0, n_keys); output to out_tiles (fragment tiles [rows, n_q * HD] in half: the O projection's input) if given,
+// else to out_rows (row-major bf16).  Called by every thread of a workgroup of NWV wavefronts.
 // DS > 1: the workgroup produces only dims [dpart * HD / DS, (dpart + 1) * HD / DS) of the output: it reads all of K (the
 // scores and the softmax are computed by each of the DS workgroups of a head, identically) but only its share of V.  What
 // bounds a narrow pass is what one compute unit can pull through its L2 (about 50 GB/s), and K and V of a head are its whole
 // traffic: four workgroups per head move 5/8 of it each, with nothing to merge.
 template <int HD, int NWV, int DS = 1>
 __device__ inline void attention_tile(const f16_t* __restrict__ q, const f16_t* __restrict__ kregion, const f16_t* __restrict__ vregion,
-                                      int row0, int row_end, int n_keys, int head, int n_q, bf16_t* __restrict__ out, bool out_pair,
+                                      int row0, int row_end, int n_keys, int head, int n_q, op_t* __restrict__ out_tiles, bf16_t* __restrict__ out_rows,
                                       AttnLds<HD, NWV, DS>& L, int dpart = 0) {
   constexpr int KS = HD / 32, DT = HD / 16 / DS, HDP = HD / DS;
   static_assert(HDP * 16 >= NWV * 64, "every thread finishes at least one dim");
@@ -138,14 +138,8 @@ __device__ inline void attention_tile(const f16_t* __restrict__ q, const f16_t* 
       for (int wv = 0; wv < NWV; ++wv) acc += w[wv] * L.so[wv][d][qi];
       const int col = head * HD + dpart * HDP + d;
       const float v = acc / Lsum;
-      const bf16_t hi = (bf16_t)v;
-      if (out_pair) {
-        const size_t idx = tile_index_pair(r, col, width, 0);
-        out[idx] = hi;
-        out[idx + 512] = (bf16_t)(v - (float)hi);
-      } else {
-        out[(size_t)r * width + col] = hi;
-      }
+      if (out_tiles) out_tiles[tile_index(r, col, width)] = to_f16_sat(v);
+      else out_rows[(size_t)r * width + col] = (bf16_t)v;
     }
   }
   __syncthreads();  // the merge buffers may be reused

@@ -10,11 +10,21 @@ typedef __bf16 bf16_t;
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef __bf16 bf16x4 __attribute__((ext_vector_type(4)));
 typedef float f32x4 __attribute__((ext_vector_type(4)));
-// IEEE half: the storage type of a bf16 model's attention operands (Q, the KV cache, the unnormalised probabilities).  Same
-// bytes and matrix-core rate as bf16 with three more mantissa bits; values beyond +-65504 saturate (to_f16_sat).
+// IEEE half: what a bf16 model's matrix-core operands are stored as.  Same bytes and matrix-core rate as bf16 with three more
+// mantissa bits; values beyond +-65504 saturate (to_f16_sat).
+//   * attention: Q, the KV cache, the unnormalised probabilities;
+//   * GEMMs (op_t): every activation a GEMM reads (the norm outputs h * gain, the attention output, the gated FFN activation)
+//     and the packed weights.  A bf16 weight converts exactly unless it is below 2^-14 in magnitude (then it keeps an absolute
+//     error of at most 2^-25).  Rounding the activations to bf16's 8 mantissa bits instead is what carries most of a deep
+//     model's logit error: at 32 layers of the 8B shape the worst logit error is 1.4e-2 of the row's scale with bf16 norm
+//     outputs (whatever the precision of the others) and 0.5e-2 with all of them in half.
+// The residual stream stays fp32, the logits bf16.
 typedef _Float16 f16_t;
 typedef _Float16 f16x8 __attribute__((ext_vector_type(8)));
 typedef _Float16 f16x4 __attribute__((ext_vector_type(4)));
+typedef f16_t op_t;
+typedef f16x8 op8;
+typedef f16x4 op4;
 
 #define DLM_WAVE 64
 
@@ -26,22 +36,13 @@ int dlm_fail(int code, const char* fmt, ...);
   } while (0)
 
 // ---- activation layouts -------------------------------------------------------------------
-// fp32 models keep activations row-major.  bf16 models keep every GEMM input in "fragment tiles":
+// fp32 models keep activations row-major.  bf16 models keep every GEMM input (op_t) in "fragment tiles":
 // element (m, k) of an [M, K] matrix lives in the 1 KiB tile (m/16, k/32), at lane
-// (m%16) + 16*((k%32)/8), slot k%8 -- exactly one operand of the 16x16x32 bf16 matrix-core
+// (m%16) + 16*((k%32)/8), slot k%8 -- exactly one operand of the 16x16x32 half-precision matrix-core
 // instruction per tile, so a wavefront fetches an operand as 64 consecutive 16-byte pieces.
 __host__ __device__ inline size_t tile_index(int m, int k, int K) {
   return ((size_t)(m >> 4) * (size_t)(K >> 5) + (size_t)(k >> 5)) * 512 + (size_t)(((m & 15) + 16 * ((k & 31) >> 3)) * 8 + (k & 7));
 }
-// The inputs of the two projections that feed the fp32 residual stream (O and down: the attention output and the gated FFN
-// activation) are kept as a PAIR of bf16 planes, hi = bf16(v) and lo = bf16(v - hi), together about 16 mantissa bits: rounding
-// them to one bf16 is, with the attention operands, what carries most of a deep model's logit error.  The two planes of a
-// fragment tile are adjacent (2 KiB per tile: hi then lo), and the GEMM multiplies each weight fragment with both.
-constexpr int PAIR_PLANES = 2;
-__host__ __device__ inline size_t tile_index_pair(int m, int k, int K, int plane) {
-  return ((size_t)(m >> 4) * (size_t)(K >> 5) + (size_t)(k >> 5)) * 1024 + (size_t)plane * 512 + (size_t)(((m & 15) + 16 * ((k & 31) >> 3)) * 8 + (k & 7));
-}
-
 // bf16 KV cache of one (slot, kv head): K in tiles of 16 positions x 32 dims (A operand of S^T = K Q^T), V in tiles of 16 dims x 32
 // positions (A operand of O^T = V^T P^T) whose 8-element lane slots hold positions {4g..4g+3, 16+4g..16+4g+3} of the 32-block: the order in
 // which the first product leaves the keys in a lane's registers.
@@ -54,10 +55,12 @@ __host__ __device__ inline size_t kv_v_index(int pos, int d, int hd) {
 }
 
 template <typename T> struct Act;
-template <> struct Act<float> {
+template <> struct Act<float> {  // x_t: what the model's GEMM inputs are stored as
+  typedef float x_t;
   static __device__ inline size_t idx(int m, int k, int K) { return (size_t)m * K + k; }
 };
 template <> struct Act<bf16_t> {
+  typedef op_t x_t;
   static __device__ inline size_t idx(int m, int k, int K) { return tile_index(m, k, K); }
 };
 
@@ -68,6 +71,8 @@ __device__ inline f16_t to_f16_sat(float x) { return (f16_t)__builtin_amdgcn_fme
 template <typename T> __device__ inline T from_f32(float x);
 template <> __device__ inline float from_f32<float>(float x) { return x; }
 template <> __device__ inline bf16_t from_f32<bf16_t>(float x) { return (bf16_t)x; }
+template <> __device__ inline f16_t from_f32<f16_t>(float x) { return to_f16_sat(x); }
+__device__ inline f32x4 mfma_op(op8 a, op8 b, f32x4 c) { return __builtin_amdgcn_mfma_f32_16x16x32_f16(a, b, c, 0, 0, 0); }
 
 __device__ inline float wave_sum(float v) {
 #pragma unroll
@@ -122,7 +127,7 @@ struct RowTables {  // device arrays of one pass, [rows]
 };
 
 // ---- launchers (callers have validated shapes) -------------------------------------------------
-// bf16 weight tiling: W [N, K] row-major -> 1 KiB fragments of 16 rows x 32 k, `pr` (1 or 2) row-tiles interleaved along k:
+// weight tiling: W [N, K] row-major bf16 -> 1 KiB fragments of 16 rows x 32 k in half precision (op_t), `pr` (1 or 2) row-tiles interleaved along k:
 // fragment (nt, kt) sits at ((nt/pr * K/32 + kt) * pr + nt%pr) KiB.  The rows may be permuted first so that the columns an
 // epilogue has to combine share one 16-column output tile (packed row n holds source row weight_source_row(n, ...)):
 //   PERM_ROTARY (param = head_dim): tile b of a head holds dims 8b..8b+7 and their rotary partners 8b+hd/2..8b+hd/2+7
@@ -140,16 +145,16 @@ __host__ __device__ inline int weight_source_row(int n, int perm, int param) {
   return n;
 }
 __host__ __device__ inline int weight_pack_rows(int N) { return N <= 8192 ? 1 : 2; }  // narrow matrices: one run per 16-column tile
-void launch_pack_weight(const bf16_t* w, bf16_t* out, int N, int K, int perm, int perm_param, hipStream_t st);
+void launch_pack_weight(const bf16_t* w, op_t* out, int N, int K, int perm, int perm_param, hipStream_t st);
 // W [N, K] row-major -> step-major fragments for the kernel that serves (N, K) at up to 16 rows: column groups of ct tiles
 // and W = 4 wavefronts per workgroup (the mid kernel's no-split launches), or ct = 1 and W = 8 (the skinny kernel's 16-column
 // workgroups).  The fragment (column tile g ct + r, k-tile w KT/W + s) that wavefront w of workgroup g reads at its step s sits
 // at (((s G + g) W + w) ct + r) KiB, G = N / (16 ct): what all workgroups read at the same step is one run of memory, and the
 // chip's reads at any moment are one moving window instead of thousands of separate streams.
-void launch_pack_weight_steps(const bf16_t* w, bf16_t* out, int N, int K, int ct, int perm, int perm_param, hipStream_t st);
+void launch_pack_weight_steps(const bf16_t* w, op_t* out, int N, int K, int ct, int perm, int perm_param, hipStream_t st);
 int gemm_bf16_steps_ct(int N, int K, int kind);  // ct of that layout for (N, K) under epilogue `kind`, 0 if the kernel that serves 16 rows has none
 int gemm_mid_steps_ct(int N, int K, int kind);   // ... if the mid kernel serves (N, K) at up to 16 rows without a K split, else 0
-void launch_pack_act(const bf16_t* x, bf16_t* out, int M, int K, hipStream_t st);  // row-major -> fragment tiles (rows padded to 16 with zeros)
+void launch_pack_act(const bf16_t* x, op_t* out, int M, int K, hipStream_t st);  // row-major bf16 -> fragment tiles in half (rows padded to 16 with zeros)
 int gemm_bf16_splits(int M, int N, int K, int kind);  // partial tiles [splits][M][N] the launch of this shape and epilogue needs in GemmEpi::part (1: none)
 int gemm_bf16_ssq_chunks(int M, int N, int K);     // chunks per row of the sums of squares an EPI_RESID launch of this shape writes
 int gemm_bf16_counters(int max_rows, int max_n);   // ticket counters a state needs in GemmEpi::counters (zero-initialised, self-resetting)
@@ -177,13 +182,13 @@ struct GemmEpi {
   f16_t *q, *kcache, *vcache;  // IEEE half (see f16_t)
   size_t slot_stride, head_stride;
   int n_q, n_kv, hd;
-  // EPI_SWIGLU (weights packed with PERM_GATED): act is written as a pair of planes (tile_index_pair)
-  bf16_t* act;
+  // EPI_SWIGLU (weights packed with PERM_GATED): act in fragment tiles
+  op_t* act;
   int ffn;
-  // EPI_RESID (the GEMM's input xt is a pair of planes): h += y; x = h * gain (fragment tiles, one plane); ssq_out[m][gemm_bf16_ssq_chunks(M, N, K)] = each column tile's share of sum h^2
+  // EPI_RESID: h += y; x = h * gain (fragment tiles); ssq_out[m][gemm_bf16_ssq_chunks(M, N, K)] = each column tile's share of sum h^2
   float* h;
   const float* gain;
-  bf16_t* x;
+  op_t* x;
   float* ssq_out;
   // EPI_DIRECT (bf16) / EPI_SUM (either)
   bf16_t* out_bf16;
@@ -194,7 +199,7 @@ struct GemmEpi {
   void* stat_parts;
   int skip_col;
   // optional second copy of W in the step-major layout (launch_pack_weight_steps) of column groups of w_steps_ct tiles
-  const bf16_t* w_steps;
+  const op_t* w_steps;
   int w_steps_ct;
 };
 constexpr int GEMM_STATS_MAX_ROWS = 64;
@@ -211,25 +216,25 @@ extern thread_local LaunchStamp g_launch_stamp;
     hipExtLaunchKernelGGL((kernel), dim3(grid), dim3(block), (unsigned)(lds), (st), ls_.start, ls_.stop, 0, __VA_ARGS__);       \
   } while (0)
 // Y = X * W^T.  xt: fragment-tiled [Mpad, K]; wt: weights [N, K] as packed by launch_pack_weight.
-void launch_gemm_bf16(const bf16_t* xt, const bf16_t* wt, int M, int N, int K, const GemmEpi& e, hipStream_t st);
+void launch_gemm_bf16(const op_t* xt, const op_t* wt, int M, int N, int K, const GemmEpi& e, hipStream_t st);
 #define GEMM_SKINNY_MAX_ROWS 64
-void launch_gemm_skinny(const bf16_t* xt, const bf16_t* wt, int pr, int M, int N, int K, const GemmEpi& e, hipStream_t st);  // M <= GEMM_SKINNY_MAX_ROWS
-void launch_gemm_tiled(const bf16_t* xt, const bf16_t* wt, int M, int N, int K, const GemmEpi& e, hipStream_t st);
+void launch_gemm_skinny(const op_t* xt, const op_t* wt, int pr, int M, int N, int K, const GemmEpi& e, hipStream_t st);  // M <= GEMM_SKINNY_MAX_ROWS
+void launch_gemm_tiled(const op_t* xt, const op_t* wt, int M, int N, int K, const GemmEpi& e, hipStream_t st);
 #define GEMM_MID_MAX_ROWS 160  // 65 .. this many rows: the mid kernel (all rows in one workgroup, wavefronts split K)
-#define GEMM_MID_MAX_ROWS_NARROW 256  // ... for matrices of at most 8192 columns (EPI_RESID, whose X is a pair of planes: GEMM_MID_MAX_ROWS)
+#define GEMM_MID_MAX_ROWS_NARROW 256  // ... for matrices of at most 8192 columns
 int gemm_mid_splits(int M, int N, int K, int kind);
 int gemm_mid_ssq_chunks(int M, int N, int K);
 bool gemm_mid_fills_chip(int M, int N, int K, int kind);  // its column groups are a whole number of rounds over the compute units, without a K split
 int gemm_mid_counters(int max_n);
 void gemm_mid_set_target(int wgs);  // tuning: workgroups the K split aims at
-void launch_gemm_mid(const bf16_t* xt, const bf16_t* wt, int M, int N, int K, const GemmEpi& e, hipStream_t st);  // M <= GEMM_MID_MAX_ROWS(_NARROW); narrow matrices from 17 rows
+void launch_gemm_mid(const op_t* xt, const op_t* wt, int M, int N, int K, const GemmEpi& e, hipStream_t st);  // M <= GEMM_MID_MAX_ROWS(_NARROW); narrow matrices from 17 rows
 #define GEMM_MACRO_MIN_ROWS_NARROW 256  // more rows than this: the macro-tile kernel whatever the width
 int gemm_macro_ssq_chunks(int M, int N, int K);
 int gemm_macro_splits(int M, int N, int K, int kind);
 int gemm_macro_counters(int max_rows, int max_n);
 void gemm_macro_set_target(int wgs);  // tuning: workgroups the K split aims at
 void gemm_macro_set_penalty(int tile, double p);  // tuning: relative cost per product of tile candidate 0 .. 4 (256x256, 128x256, 128x128, 192x256, 256x192)
-void launch_gemm_macro(const bf16_t* xt, const bf16_t* wt, int M, int N, int K, const GemmEpi& e, hipStream_t st);
+void launch_gemm_macro(const op_t* xt, const op_t* wt, int M, int N, int K, const GemmEpi& e, hipStream_t st);
 void launch_gemm_f32(const float* x, const float* w, float* y, int M, int N, int K, RowScale rs, hipStream_t st);
 
 void launch_prepare(const SeqMeta& meta, const StatsMeta& sm, RowTables t, int rows, int vocab, int head_dim, float theta, hipStream_t st);
@@ -237,7 +242,7 @@ void launch_prepare(const SeqMeta& meta, const StatsMeta& sm, RowTables t, int r
 // following GEMM multiplies rsqrt(sum(ssq)/d + eps) back in (a per-row scalar commutes with the GEMM).
 int norm_chunks(int d);
 template <typename T>
-void launch_embed_norm(const T* embed, const int32_t* tokens, const RowTables& t, const float* gain, float* h, T* x, float* ssq, int rows,
+void launch_embed_norm(const T* embed, const int32_t* tokens, const RowTables& t, const float* gain, float* h, typename Act<T>::x_t* x, float* ssq, int rows,
                        int d, int vocab, hipStream_t st);
 // h += sum_s part[s]; x = h * gain; ssq
 template <typename T>
@@ -255,10 +260,10 @@ void launch_rope_kv(const float* part, int splits, const float* ssq, int d, floa
 template <typename T>
 void launch_attention(const T* q, const T* kcache, const T* vcache, size_t slot_stride, size_t head_stride, const AttnMeta& meta, T* out,
                       bool out_tiled, int rows, int max_seq_rows, int n_q, int n_kv, int hd, hipStream_t st);
-// bf16 models: q and the KV cache hold IEEE half; out_pair: the output goes to the pair-of-planes activation layout [rows, n_q*hd]
-// (the O projection's input), else row-major bf16
+// bf16 models: q and the KV cache hold IEEE half; the output goes to out_tiles (fragment tiles [rows, n_q*hd] in half: the O
+// projection's input) if that is given, else to out_rows (row-major bf16)
 void launch_attention_f16(const f16_t* q, const f16_t* kcache, const f16_t* vcache, size_t slot_stride, size_t head_stride, const AttnMeta& meta,
-                          bf16_t* out, bool out_pair, int rows, int max_seq_rows, int n_q, int n_kv, int hd, hipStream_t st);
+                          op_t* out_tiles, bf16_t* out_rows, int rows, int max_seq_rows, int n_q, int n_kv, int hd, hipStream_t st);
 // test helper of dlm_attention: K, V [T, n_kv, hd] row-major bf16 -> the tiled half-precision cache layout of one slot; q -> half
 void launch_pack_kv(const bf16_t* k, const bf16_t* v, f16_t* kt, f16_t* vt, int T, int n_kv, int hd, size_t head_stride, hipStream_t st);
 void launch_to_f16(const bf16_t* src, f16_t* dst, size_t n, hipStream_t st);

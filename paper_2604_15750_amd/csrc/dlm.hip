@@ -161,7 +161,7 @@ int copy_gain(DevBuf& dst, const void* src, int n, int dtype, hipStream_t st) {
 int copy_matrix(DevBuf& dst, const void* src, int N, int K, int dtype, hipStream_t st, int perm = PERM_NONE, int perm_param = 0) {
   int rc = dst.alloc((size_t)N * K * elem_size(dtype));
   if (rc) return rc;
-  if (dtype == DLM_BF16) launch_pack_weight((const bf16_t*)src, (bf16_t*)dst.p, N, K, perm, perm_param, st);
+  if (dtype == DLM_BF16) launch_pack_weight((const bf16_t*)src, (op_t*)dst.p, N, K, perm, perm_param, st);
   else DLM_HIP(hipMemcpyAsync(dst.p, src, (size_t)N * K * 4, hipMemcpyDeviceToDevice, st));
   return DLM_OK;
 }
@@ -231,7 +231,7 @@ extern "C" int dlm_model_create(const dlm_config* cfg, const dlm_weights* w, voi
         }
         m->w_steps[k][l].p = p;
         const void* src = k == 0 ? w->wqkv[l] : k == 1 ? w->wo[l] : k == 2 ? w->w_gate_up[l] : w->w_down[l];
-        launch_pack_weight_steps((const bf16_t*)src, (bf16_t*)p, shape[k][0], shape[k][1], m->steps_ct[k], shape[k][2], shape[k][3], st);
+        launch_pack_weight_steps((const bf16_t*)src, (op_t*)p, shape[k][0], shape[k][1], m->steps_ct[k], shape[k][2], shape[k][3], st);
       }
     }
   }
@@ -281,10 +281,8 @@ extern "C" int dlm_state_create(const dlm_model* m, int max_seqs, int max_seq_le
   A(s->prev_lse, (size_t)max_seqs * 2 * look * 4);
   A(s->h, (size_t)max_rows * c.d_model * 4);
   A(s->x, (size_t)s->max_rows_pad * xw * es);
-  // a bf16 model keeps the inputs of the O and down projections as pairs of planes (tile_index_pair)
-  const size_t planes = c.dtype == DLM_BF16 ? PAIR_PLANES : 1;
-  A(s->x2, (size_t)s->max_rows_pad * xw * es * planes);
-  A(s->act, (size_t)s->max_rows_pad * c.d_ffn * es * planes);
+  A(s->x2, (size_t)s->max_rows_pad * xw * es);
+  A(s->act, (size_t)s->max_rows_pad * c.d_ffn * es);
   A(s->q, (size_t)max_rows * qd * es);
   A(s->part, pe * 4);
   size_t stats_bytes = stats_workspace_bytes(max_rows);
@@ -311,8 +309,8 @@ extern "C" int dlm_state_create(const dlm_model* m, int max_seqs, int max_seq_le
     hipError_t e = hipMemset(s->x.p, 0, (size_t)s->max_rows_pad * xw * es);
     if (e == hipSuccess) e = hipMemset(s->kcache.p, 0, s->layer_stride * c.n_layers * es);
     if (e == hipSuccess) e = hipMemset(s->vcache.p, 0, s->layer_stride * c.n_layers * es);
-    if (e == hipSuccess) e = hipMemset(s->x2.p, 0, (size_t)s->max_rows_pad * xw * es * planes);
-    if (e == hipSuccess) e = hipMemset(s->act.p, 0, (size_t)s->max_rows_pad * c.d_ffn * es * planes);
+    if (e == hipSuccess) e = hipMemset(s->x2.p, 0, (size_t)s->max_rows_pad * xw * es);
+    if (e == hipSuccess) e = hipMemset(s->act.p, 0, (size_t)s->max_rows_pad * c.d_ffn * es);
     if (e == hipSuccess) e = hipMemset(s->counters.p, 0, (size_t)n_counters * 4);
     if (e != hipSuccess) rc = dlm_fail(DLM_EHIP, "dlm_state_create: hipMemset: %s", hipGetErrorString(e));
   }
@@ -440,7 +438,7 @@ int run_step_bf16(dlm_state* s, const dlm_step_desc* d, const SeqMeta& meta, con
   RowTables t{(int32_t*)s->row_seq.p, (int32_t*)s->row_pos.p, (int32_t*)s->row_tok.p, (int32_t*)s->row_slot.p, (float*)s->rope_cos.p, (float*)s->rope_sin.p,
               (int64_t*)s->prev_row.p, (int64_t*)s->save_row.p};
   float* h = (float*)s->h.p;
-  T *x = (T*)s->x.p, *x2 = (T*)s->x2.p, *act = (T*)s->act.p;
+  op_t *x = (op_t*)s->x.p, *x2 = (op_t*)s->x2.p, *act = (op_t*)s->act.p;  // GEMM inputs: IEEE half in fragment tiles (common.h)
   f16_t* q = (f16_t*)s->q.p;  // Q and the KV cache hold IEEE half (common.h)
   float* ssq = (float*)s->ssq.p;
   Profile& pf = s->prof;
@@ -455,9 +453,9 @@ int run_step_bf16(dlm_state* s, const dlm_step_desc* d, const SeqMeta& meta, con
       if ((size_t)gemm_bf16_splits(rows, sh[0], sh[1], sh[2]) * rows * sh[0] > s->part_elems)
         return dlm_fail(DLM_ECAPACITY, "dlm_step: split-K workspace too small for %d rows x %d columns", rows, sh[0]);
   }
-  auto gemm = [&](int cls, const T* a, const void* w, int N, int K, const GemmEpi& e) {
+  auto gemm = [&](int cls, const op_t* a, const void* w, int N, int K, const GemmEpi& e) {
     ProfScope ps(pf, st, cls);
-    launch_gemm_bf16(a, (const T*)w, rows, N, K, e, st);
+    launch_gemm_bf16(a, (const op_t*)w, rows, N, K, e, st);
   };
   {
     ProfScope ps(pf, st, PC_OTHER, 2);
@@ -476,16 +474,16 @@ int run_step_bf16(dlm_state* s, const dlm_step_desc* d, const SeqMeta& meta, con
       e.row_pos = t.row_pos; e.row_slot = t.row_slot; e.rope_cos = t.rope_cos; e.rope_sin = t.rope_sin;
       e.q = q; e.kcache = kc; e.vcache = vc; e.slot_stride = s->slot_stride; e.head_stride = s->head_stride;
       e.n_q = nq; e.n_kv = nkv; e.hd = hd;
-      if (m->steps_ct[0]) { e.w_steps = (const T*)m->w_steps[0][l].p; e.w_steps_ct = m->steps_ct[0]; }
+      if (m->steps_ct[0]) { e.w_steps = (const op_t*)m->w_steps[0][l].p; e.w_steps_ct = m->steps_ct[0]; }
       gemm(PC_QKV, x, m->wqkv[l].p, qd + 2 * nkv * hd, dm, e);
     }
     { ProfScope ps(pf, st, PC_ATTENTION);
-      launch_attention_f16(q, kc, vc, s->slot_stride, s->head_stride, am, x2, true, rows, max_seq_rows, nq, nkv, hd, st); }
+      launch_attention_f16(q, kc, vc, s->slot_stride, s->head_stride, am, x2, nullptr, rows, max_seq_rows, nq, nkv, hd, st); }
     {
       GemmEpi e = base;
       e.kind = EPI_RESID;
       e.h = h; e.gain = (const float*)m->norm2[l].p; e.x = x; e.ssq_out = ssq;
-      if (m->steps_ct[1]) { e.w_steps = (const T*)m->w_steps[1][l].p; e.w_steps_ct = m->steps_ct[1]; }
+      if (m->steps_ct[1]) { e.w_steps = (const op_t*)m->w_steps[1][l].p; e.w_steps_ct = m->steps_ct[1]; }
       gemm(PC_O, x2, m->wo[l].p, dm, qd, e);
       nch = gemm_bf16_ssq_chunks(rows, dm, qd);
     }
@@ -494,7 +492,7 @@ int run_step_bf16(dlm_state* s, const dlm_step_desc* d, const SeqMeta& meta, con
       e.kind = EPI_SWIGLU;
       e.rs = RowScale{ssq, nch, 1.f / (float)dm, c.rms_eps};
       e.act = act; e.ffn = ffn;
-      if (m->steps_ct[2]) { e.w_steps = (const T*)m->w_steps[2][l].p; e.w_steps_ct = m->steps_ct[2]; }
+      if (m->steps_ct[2]) { e.w_steps = (const op_t*)m->w_steps[2][l].p; e.w_steps_ct = m->steps_ct[2]; }
       gemm(PC_GATE_UP, x, m->w_gate_up[l].p, 2 * ffn, dm, e);
     }
     {
@@ -502,7 +500,7 @@ int run_step_bf16(dlm_state* s, const dlm_step_desc* d, const SeqMeta& meta, con
       e.kind = EPI_RESID;
       e.h = h; e.gain = l + 1 < c.n_layers ? (const float*)m->norm1[l + 1].p : (const float*)m->final_norm.p;
       e.x = x; e.ssq_out = ssq;
-      if (m->steps_ct[3]) { e.w_steps = (const T*)m->w_steps[3][l].p; e.w_steps_ct = m->steps_ct[3]; }
+      if (m->steps_ct[3]) { e.w_steps = (const op_t*)m->w_steps[3][l].p; e.w_steps_ct = m->steps_ct[3]; }
       gemm(PC_DOWN, act, m->w_down[l].p, dm, ffn, e);
       nch = gemm_bf16_ssq_chunks(rows, dm, ffn);
     }
@@ -711,8 +709,8 @@ extern "C" int dlm_gemm_nt(const void* x, const void* w, void* y, int M, int N, 
   const size_t part_bytes = (size_t)gemm_bf16_splits(M, N, K, EPI_SUM) * M * N * 4;
   void* ws = nullptr;
   if (hipMalloc(&ws, tiled_bytes + part_bytes + (size_t)n_counters * 4) != hipSuccess) { (void)hipGetLastError(); return dlm_fail(DLM_ENOMEM, "dlm_gemm_nt: workspace allocation failed"); }
-  bf16_t* xt = (bf16_t*)ws;
-  bf16_t* wt = xt + mp * K;
+  op_t* xt = (op_t*)ws;
+  op_t* wt = xt + mp * K;
   float* part = (float*)((char*)ws + tiled_bytes);
   launch_pack_act((const bf16_t*)x, xt, M, K, st);
   launch_pack_weight((const bf16_t*)w, wt, N, K, PERM_NONE, 0, st);
@@ -758,7 +756,7 @@ extern "C" int dlm_attention(const void* q, const void* k, const void* v, void* 
   hipError_t e = hipMemsetAsync(ws, 0, 2 * bytes, st);
   launch_pack_kv((const bf16_t*)k, (const bf16_t*)v, kt, vt, T, n_kv, head_dim, head_stride, st);
   launch_to_f16((const bf16_t*)q, qh, q_elems, st);
-  launch_attention_f16(qh, kt, vt, 0, head_stride, am, (bf16_t*)out, false, A, A, n_q, n_kv, head_dim, st);
+  launch_attention_f16(qh, kt, vt, 0, head_stride, am, nullptr, (bf16_t*)out, A, A, n_q, n_kv, head_dim, st);
   if (e == hipSuccess) e = hipStreamSynchronize(st);
   (void)hipFree(ws);
   if (e != hipSuccess) return dlm_fail(DLM_EHIP, "dlm_attention: %s", hipGetErrorString(e));

@@ -1,6 +1,6 @@
 // Row-wise glue of the transformer pass: row tables and rotary tables, embedding + RMSNorm,
 // split-K reduction fused with residual add + RMSNorm, SiLU-gating, rotary embedding + KV-cache
-// write.  All fp32 arithmetic; bf16 outputs are written in the fragment tiling the GEMM reads.
+// write.  All fp32 arithmetic; a bf16 model's GEMM inputs are written in half precision, in the fragment tiling the GEMM reads.
 #include "common.h"
 
 namespace {
@@ -55,8 +55,8 @@ __device__ inline float row_rinv(const float* __restrict__ ssq, int r, int nch, 
 // grid (chunks, rows): h = embedding row, x = h * gain, ssq[row][chunk]
 template <typename T>
 __global__ __launch_bounds__(256) void embed_norm_kernel(const T* __restrict__ embed, const int32_t* __restrict__ tokens, RowTables t,
-                                                         const float* __restrict__ gain, float* __restrict__ h, T* __restrict__ x,
-                                                         float* __restrict__ ssq, int d, int vocab) {
+                                                         const float* __restrict__ gain, float* __restrict__ h,
+                                                         typename Act<T>::x_t* __restrict__ x, float* __restrict__ ssq, int d, int vocab) {
   __shared__ float buf[4];
   const int r = blockIdx.y, k = blockIdx.x * NORM_CHUNK + threadIdx.x * 4;
   // the token buffer is the caller's device memory, which the host cannot validate: an id outside the vocabulary is clamped
@@ -70,7 +70,7 @@ __global__ __launch_bounds__(256) void embed_norm_kernel(const T* __restrict__ e
     for (int i = 0; i < 4; ++i) v[i] = to_f32(e[k + i]);
     *(f32x4*)(h + (size_t)r * d + k) = v;
 #pragma unroll
-    for (int i = 0; i < 4; ++i) x[Act<T>::idx(r, k + i, d)] = from_f32<T>(v[i] * g[i]);
+    for (int i = 0; i < 4; ++i) x[Act<T>::idx(r, k + i, d)] = from_f32<typename Act<T>::x_t>(v[i] * g[i]);
     ss = v[0] * v[0] + v[1] * v[1] + v[2] * v[2] + v[3] * v[3];
   }
   ss = block_sum_256(ss, buf);
@@ -167,8 +167,8 @@ void launch_prepare(const SeqMeta& meta, const StatsMeta& sm, RowTables t, int r
 int norm_chunks(int d) { return (d + NORM_CHUNK - 1) / NORM_CHUNK; }
 
 template <typename T>
-void launch_embed_norm(const T* embed, const int32_t* tokens, const RowTables& t, const float* gain, float* h, T* x, float* ssq, int rows,
-                       int d, int vocab, hipStream_t st) {
+void launch_embed_norm(const T* embed, const int32_t* tokens, const RowTables& t, const float* gain, float* h, typename Act<T>::x_t* x, float* ssq,
+                       int rows, int d, int vocab, hipStream_t st) {
   embed_norm_kernel<T><<<dim3(norm_chunks(d), rows), 256, 0, st>>>(embed, tokens, t, gain, h, x, ssq, d, vocab);
 }
 template <typename T>
@@ -190,7 +190,7 @@ void launch_rope_kv(const float* part, int splits, const float* ssq, int d, floa
 
 // the row-wise glue kernels serve the fp32 model; a bf16 model runs them in its GEMM epilogues and uses only the embedding here
 template void launch_embed_norm<float>(const float*, const int32_t*, const RowTables&, const float*, float*, float*, float*, int, int, int, hipStream_t);
-template void launch_embed_norm<bf16_t>(const bf16_t*, const int32_t*, const RowTables&, const float*, float*, bf16_t*, float*, int, int, int, hipStream_t);
+template void launch_embed_norm<bf16_t>(const bf16_t*, const int32_t*, const RowTables&, const float*, float*, op_t*, float*, int, int, int, hipStream_t);
 template void launch_reduce_residual_norm<float>(const float*, int, float*, const float*, float*, float*, int, int, hipStream_t);
 template void launch_silu_mul<float>(const float*, int, const float*, int, float, float*, int, int, hipStream_t);
 template void launch_rope_kv<float>(const float*, int, const float*, int, float, const RowTables&, const SeqMeta&, float*, float*, float*, size_t,

@@ -1,9 +1,10 @@
-// bf16 GEMM  Y[M,N] = X[M,K] * W[N,K]^T  on the gfx950 matrix cores: operand tiling and the choice of kernel.
+// GEMM of a bf16 model  Y[M,N] = X[M,K] * W[N,K]^T  on the gfx950 matrix cores (operands in IEEE half, see op_t in common.h):
+// operand tiling and the choice of kernel.
 //
 // At decode shapes (M = 8 .. 384 rows against 15 GB of weights per pass) the GEMMs are bound by
 // streaming W from HBM, so both kernels are weight streamers that happen to multiply:
 //   * W is re-tiled once, when the model is created, into 1 KiB fragments (16 rows x 32 k) that are
-//     exactly the A operand of v_mfma_f32_16x16x32_bf16: a wavefront fetches a fragment as 64
+//     exactly the A operand of v_mfma_f32_16x16x32_f16: a wavefront fetches a fragment as 64
 //     consecutive 16-byte loads and walks a contiguous run of HBM along K; W goes HBM -> registers;
 //   * activations live in the same fragment tiling (B operand), written that way by their producer;
 //   * the product is computed transposed (W fragment = A operand), so a lane ends up with four
@@ -24,7 +25,14 @@
 namespace {
 
 // W [N, K] row-major -> fragment tiles, `pr` row-tiles interleaved along k, rows permuted by (perm, param).
-__global__ void pack_weight_kernel(const bf16x8* __restrict__ w, bf16x8* __restrict__ out, int N, int K, int pr, int perm, int param) {
+__device__ inline op8 to_op8(bf16x8 v) {
+  op8 r;
+#pragma unroll
+  for (int i = 0; i < 8; ++i) r[i] = to_f16_sat((float)v[i]);
+  return r;
+}
+
+__global__ void pack_weight_kernel(const bf16x8* __restrict__ w, op8* __restrict__ out, int N, int K, int pr, int perm, int param) {
   const int KT = K >> 5;
   const size_t total = (size_t)(N >> 4) * KT * 64;
   for (size_t idx = (size_t)blockIdx.x * blockDim.x + threadIdx.x; idx < total; idx += (size_t)gridDim.x * blockDim.x) {
@@ -36,11 +44,11 @@ __global__ void pack_weight_kernel(const bf16x8* __restrict__ w, bf16x8* __restr
     const int grp = rest / KT;
     const int n = weight_source_row((grp * pr + sub) * 16 + (lane & 15), perm, param);
     const int k8 = t * 4 + (lane >> 4);
-    out[idx] = w[(size_t)n * (K >> 3) + k8];
+    out[idx] = to_op8(w[(size_t)n * (K >> 3) + k8]);
   }
 }
 
-__global__ void pack_weight_steps_kernel(const bf16x8* __restrict__ w, bf16x8* __restrict__ out, int N, int K, int ct, int nwv, int perm, int param) {
+__global__ void pack_weight_steps_kernel(const bf16x8* __restrict__ w, op8* __restrict__ out, int N, int K, int ct, int nwv, int perm, int param) {
   const int KT = K >> 5, G = N / (16 * ct), per = KT / nwv;
   const size_t total = (size_t)(N >> 4) * KT * 64;
   for (size_t idx = (size_t)blockIdx.x * blockDim.x + threadIdx.x; idx < total; idx += (size_t)gridDim.x * blockDim.x) {
@@ -52,21 +60,21 @@ __global__ void pack_weight_steps_kernel(const bf16x8* __restrict__ w, bf16x8* _
     const int s = (int)(f / G);
     const int n = weight_source_row((grp * ct + r) * 16 + (lane & 15), perm, param);
     const int k8 = (wv * per + s) * 4 + (lane >> 4);
-    out[idx] = w[(size_t)n * (K >> 3) + k8];
+    out[idx] = to_op8(w[(size_t)n * (K >> 3) + k8]);
   }
 }
 
 // X [M, K] row-major -> fragment tiles [ceil(M/16)][K/32]; rows beyond M are zero.
-__global__ void pack_act_kernel(const bf16x8* __restrict__ x, bf16x8* __restrict__ out, int M, int K) {
+__global__ void pack_act_kernel(const bf16x8* __restrict__ x, op8* __restrict__ out, int M, int K) {
   const int KT = K >> 5;
   const size_t total = (size_t)((M + 15) >> 4) * KT * 64;
-  const bf16x8 zero8 = {0, 0, 0, 0, 0, 0, 0, 0};
+  const op8 zero8 = {0, 0, 0, 0, 0, 0, 0, 0};
   for (size_t idx = (size_t)blockIdx.x * blockDim.x + threadIdx.x; idx < total; idx += (size_t)gridDim.x * blockDim.x) {
     const int lane = idx & 63;
     const size_t tile = idx >> 6;
     const int t = tile % KT;
     const int m = (int)(tile / KT) * 16 + (lane & 15);
-    out[idx] = m < M ? x[(size_t)m * (K >> 3) + t * 4 + (lane >> 4)] : zero8;
+    out[idx] = m < M ? to_op8(x[(size_t)m * (K >> 3) + t * 4 + (lane >> 4)]) : zero8;
   }
 }
 
@@ -84,7 +92,6 @@ int choose_kernel(int M, int N, int K, int kind) {
   if (kind == EPI_STATS) return KERNEL_TILED;  // only the tiled kernel has that epilogue (the caller keeps to GEMM_STATS_MAX_ROWS rows)
   const int pr = weight_pack_rows(N);
   const bool whole_groups = N % (16 * pr) == 0;
-  const bool pair = kind == EPI_RESID;  // X is a pair of planes: twice the X fragments in the mid kernel's registers
   if (M <= GEMM_SKINNY_MAX_ROWS && kind != EPI_DIRECT && whole_groups) {
     if (pr == 2 && (M > 16 || gemm_mid_fills_chip(M, N, K, kind))) return KERNEL_MID;
     if (pr == 1 && M > 16 && K >= 8192) return KERNEL_MID;
@@ -93,19 +100,19 @@ int choose_kernel(int M, int N, int K, int kind) {
     if (pr == 1 && M <= 16 && (N >> 4) > 256 && (N >> 4) <= 384) return KERNEL_MID;
     return KERNEL_SKINNY;
   }
-  if (M > GEMM_SKINNY_MAX_ROWS && M <= (pr == 1 && !pair ? GEMM_MID_MAX_ROWS_NARROW : GEMM_MID_MAX_ROWS) && whole_groups) return KERNEL_MID;
-  // EPI_RESID has no instantiation of the tiled kernel (which stages one plane of X): what the mid kernel does not take goes to the macro kernel
-  if (M > GEMM_MACRO_MIN_ROWS_NARROW || (M > GEMM_SKINNY_MAX_ROWS && N > 8192) || pair) return KERNEL_MACRO;
+  if (M > GEMM_SKINNY_MAX_ROWS && M <= (pr == 1 ? GEMM_MID_MAX_ROWS_NARROW : GEMM_MID_MAX_ROWS) && whole_groups) return KERNEL_MID;
+  // EPI_RESID has no instantiation of the tiled kernel: what the mid kernel does not take goes to the macro kernel
+  if (M > GEMM_MACRO_MIN_ROWS_NARROW || (M > GEMM_SKINNY_MAX_ROWS && N > 8192) || kind == EPI_RESID) return KERNEL_MACRO;
   return KERNEL_TILED;
 }
 
 }  // namespace
 
-void launch_pack_weight(const bf16_t* w, bf16_t* out, int N, int K, int perm, int perm_param, hipStream_t st) {
-  pack_weight_kernel<<<2048, 256, 0, st>>>((const bf16x8*)w, (bf16x8*)out, N, K, weight_pack_rows(N), perm, perm_param);
+void launch_pack_weight(const bf16_t* w, op_t* out, int N, int K, int perm, int perm_param, hipStream_t st) {
+  pack_weight_kernel<<<2048, 256, 0, st>>>((const bf16x8*)w, (op8*)out, N, K, weight_pack_rows(N), perm, perm_param);
 }
-void launch_pack_weight_steps(const bf16_t* w, bf16_t* out, int N, int K, int ct, int perm, int perm_param, hipStream_t st) {
-  pack_weight_steps_kernel<<<2048, 256, 0, st>>>((const bf16x8*)w, (bf16x8*)out, N, K, ct, ct == 1 ? 8 : 4, perm, perm_param);
+void launch_pack_weight_steps(const bf16_t* w, op_t* out, int N, int K, int ct, int perm, int perm_param, hipStream_t st) {
+  pack_weight_steps_kernel<<<2048, 256, 0, st>>>((const bf16x8*)w, (op8*)out, N, K, ct, ct == 1 ? 8 : 4, perm, perm_param);
 }
 int gemm_bf16_steps_ct(int N, int K, int kind) {
   switch (choose_kernel(16, N, K, kind)) {
@@ -117,8 +124,8 @@ int gemm_bf16_steps_ct(int N, int K, int kind) {
     default: return 0;
   }
 }
-void launch_pack_act(const bf16_t* x, bf16_t* out, int M, int K, hipStream_t st) {
-  pack_act_kernel<<<512, 256, 0, st>>>((const bf16x8*)x, (bf16x8*)out, M, K);
+void launch_pack_act(const bf16_t* x, op_t* out, int M, int K, hipStream_t st) {
+  pack_act_kernel<<<512, 256, 0, st>>>((const bf16x8*)x, (op8*)out, M, K);
 }
 
 int gemm_bf16_splits(int M, int N, int K, int kind) {
@@ -143,7 +150,7 @@ int gemm_bf16_counters(int max_rows, int max_n) {
   return a > b ? (a > c ? a : c) : (b > c ? b : c);
 }
 
-void launch_gemm_bf16(const bf16_t* xt, const bf16_t* wt, int M, int N, int K, const GemmEpi& e, hipStream_t st) {
+void launch_gemm_bf16(const op_t* xt, const op_t* wt, int M, int N, int K, const GemmEpi& e, hipStream_t st) {
   switch (choose_kernel(M, N, K, e.kind)) {
     case KERNEL_SKINNY: launch_gemm_skinny(xt, wt, weight_pack_rows(N), M, N, K, e, st); break;
     case KERNEL_MID: launch_gemm_mid(xt, wt, M, N, K, e, st); break;

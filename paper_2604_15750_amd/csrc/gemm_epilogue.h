@@ -1,16 +1,11 @@
-// Epilogues of the bf16 GEMM kernels, on finished values in the accumulator layout of
-// v_mfma_f32_16x16x32_bf16 (transposed product): in a 16 x 16 output tile, lane ml + 16 g holds
+// Epilogues of a bf16 model's GEMM kernels, on finished values in the accumulator layout of
+// v_mfma_f32_16x16x32_f16 (transposed product): in a 16 x 16 output tile, lane ml + 16 g holds
 // columns 4g .. 4g+3 of row ml.
 #pragma once
 #include "common.h"
 
 __device__ inline bf16x4 to_bf16x4(f32x4 v) { return bf16x4{(bf16_t)v[0], (bf16_t)v[1], (bf16_t)v[2], (bf16_t)v[3]}; }
 __device__ inline f16x4 to_f16x4_sat(f32x4 v) { return f16x4{to_f16_sat(v[0]), to_f16_sat(v[1]), to_f16_sat(v[2]), to_f16_sat(v[3])}; }
-__device__ inline f32x4 widen4(bf16x4 v) { return f32x4{(float)v[0], (float)v[1], (float)v[2], (float)v[3]}; }
-
-// Planes of the GEMM's input X: the EPI_RESID GEMMs (O and down) read a pair (hi, lo) per fragment tile, the others one.
-template <int EPI>
-struct XPlanes { static constexpr int value = EPI == EPI_RESID ? PAIR_PLANES : 1; };
 
 // 1/rms of rows [m_lo, m_lo + rows) from the producer's partial sums of squares into s_rinv, by the whole workgroup of NT
 // threads: sixteen lanes per row, each adding every sixteenth chunk in ascending order, then a fixed butterfly
@@ -151,10 +146,7 @@ __device__ inline void finish_swiglu(const GemmEpi& e, int m, int nc, int gp, f3
   f32x4 a;
 #pragma unroll
   for (int t = 0; t < 4; ++t) a[t] = g[t] * __builtin_amdgcn_rcpf(1.f + __expf(-g[t])) * u[t];  // (the hardware reciprocal: 1 ulp)
-  const bf16x4 hi = to_bf16x4(a), lo = to_bf16x4(a - widen4(hi));  // the down projection's input: a pair of planes
-  const size_t o = tile_index_pair(m, 8 * (nc >> 4) + 4 * gp, e.ffn, 0);
-  *(bf16x4*)(e.act + o) = hi;
-  *(bf16x4*)(e.act + o + 512) = lo;
+  *(op4*)(e.act + tile_index(m, 8 * (nc >> 4) + 4 * gp, e.ffn)) = to_f16x4_sat(a);
 }
 
 // residual add and next norm's x for columns n .. n+3 of row m; returns the four columns' share of sum h^2
@@ -164,7 +156,7 @@ __device__ inline float finish_resid(const GemmEpi& e, int m, int n, int N, f32x
   const f32x4 v = (pre ? ahead.a : *(const f32x4*)(e.h + o)) + y;
   *(f32x4*)(e.h + o) = v;
   const f32x4 g = pre ? ahead.b : *(const f32x4*)(e.gain + n);
-  *(bf16x4*)(e.x + tile_index(m, n, N)) = to_bf16x4(v * g);
+  *(op4*)(e.x + tile_index(m, n, N)) = to_f16x4_sat(v * g);
   return v[0] * v[0] + v[1] * v[1] + v[2] * v[2] + v[3] * v[3];
 }
 

@@ -1,4 +1,4 @@
-// Macro-tile bf16 GEMM for wide passes (M > 256 rows: batched decoding, prefill): Y[M,N] = X[M,K] * W[N,K]^T,
+// Macro-tile GEMM of a bf16 model for wide passes (M > 256 rows: batched decoding, prefill): Y[M,N] = X[M,K] * W[N,K]^T,
 // fp32 accumulation, epilogue fused.
 //
 // Beyond a few hundred rows the GEMMs leave the weight-streaming regime and are bound by the matrix
@@ -37,12 +37,11 @@ __device__ inline __amdgpu_buffer_rsrc_t part_rsrc(const float* base) {
 #define GLOBAL_PTR(p) ((const void __attribute__((address_space(1)))*)(p))
 #define LDS_PTR(p) ((void __attribute__((address_space(3)))*)(p))
 
-// XP: planes of X (the EPI_RESID GEMMs read a pair per fragment tile)
-template <int WM, int WN, int XP = 1, int NW = 4, bool TWO = false>
+template <int WM, int WN, int NW = 4, bool TWO = false>
 struct MacroShape {
   static constexpr int TPB = NW * 64;
   static constexpr int AT = (NW / 2) * WM;         // row tiles of the workgroup
-  static constexpr int AF = AT * XP, BF = 2 * WN;  // X (row tiles x planes) and W (column) fragments of a stage
+  static constexpr int AF = AT, BF = 2 * WN;       // X (row) and W (column) fragments of a stage
   static constexpr int NFR = AF + BF;
   static constexpr int LPS = (NFR + NW - 1) / NW;  // direct-to-LDS loads per wavefront and stage (surplus ones repeat the last fragment)
   static constexpr int STAGE = NFR * 1024;
@@ -53,10 +52,9 @@ struct MacroShape {
 };
 
 template <int WM, int WN, int PR, int EPI, int NW = 4, bool TWO = false>
-__global__ __launch_bounds__(NW * 64, TWO ? 2 : 1) void gemm_macro_kernel(const bf16x8* __restrict__ xt, const bf16x8* __restrict__ wt, int M, int N,
+__global__ __launch_bounds__(NW * 64, TWO ? 2 : 1) void gemm_macro_kernel(const op8* __restrict__ xt, const op8* __restrict__ wt, int M, int N,
                                                                           int K, int nblocks, int mblocks, int splits, int kt_per_split, GemmEpi e) {
-  constexpr int XP = XPlanes<EPI>::value;
-  typedef MacroShape<WM, WN, XP, NW, TWO> SH;
+  typedef MacroShape<WM, WN, NW, TWO> SH;
   constexpr int TPB = SH::TPB, AT = SH::AT, AF = SH::AF, BF = SH::BF, LPS = SH::LPS, STAGE = SH::STAGE, S = SH::S;
   static_assert(AF % NW == 0 && S >= 3 && (S - 2) * LPS < 64, "pipeline shape");
   extern __shared__ __align__(16) unsigned char lds[];
@@ -77,7 +75,7 @@ __global__ __launch_bounds__(NW * 64, TWO ? 2 : 1) void gemm_macro_kernel(const 
   const int KT = K >> 5, MTILES = (M + 15) >> 4, NT = N >> 4;
   const int mt0 = rb * AT, nt0 = cb * BF;
 
-  // stage kt % S <- k-tile kt: fragment f (f < AF: plane f % XP of X row tile mt0 + f / XP, else W column tile nt0 + f - AF) is
+  // stage kt % S <- k-tile kt: fragment f (f < AF: X row tile mt0 + f, else W column tile nt0 + f - AF) is
   // moved by wavefront f % NW
   const int kb = split * kt_per_split, nk = min(KT, kb + kt_per_split) - kb;  // this workgroup's k-tiles: kb .. kb + nk - 1
   auto issue = [&](int kt) {
@@ -86,10 +84,10 @@ __global__ __launch_bounds__(NW * 64, TWO ? 2 : 1) void gemm_macro_kernel(const 
 #pragma unroll
     for (int i = 0; i < LPS; ++i) {
       const int f = i * NW + wave;
-      const bf16x8* src;
+      const op8* src;
       if (i < AF / NW) {
-        const int mt = min(mt0 + f / XP, MTILES - 1);
-        src = xt + (((size_t)mt * KT + t) * XP + f % XP) * 64 + lane;
+        const int mt = min(mt0 + f, MTILES - 1);
+        src = xt + ((size_t)mt * KT + t) * 64 + lane;
       } else {
         const int fw = min(f - AF, BF - 1);  // a wavefront without a fragment of its own in the last round moves the last one again
         const int nt = min(nt0 + fw, NT - 1);
@@ -106,11 +104,11 @@ __global__ __launch_bounds__(NW * 64, TWO ? 2 : 1) void gemm_macro_kernel(const 
   for (int j = 0; j < WN; ++j)
 #pragma unroll
     for (int i = 0; i < WM; ++i) acc[j][i] = f32x4{0.f, 0.f, 0.f, 0.f};
-  bf16x8 xf[2][WM * XP], wf[2][WN];
+  op8 xf[2][WM], wf[2][WN];
   auto read_frags = [&](int buf, int kt) {
-    const bf16x8* st = (const bf16x8*)(lds + (kt % S) * STAGE) + lane;
+    const op8* st = (const op8*)(lds + (kt % S) * STAGE) + lane;
 #pragma unroll
-    for (int i = 0; i < WM * XP; ++i) xf[buf][i] = st[(wm * WM * XP + i) * 64];
+    for (int i = 0; i < WM; ++i) xf[buf][i] = st[(wm * WM + i) * 64];
 #pragma unroll
     for (int j = 0; j < WN; ++j) wf[buf][j] = st[(AF + wn * WN + j) * 64];
   };
@@ -118,7 +116,7 @@ __global__ __launch_bounds__(NW * 64, TWO ? 2 : 1) void gemm_macro_kernel(const 
 #pragma unroll
     for (int j = 0; j < WN; ++j)
 #pragma unroll
-      for (int i = 0; i < WM * XP; ++i) acc[j][i / XP] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(wf[buf][j], xf[buf][i], acc[j][i / XP], 0, 0, 0);
+      for (int i = 0; i < WM; ++i) acc[j][i] = mfma_op(wf[buf][j], xf[buf][i], acc[j][i]);
   };
 
   // 1/rms of the workgroup's input rows, needed only by the epilogue: fetched before the pipeline starts (its loads are counted
@@ -146,7 +144,7 @@ __global__ __launch_bounds__(NW * 64, TWO ? 2 : 1) void gemm_macro_kernel(const 
     // Issue order, fixed by hand: the products (which depend on registers only) start right behind the barrier, and the copies
     // and the LDS reads of the next k-tile go out between them.  Left alone, the scheduler puts the reads next to their uses,
     // and all wavefronts of a SIMD, which leave the barrier together, would issue their loads while its matrix core idles.
-    constexpr int NM = WN * WM * XP, RF = WM * XP + WN;
+    constexpr int NM = WN * WM, RF = WM + WN;
     constexpr int OPS = 2 * (LPS + RF) <= NM ? 1 : 2;  // copies / reads per product: all of them go out in the first half of the products,
                                                         // so that the last read has the second half's time to return
 #pragma unroll
@@ -277,31 +275,26 @@ struct MacroPlan {
 };
 
 // the tile with the least estimated time: rounds of workgroups over the chip x products per workgroup, each tile charged
-// for what it fetches per product (measured: see penalty)
+// for what it fetches per product (measured: see penalty), plus the partial-tile traffic of a K split
 int g_macro_wgs = 256;  // workgroups a K split aims at
 constexpr int NCAND = 5;
 // time of a round of workgroups over the chip / tile area, relative to 128 x 256 with four wavefronts (measured on the layer
-// matrices of an 8B model with random operand values; the second row: X as a pair of planes)
+// matrices of an 8B model with random operand values)
 double g_macro_penalty[NCAND] = {0.63, 1.0, 1.21, 0.86, 0.72};
-double g_macro_penalty_pair[3] = {0.84, 1.0, 1.12};
 // A four-wavefront tile of single planes that needs two or more rounds runs as two workgroups per compute unit, three stages
 // each: the pair hides each other's barriers, waits and output stores and takes 1.45 of one deep workgroup's time instead of 2;
 // the odd round's workgroups run at about the deep variant's pace (measured at 256 .. 2048 rows, operands of random values:
-// constant ones let the chip clock higher and flatter the large tiles).  Tiles of plane pairs,
-// bound by what they fetch, lose more from three stages than the sharing returns and stay as they are.
+// constant ones let the chip clock higher and flatter the large tiles).
 double g_macro_shared_pair[NCAND] = {0, 1.45, 1.45, 0, 0}, g_macro_shared_single[NCAND] = {0, 1.15, 0.9, 0, 0};
-double g_macro_split_cost = 328.0;
+double g_macro_us_per_mac = 6.2e-7;  // a round of 128 x 256 tiles over the chip: microseconds per element of the tile and column of K
 
-MacroPlan macro_plan(int M, int N, int K, bool may_split, int kind) {
-  // {WM, WN, wavefronts}: 256 x 256, 128 x 256, 128 x 128, 192 x 256, 256 x 192; when X is a pair of planes (EPI_RESID) the eight
-  // wavefronts take 128 x 256 (two row tiles each, both planes: the same fetch per product as 256 x 256 of single planes) and
-  // the 192-row tile is left out (its stages no longer fit LDS four deep)
-  const bool pair = kind == EPI_RESID;
-  const int cand[NCAND][3] = {{pair ? 2 : 4, 8, 8}, {4, 8, 4}, {4, 4, 4}, {6, 8, 4}, {4, 6, 8}};
+MacroPlan macro_plan(int M, int N, int K, bool may_split) {
+  // {WM, WN, wavefronts}: 256 x 256, 128 x 256, 128 x 128, 192 x 256, 256 x 192
+  const int cand[NCAND][3] = {{4, 8, 8}, {4, 8, 4}, {4, 4, 4}, {6, 8, 4}, {4, 6, 8}};
   MacroPlan best{4, 8, 4, 1, 1, 1, 0, false};
   double best_cost = 1e300;
-  const int ncand = pair ? 3 : NCAND, KT = K >> 5;
-  for (int c = 0; c < ncand; ++c) {
+  const int KT = K >> 5;
+  for (int c = 0; c < NCAND; ++c) {
     const int bm = 8 * cand[c][2] * cand[c][0], bn = 32 * cand[c][1];
     const int mb = (M + bm - 1) / bm, nb = (N + bn - 1) / bn, tiles = mb * nb;
     // tiles that cover at most half of the chip (narrow matrices at a few hundred rows): split K until they cover it
@@ -312,64 +305,60 @@ MacroPlan macro_plan(int M, int N, int K, bool may_split, int kind) {
     const int kps = (KT + sp - 1) / sp;
     sp = (KT + kps - 1) / kps;  // no empty split
     const int rounds = (tiles * sp + 255) / 256;
-    const bool two = !pair && g_macro_shared_pair[c] > 0 && rounds >= 2;
+    const bool two = g_macro_shared_pair[c] > 0 && rounds >= 2;
     const double turns = two ? (rounds / 2) * g_macro_shared_pair[c] + (rounds & 1) * g_macro_shared_single[c] : rounds;
-    // a split workgroup does 1 / sp of the products, and writes and re-reads partial tiles: about g_macro_split_cost columns of K each
-    const double share = 1.0 / sp + (sp > 1 ? g_macro_split_cost * sp / K : 0.0);
-    const double cost = turns * bm * bn * (pair ? g_macro_penalty_pair[c] : g_macro_penalty[c]) * share;
+    // microseconds: the rounds' products, 1 / sp of K each; a split launch also writes and re-reads one partial tile (8 bytes per
+    // element) per workgroup, at about 2.5 TB/s over the chip
+    const double cost = turns * bm * bn * g_macro_penalty[c] * K * g_macro_us_per_mac / sp + (sp > 1 ? (double)tiles * sp * bm * bn * 3.2e-6 : 0.0);
     if (cost < best_cost) { best_cost = cost; best = MacroPlan{cand[c][0], cand[c][1], cand[c][2], nb, mb, sp, kps, two}; }
   }
   return best;
 }
 
 template <int WM, int WN, int NW, int PR, int EPI, bool TWO = false>
-void launch_one(const bf16_t* xt, const bf16_t* wt, int M, int N, int K, const MacroPlan& p, const GemmEpi& e, hipStream_t st) {
-  typedef MacroShape<WM, WN, XPlanes<EPI>::value, NW, TWO> SH;
+void launch_one(const op_t* xt, const op_t* wt, int M, int N, int K, const MacroPlan& p, const GemmEpi& e, hipStream_t st) {
+  typedef MacroShape<WM, WN, NW, TWO> SH;
   static bool configured = false;  // raise the dynamic LDS limit of this instantiation once
   if (!configured) {
     (void)hipFuncSetAttribute((const void*)gemm_macro_kernel<WM, WN, PR, EPI, NW, TWO>, hipFuncAttributeMaxDynamicSharedMemorySize, SH::LDS_BYTES);
     configured = true;
   }
   const int grid = (p.nblocks + 7) / 8 * 8 * p.mblocks * p.splits;
-  DLM_LAUNCH((gemm_macro_kernel<WM, WN, PR, EPI, NW, TWO>), grid, SH::TPB, SH::LDS_BYTES, st, (const bf16x8*)xt, (const bf16x8*)wt, M, N, K, p.nblocks,
+  DLM_LAUNCH((gemm_macro_kernel<WM, WN, PR, EPI, NW, TWO>), grid, SH::TPB, SH::LDS_BYTES, st, (const op8*)xt, (const op8*)wt, M, N, K, p.nblocks,
              p.mblocks, p.splits, p.kps, e);
 }
 
 template <int PR, int EPI>
-void launch_shape(const bf16_t* xt, const bf16_t* wt, int M, int N, int K, const MacroPlan& p, const GemmEpi& e, hipStream_t st) {
-  constexpr bool pair = EPI == EPI_RESID;
-  if (p.nw == 8 && p.wn == 6) { if constexpr (!pair) launch_one<4, 6, 8, PR, EPI>(xt, wt, M, N, K, p, e, st); }
-  else if (p.nw == 8) launch_one<(pair ? 2 : 4), 8, 8, PR, EPI>(xt, wt, M, N, K, p, e, st);
-  else if (p.wm == 6) { if constexpr (!pair) launch_one<6, 8, 4, PR, EPI>(xt, wt, M, N, K, p, e, st); }
+void launch_shape(const op_t* xt, const op_t* wt, int M, int N, int K, const MacroPlan& p, const GemmEpi& e, hipStream_t st) {
+  if (p.nw == 8 && p.wn == 6) launch_one<4, 6, 8, PR, EPI>(xt, wt, M, N, K, p, e, st);
+  else if (p.nw == 8) launch_one<4, 8, 8, PR, EPI>(xt, wt, M, N, K, p, e, st);
+  else if (p.wm == 6) launch_one<6, 8, 4, PR, EPI>(xt, wt, M, N, K, p, e, st);
   else if (p.two) {
-    if constexpr (!pair) {
-      if (p.wn == 8) launch_one<4, 8, 4, PR, EPI, true>(xt, wt, M, N, K, p, e, st);
-      else launch_one<4, 4, 4, PR, EPI, true>(xt, wt, M, N, K, p, e, st);
-    }
+    if (p.wn == 8) launch_one<4, 8, 4, PR, EPI, true>(xt, wt, M, N, K, p, e, st);
+    else launch_one<4, 4, 4, PR, EPI, true>(xt, wt, M, N, K, p, e, st);
   }
   else if (p.wn == 8) launch_one<4, 8, 4, PR, EPI>(xt, wt, M, N, K, p, e, st);
   else launch_one<4, 4, 4, PR, EPI>(xt, wt, M, N, K, p, e, st);
 }
 
 template <int EPI>
-void launch_epi(const bf16_t* xt, const bf16_t* wt, int M, int N, int K, const MacroPlan& p, const GemmEpi& e, hipStream_t st) {
+void launch_epi(const op_t* xt, const op_t* wt, int M, int N, int K, const MacroPlan& p, const GemmEpi& e, hipStream_t st) {
   if (weight_pack_rows(N) == 2) launch_shape<2, EPI>(xt, wt, M, N, K, p, e, st);
   else launch_shape<1, EPI>(xt, wt, M, N, K, p, e, st);
 }
 
 }  // namespace
 
-int gemm_macro_ssq_chunks(int M, int N, int K) { return macro_plan(M, N, K, true, EPI_RESID).nblocks; }  // (the plan of the launch itself)
-int gemm_macro_splits(int M, int N, int K, int kind) { return macro_plan(M, N, K, true, kind).splits; }
+int gemm_macro_ssq_chunks(int M, int N, int K) { return macro_plan(M, N, K, true).nblocks; }  // (the plan of the launch itself)
+int gemm_macro_splits(int M, int N, int K, int) { return macro_plan(M, N, K, true).splits; }
 int gemm_macro_counters(int max_rows, int max_n) { return ((max_n + 127) / 128) * ((max_rows + 127) / 128); }  // 128 x 128 tiles are the smallest
 void gemm_macro_set_target(int wgs) { g_macro_wgs = wgs; }
 void gemm_macro_set_penalty(int tile, double p) {
   if (tile >= 0 && tile < NCAND) g_macro_penalty[tile] = p;
-  if (tile >= 0 && tile < 3) g_macro_penalty_pair[tile] = p;
 }
 
-void launch_gemm_macro(const bf16_t* xt, const bf16_t* wt, int M, int N, int K, const GemmEpi& e, hipStream_t st) {
-  const MacroPlan p = macro_plan(M, N, K, e.kind != EPI_DIRECT, e.kind);  // EPI_DIRECT has no workspace
+void launch_gemm_macro(const op_t* xt, const op_t* wt, int M, int N, int K, const GemmEpi& e, hipStream_t st) {
+  const MacroPlan p = macro_plan(M, N, K, e.kind != EPI_DIRECT);  // EPI_DIRECT has no workspace
   switch (e.kind) {
     case EPI_QKV: launch_epi<EPI_QKV>(xt, wt, M, N, K, p, e, st); break;
     case EPI_SWIGLU: launch_epi<EPI_SWIGLU>(xt, wt, M, N, K, p, e, st); break;

@@ -1,4 +1,4 @@
-// Mid-size bf16 GEMM (65 .. 160 rows: a block plus its look-ahead window, a few packed blocks; fewer rows where its wide
+// Mid-size GEMM of a bf16 model (65 .. 160 rows: a block plus its look-ahead window, a few packed blocks; fewer rows where its wide
 // column groups pay, see choose_kernel in gemm_bf16.hip):
 // Y[M,N] = X[M,K] * W[N,K]^T, fp32 accumulation, epilogue fused.
 //
@@ -38,15 +38,13 @@ __device__ inline __amdgpu_buffer_rsrc_t part_rsrc(const float* base) {
   return __builtin_amdgcn_make_buffer_rsrc((void*)base, 0, 0x7fffffff, 0x00020000);
 }
 
-// XP: planes of X (the EPI_RESID GEMMs read a pair per fragment tile: XF = MT * XP X fragments per k-tile)
-template <int MT, int CT, int XP = 1>
+template <int MT, int CT>
 struct MidShape {
-  static constexpr int XF = MT * XP;
   static constexpr int KB = CT <= 3 ? 2 : 1;  // k-tiles per step: narrow column groups take two, so that a step's loads are still 6 KiB of W
   // steps of W per register ring (one in use, the others in flight): as many as fit beside the accumulators and two steps of
   // X in about 370 registers, and whose loads the memory counter can count; 3 .. MID_WD_MAX
-  static constexpr int WD_FIT = (92 - CT * MT - 2 * KB * XF) / (KB * CT);
-  static constexpr int WD_CNT = (63 / KB - XF) / CT + 1;
+  static constexpr int WD_FIT = (92 - CT * MT - 2 * KB * MT) / (KB * CT);
+  static constexpr int WD_CNT = (63 / KB - MT) / CT + 1;
   static constexpr int WD_ = WD_FIT < WD_CNT ? WD_FIT : WD_CNT;
   static constexpr int WD = WD_ < 3 ? 3 : WD_ > MID_WD_MAX ? MID_WD_MAX : WD_;
   static constexpr int TRIP = WD % 2 ? 2 * WD : WD;  // steps after which both the W ring and the two X sets are back where they started
@@ -61,13 +59,12 @@ struct MidShape {
 // grid.x = groups * splits; MT >= ceil(M / 16), and X has MT row tiles (the activation buffers are padded to 16 rows).
 // STEPS: W is read from the step-major copy (e.w_steps) instead of wt.
 template <int MT, int CT, int PR, int EPI, bool STEPS = false>
-__global__ __launch_bounds__(TPB) void gemm_mid_kernel(const bf16x8* __restrict__ xt, const bf16x8* __restrict__ wt, int M, int N, int K,
+__global__ __launch_bounds__(TPB) void gemm_mid_kernel(const op8* __restrict__ xt, const op8* __restrict__ wt, int M, int N, int K,
                                                        int kt_per_split, int splits, GemmEpi e) {
-  constexpr int XP = XPlanes<EPI>::value, XF = MT * XP;
-  typedef MidShape<MT, CT, XP> SH;
+  typedef MidShape<MT, CT> SH;
   constexpr int F = SH::F, FW = SH::FW, FR = SH::FR, ROUNDS = SH::ROUNDS;
   constexpr int KB = SH::KB, WD = SH::WD, TRIP = SH::TRIP;
-  static_assert(KB * (XF + (WD - 1) * CT) < 64, "the loads in flight must fit the memory counter");
+  static_assert(KB * (MT + (WD - 1) * CT) < 64, "the loads in flight must fit the memory counter");
   extern __shared__ __align__(16) unsigned char lds[];
   __shared__ int s_last;
   float* s_rinv = (float*)(lds + SH::BODY);  // [MT * 16]
@@ -87,26 +84,26 @@ __global__ __launch_bounds__(TPB) void gemm_mid_kernel(const bf16x8* __restrict_
   constexpr bool steps = STEPS;
   const size_t wstep = steps ? (size_t)groups * NWV * CT * 64 : (PR == 2 ? 128 : 64);
   const int tsub = steps ? t0 : 0;
-  const bf16x8* wptr[CT];
+  const op8* wptr[CT];
 #pragma unroll
   for (int r = 0; r < CT; ++r) {
     const int nt = min(nt0 + r, NT - 1);
-    wptr[r] = steps ? (const bf16x8*)e.w_steps + ((size_t)(group * NWV + wave) * CT + r) * 64 + lane
+    wptr[r] = steps ? (const op8*)e.w_steps + ((size_t)(group * NWV + wave) * CT + r) * 64 + lane
                     : PR == 2 ? wt + ((size_t)(nt >> 1) * KT * 2 + (nt & 1)) * 64 + lane : wt + (size_t)nt * KT * 64 + lane;
   }
-  const bf16x8* xptr = xt + lane;  // plane p of fragment (j, t) = xptr[((j * KT + t) * XP + p) * 64]
+  const op8* xptr = xt + lane;  // fragment (j, t) = xptr[(j * KT + t) * 64]
   // In the last row tile, lanes whose row does not exist re-read row 0 of their k-group instead of fetching lines of their
   // own (a fragment's 128-byte lines hold 8 rows each: a block of 8 rows reads half of them); what they get is never stored.
-  const bf16x8* xptr_last = xt + ((MT - 1) * 16 + (lane & 15) < M ? lane : (lane & ~15));
+  const op8* xptr_last = xt + ((MT - 1) * 16 + (lane & 15) < M ? lane : (lane & ~15));
 
   f32x4 acc[CT][MT];
 #pragma unroll
   for (int r = 0; r < CT; ++r)
 #pragma unroll
     for (int j = 0; j < MT; ++j) acc[r][j] = f32x4{0.f, 0.f, 0.f, 0.f};
-  bf16x8 w[WD][KB][CT], x[2][KB][XF];
+  op8 w[WD][KB][CT], x[2][KB][MT];
   const int nsteps = (t1 - t0 + KB - 1) / KB;
-  const bf16x8 zero8 = {0, 0, 0, 0, 0, 0, 0, 0};
+  const op8 zero8 = {0, 0, 0, 0, 0, 0, 0, 0};
 
   // step st of the wavefront (its k-tiles clamped to the wavefront's last one) -> register set `slot`
   auto load_x = [&](const int slot, int st) __attribute__((always_inline)) {
@@ -114,9 +111,7 @@ __global__ __launch_bounds__(TPB) void gemm_mid_kernel(const bf16x8* __restrict_
     for (int i = 0; i < KB; ++i) {
       const int tc = min(t0 + st * KB + i, t1 - 1);
 #pragma unroll
-      for (int j = 0; j < MT; ++j)
-#pragma unroll
-        for (int p = 0; p < XP; ++p) x[slot][i][j * XP + p] = (j == MT - 1 ? xptr_last : xptr)[(((size_t)j * KT + tc) * XP + p) * 64];
+      for (int j = 0; j < MT; ++j) x[slot][i][j] = (j == MT - 1 ? xptr_last : xptr)[((size_t)j * KT + tc) * 64];
     }
   };
   auto load_w = [&](const int slot, int st) __attribute__((always_inline)) {
@@ -132,10 +127,10 @@ __global__ __launch_bounds__(TPB) void gemm_mid_kernel(const bf16x8* __restrict_
     for (int i = 0; i < KB; ++i) {
       const bool past = KB > 1 && t0 + st * KB + i >= t1;  // the surplus k-tile of a ragged last step multiplies zeros
 #pragma unroll
-      for (int j = 0; j < XF; ++j) {
-        const bf16x8 xv = past ? zero8 : x[xs][i][j];
+      for (int j = 0; j < MT; ++j) {
+        const op8 xv = past ? zero8 : x[xs][i][j];
 #pragma unroll
-        for (int r = 0; r < CT; ++r) acc[r][j / XP] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(w[ws][i][r], xv, acc[r][j / XP], 0, 0, 0);
+        for (int r = 0; r < CT; ++r) acc[r][j] = mfma_op(w[ws][i][r], xv, acc[r][j]);
       }
     }
   };
@@ -289,14 +284,14 @@ struct MidPlan {
 // compute units best, without a K split if it can (QKV of an 8B model: 256 groups of 48; gate/up: 256 groups of 96).
 // Narrow ones (O, down; at most 256 column tiles): 64-column groups and a four-way K split when K is long (down), 32-column
 // groups and a two-way split when it is short (O); all measured against their alternatives.
-MidPlan mid_plan(int M, int N, int K, bool may_split, int kind) {
+MidPlan mid_plan(int M, int N, int K, bool may_split) {
   MidPlan best;
   double best_fill = -1.;
   const int pr = weight_pack_rows(N), mt = (M + 15) >> 4, KT = K >> 5;
   // accumulators (4 CT MT registers) + three k-tiles of W + two of X within the register file: 128-column groups up to 112 rows
-  // short K: the partial tiles of a four-way split cost more than X re-read by twice the groups; beyond 13 row tiles (8 when X
-  // is a pair of planes) the 32-column variant's two k-tiles of X per step no longer fit the registers
-  const int narrow = (K >= 8192 && mt > 1) || mt > (kind == EPI_RESID ? 8 : 13) ? 4 : 2;
+  // short K: the partial tiles of a four-way split cost more than X re-read by twice the groups; beyond 13 row tiles the
+  // 32-column variant's two k-tiles of X per step no longer fit the registers
+  const int narrow = (K >= 8192 && mt > 1) || mt > 13 ? 4 : 2;
   const int cts[3] = {pr == 2 ? (mt <= 7 ? 8 : 6) : narrow, pr == 2 ? 6 : narrow, pr == 2 ? (mt <= 10 ? 3 : 6) : narrow};
   for (int c = 0; c < 3; ++c) {
     MidPlan p;
@@ -321,8 +316,8 @@ MidPlan mid_plan(int M, int N, int K, bool may_split, int kind) {
 }
 
 template <int MT, int CT, int PR, int EPI>
-void launch_one(const bf16_t* xt, const bf16_t* wt, int M, int N, int K, const MidPlan& p, const GemmEpi& e, hipStream_t st) {
-  typedef MidShape<MT, CT, XPlanes<EPI>::value> SH;
+void launch_one(const op_t* xt, const op_t* wt, int M, int N, int K, const MidPlan& p, const GemmEpi& e, hipStream_t st) {
+  typedef MidShape<MT, CT> SH;
   static bool configured = false;  // raise the dynamic LDS limit of this instantiation once
   if (!configured) {
     (void)hipFuncSetAttribute((const void*)gemm_mid_kernel<MT, CT, PR, EPI>, hipFuncAttributeMaxDynamicSharedMemorySize, SH::LDS_BYTES);
@@ -335,20 +330,18 @@ void launch_one(const bf16_t* xt, const bf16_t* wt, int M, int N, int K, const M
         (void)hipFuncSetAttribute((const void*)gemm_mid_kernel<MT, CT, PR, EPI, true>, hipFuncAttributeMaxDynamicSharedMemorySize, SH::LDS_BYTES);
         configured_steps = true;
       }
-      DLM_LAUNCH((gemm_mid_kernel<MT, CT, PR, EPI, true>), p.groups * p.splits, TPB, SH::LDS_BYTES, st, (const bf16x8*)xt, (const bf16x8*)wt, M, N, K, p.kps, p.splits, e);
+      DLM_LAUNCH((gemm_mid_kernel<MT, CT, PR, EPI, true>), p.groups * p.splits, TPB, SH::LDS_BYTES, st, (const op8*)xt, (const op8*)wt, M, N, K, p.kps, p.splits, e);
       return;
     }
   }
-  DLM_LAUNCH((gemm_mid_kernel<MT, CT, PR, EPI>), p.groups * p.splits, TPB, SH::LDS_BYTES, st, (const bf16x8*)xt, (const bf16x8*)wt, M, N, K, p.kps, p.splits, e);
+  DLM_LAUNCH((gemm_mid_kernel<MT, CT, PR, EPI>), p.groups * p.splits, TPB, SH::LDS_BYTES, st, (const op8*)xt, (const op8*)wt, M, N, K, p.kps, p.splits, e);
 }
 
 template <int MT, int EPI>
-void launch_mt(const bf16_t* xt, const bf16_t* wt, int M, int N, int K, const MidPlan& p, const GemmEpi& e, hipStream_t st) {
-  // (EPI_RESID, whose X fragments are pairs, comes here with at most GEMM_MID_MAX_ROWS rows: 10 row tiles, 8 for 32-column groups)
-  constexpr bool pair = EPI == EPI_RESID;
+void launch_mt(const op_t* xt, const op_t* wt, int M, int N, int K, const MidPlan& p, const GemmEpi& e, hipStream_t st) {
   if (p.pr == 1) {
-    if (p.ct == 2) { if constexpr (MT <= (pair ? 8 : 13)) launch_one<MT, 2, 1, EPI>(xt, wt, M, N, K, p, e, st); }
-    else if constexpr (MT >= 2 && (!pair || MT <= 10)) launch_one<MT, 4, 1, EPI>(xt, wt, M, N, K, p, e, st);
+    if (p.ct == 2) { if constexpr (MT <= 13) launch_one<MT, 2, 1, EPI>(xt, wt, M, N, K, p, e, st); }
+    else if constexpr (MT >= 2) launch_one<MT, 4, 1, EPI>(xt, wt, M, N, K, p, e, st);
   } else if (p.ct == 8) {
     if constexpr (MT <= 7) launch_one<MT, 8, 2, EPI>(xt, wt, M, N, K, p, e, st);
   } else if (p.ct == 3) {
@@ -359,7 +352,7 @@ void launch_mt(const bf16_t* xt, const bf16_t* wt, int M, int N, int K, const Mi
 }
 
 template <int EPI>
-void launch_epi(const bf16_t* xt, const bf16_t* wt, int M, int N, int K, const MidPlan& p, const GemmEpi& e, hipStream_t st) {
+void launch_epi(const op_t* xt, const op_t* wt, int M, int N, int K, const MidPlan& p, const GemmEpi& e, hipStream_t st) {
   switch (p.mt) {  // the dispatcher sends only row counts that have an instantiation
     case 1: launch_mt<1, EPI>(xt, wt, M, N, K, p, e, st); break;
     case 2: launch_mt<2, EPI>(xt, wt, M, N, K, p, e, st); break;
@@ -383,23 +376,23 @@ void launch_epi(const bf16_t* xt, const bf16_t* wt, int M, int N, int K, const M
 }  // namespace
 
 // one compute unit's worth of workgroups per 96-column group, no K split: the shapes the mid kernel takes even below 17 rows
-bool gemm_mid_fills_chip(int M, int N, int K, int kind) {
-  const MidPlan p = mid_plan(M, N, K, true, kind);
+bool gemm_mid_fills_chip(int M, int N, int K, int) {
+  const MidPlan p = mid_plan(M, N, K, true);
   return p.splits == 1 && p.groups % 256 == 0;
 }
-int gemm_mid_splits(int M, int N, int K, int kind) { return mid_plan(M, N, K, true, kind).splits; }
-int gemm_mid_ssq_chunks(int M, int N, int K) { return mid_plan(M, N, K, true, EPI_RESID).groups; }
+int gemm_mid_splits(int M, int N, int K, int) { return mid_plan(M, N, K, true).splits; }
+int gemm_mid_ssq_chunks(int M, int N, int K) { return mid_plan(M, N, K, true).groups; }
 int gemm_mid_counters(int max_n) { return (max_n + 31) / 32; }  // 32-column groups are the narrowest
 void gemm_mid_set_target(int wgs) { g_mid_wgs = wgs; }
 
 
-int gemm_mid_steps_ct(int N, int K, int kind) {
-  const MidPlan p = mid_plan(16, N, K, true, kind);
+int gemm_mid_steps_ct(int N, int K, int) {
+  const MidPlan p = mid_plan(16, N, K, true);
   return (p.splits == 1 && N % (16 * p.ct) == 0 && (K >> 5) % NWV == 0) ? p.ct : 0;
 }
 
-void launch_gemm_mid(const bf16_t* xt, const bf16_t* wt, int M, int N, int K, const GemmEpi& e_in, hipStream_t st) {
-  const MidPlan p = mid_plan(M, N, K, e_in.kind != EPI_DIRECT, e_in.kind);  // EPI_DIRECT has no workspace
+void launch_gemm_mid(const op_t* xt, const op_t* wt, int M, int N, int K, const GemmEpi& e_in, hipStream_t st) {
+  const MidPlan p = mid_plan(M, N, K, e_in.kind != EPI_DIRECT);  // EPI_DIRECT has no workspace
   GemmEpi e = e_in;
   // the step-major copy serves exactly the launches it was laid out for
   if (!(e.w_steps && p.mt <= MID_STEPS_MAX_MT && e.w_steps_ct == p.ct && p.splits == 1 && N % (16 * p.ct) == 0 && (K >> 5) % NWV == 0)) e.w_steps = nullptr;

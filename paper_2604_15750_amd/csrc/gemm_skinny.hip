@@ -1,4 +1,4 @@
-// Skinny bf16 GEMM (M <= 64 rows): Y[M,N] = X[M,K] * W[N,K]^T, fp32 accumulation, epilogue fused.
+// Skinny GEMM of a bf16 model (M <= 64 rows): Y[M,N] = X[M,K] * W[N,K]^T, fp32 accumulation, epilogue fused.
 //
 // One workgroup per 16- or 32-column output tile over the whole of K.  Its wavefronts split K among
 // themselves; each keeps 8 KiB of W fragments (and the matching X fragments) in flight, HBM ->
@@ -17,7 +17,7 @@ namespace {
 // workgroup's R column tiles against all MT row tiles, D k-tiles per batch, two batches of registers.
 // STEPS: W is read from the step-major copy (e.w_steps) instead of wt.
 template <int MT, int R, int NWV, int D, int EPI, bool STEPS = false>
-__global__ __launch_bounds__(NWV * 64) void gemm_skinny_kernel(const bf16x8* __restrict__ xt, const bf16x8* __restrict__ wt, int M, int N,
+__global__ __launch_bounds__(NWV * 64) void gemm_skinny_kernel(const op8* __restrict__ xt, const op8* __restrict__ wt, int M, int N,
                                                                int K, GemmEpi e) {
   __shared__ f32x4 red[NWV][R * MT][64];
   __shared__ float s_rinv[MT * 16];
@@ -25,23 +25,22 @@ __global__ __launch_bounds__(NWV * 64) void gemm_skinny_kernel(const bf16x8* __r
   const int KT = K >> 5, MTILES = (M + 15) >> 4;
   const int per = (KT + NWV - 1) / NWV;
   const int t_begin = wave * per, t_end = min(KT, t_begin + per);
-  const bf16x8 zero8 = {0, 0, 0, 0, 0, 0, 0, 0};
+  const op8 zero8 = {0, 0, 0, 0, 0, 0, 0, 0};
   // lanes of the last row tile whose row does not exist re-read row 0 of their k-group (whatever they get is never stored)
   const int xlane_last = (MTILES - 1) * 16 + (lane & 15) < M ? lane : (lane & ~15);
   // the workgroup's R tiles are one interleaved run; in the step-major copy (KT a multiple of NWV: the host checks) the
   // wavefront's step s is the R fragments from ((s * workgroups + this workgroup) * NWV + wave) * R on
   constexpr bool steps = STEPS;
-  const bf16x8* wbase = steps ? (const bf16x8*)e.w_steps + ((size_t)blockIdx.x * NWV + wave) * R * 64 + lane : wt + (size_t)blockIdx.x * KT * R * 64 + lane;
+  const op8* wbase = steps ? (const op8*)e.w_steps + ((size_t)blockIdx.x * NWV + wave) * R * 64 + lane : wt + (size_t)blockIdx.x * KT * R * 64 + lane;
   const size_t wstride = steps ? (size_t)gridDim.x * NWV * R * 64 : R * 64;
   const int tsub = steps ? t_begin : 0;
 
-  constexpr int XP = XPlanes<EPI>::value;  // planes of X: a fragment tile of the EPI_RESID GEMMs' input is a pair (hi, lo), 2 KiB
   f32x4 acc[R][MT];
 #pragma unroll
   for (int r = 0; r < R; ++r)
 #pragma unroll
     for (int j = 0; j < MT; ++j) acc[r][j] = f32x4{0.f, 0.f, 0.f, 0.f};
-  bf16x8 wreg[2][D][R], xreg[2][D][MT * XP];
+  op8 wreg[2][D][R], xreg[2][D][MT];
 
   auto load = [&](int buf, int tb) {
 #pragma unroll
@@ -51,10 +50,7 @@ __global__ __launch_bounds__(NWV * 64) void gemm_skinny_kernel(const bf16x8* __r
 #pragma unroll
       for (int r = 0; r < R; ++r) wreg[buf][i][r] = ok ? wbase[(size_t)(t - tsub) * wstride + r * 64] : zero8;
 #pragma unroll
-      for (int j = 0; j < MT; ++j)
-#pragma unroll
-        for (int p = 0; p < XP; ++p)
-          xreg[buf][i][j * XP + p] = (ok && j < MTILES) ? xt[(((size_t)j * KT + t) * XP + p) * 64 + (j == MTILES - 1 ? xlane_last : lane)] : zero8;
+      for (int j = 0; j < MT; ++j) xreg[buf][i][j] = (ok && j < MTILES) ? xt[((size_t)j * KT + t) * 64 + (j == MTILES - 1 ? xlane_last : lane)] : zero8;
     }
   };
   auto compute = [&](int buf) {
@@ -63,9 +59,7 @@ __global__ __launch_bounds__(NWV * 64) void gemm_skinny_kernel(const bf16x8* __r
 #pragma unroll
       for (int j = 0; j < MT; ++j)
 #pragma unroll
-        for (int p = 0; p < XP; ++p)
-#pragma unroll
-          for (int r = 0; r < R; ++r) acc[r][j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(wreg[buf][i][r], xreg[buf][i][j * XP + p], acc[r][j], 0, 0, 0);
+        for (int r = 0; r < R; ++r) acc[r][j] = mfma_op(wreg[buf][i][r], xreg[buf][i][j], acc[r][j]);
   };
 
   load(0, t_begin);
@@ -101,20 +95,18 @@ __global__ __launch_bounds__(NWV * 64) void gemm_skinny_kernel(const bf16x8* __r
   }
 }
 
-// batch depth: 8 KiB of W in flight per wavefront for up to 32 rows (of X fragments: 16 when X is a pair of planes), half of
-// that beyond (the X fragments take the registers); the step-major copy reads best with batches of four (measured: deeper
-// batches add queueing, not bandwidth)
+// batch depth: 8 KiB of W in flight per wavefront for up to 32 rows, half of that beyond (the X fragments take the registers);
+// the step-major copy reads best with batches of four (measured: deeper batches add queueing, not bandwidth)
 template <int MT, int EPI>
-void launch_skinny(const bf16_t* xt, const bf16_t* wt, int pr, int M, int N, int K, const GemmEpi& e, hipStream_t st) {
-  constexpr int XF = MT * XPlanes<EPI>::value;  // X fragments per k-tile
-  if (pr == 1 && e.w_steps) DLM_LAUNCH((gemm_skinny_kernel<MT, 1, 8, (XF <= 4 ? 4 : 2), EPI, true>), N / 16, 512, 0, st, (const bf16x8*)xt, (const bf16x8*)wt, M, N, K, e);
-  else if (pr == 1) DLM_LAUNCH((gemm_skinny_kernel<MT, 1, 8, (XF <= 2 ? 8 : XF <= 4 ? 4 : 2), EPI>), N / 16, 512, 0, st, (const bf16x8*)xt, (const bf16x8*)wt, M, N, K, e);
-  else if (e.w_steps) DLM_LAUNCH((gemm_skinny_kernel<MT, 2, 4, (XF <= 2 ? 4 : 2), EPI, true>), N / 32, 256, 0, st, (const bf16x8*)xt, (const bf16x8*)wt, M, N, K, e);
-  else DLM_LAUNCH((gemm_skinny_kernel<MT, 2, 4, (XF <= 2 ? 4 : 2), EPI>), N / 32, 256, 0, st, (const bf16x8*)xt, (const bf16x8*)wt, M, N, K, e);
+void launch_skinny(const op_t* xt, const op_t* wt, int pr, int M, int N, int K, const GemmEpi& e, hipStream_t st) {
+  if (pr == 1 && e.w_steps) DLM_LAUNCH((gemm_skinny_kernel<MT, 1, 8, 4, EPI, true>), N / 16, 512, 0, st, (const op8*)xt, (const op8*)wt, M, N, K, e);
+  else if (pr == 1) DLM_LAUNCH((gemm_skinny_kernel<MT, 1, 8, (MT <= 2 ? 8 : 4), EPI>), N / 16, 512, 0, st, (const op8*)xt, (const op8*)wt, M, N, K, e);
+  else if (e.w_steps) DLM_LAUNCH((gemm_skinny_kernel<MT, 2, 4, (MT <= 2 ? 4 : 2), EPI, true>), N / 32, 256, 0, st, (const op8*)xt, (const op8*)wt, M, N, K, e);
+  else DLM_LAUNCH((gemm_skinny_kernel<MT, 2, 4, (MT <= 2 ? 4 : 2), EPI>), N / 32, 256, 0, st, (const op8*)xt, (const op8*)wt, M, N, K, e);
 }
 
 template <int EPI>
-void launch_epi(const bf16_t* xt, const bf16_t* wt, int pr, int M, int N, int K, const GemmEpi& e, hipStream_t st) {
+void launch_epi(const op_t* xt, const op_t* wt, int pr, int M, int N, int K, const GemmEpi& e, hipStream_t st) {
   if (M <= 16) launch_skinny<1, EPI>(xt, wt, pr, M, N, K, e, st);
   else if (M <= 32) launch_skinny<2, EPI>(xt, wt, pr, M, N, K, e, st);
   else if (M <= 48) launch_skinny<3, EPI>(xt, wt, pr, M, N, K, e, st);
@@ -123,7 +115,7 @@ void launch_epi(const bf16_t* xt, const bf16_t* wt, int pr, int M, int N, int K,
 
 }  // namespace
 
-void launch_gemm_skinny(const bf16_t* xt, const bf16_t* wt, int pr, int M, int N, int K, const GemmEpi& e_in, hipStream_t st) {
+void launch_gemm_skinny(const op_t* xt, const op_t* wt, int pr, int M, int N, int K, const GemmEpi& e_in, hipStream_t st) {
   GemmEpi e = e_in;
   // the step-major copy serves the launches it was laid out for: pr column tiles per workgroup, 8 wavefronts (pr 1) or 4 (pr 2)
   if (!(e.w_steps && e.w_steps_ct == pr && (K >> 5) % (pr == 1 ? 8 : 4) == 0 && N % (16 * pr) == 0)) e.w_steps = nullptr;

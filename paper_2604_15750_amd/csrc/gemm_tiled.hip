@@ -1,4 +1,4 @@
-// Tiled bf16 GEMM (M > 32 rows, and the LM head): Y[M,N] = X[M,K] * W[N,K]^T, fp32 accumulation,
+// Tiled GEMM of a bf16 model (M > 32 rows, and the LM head): Y[M,N] = X[M,K] * W[N,K]^T, fp32 accumulation,
 // epilogue fused.
 //
 // A workgroup of four wavefronts owns up to 128 rows (MT row tiles) x 128 or 256 columns; a wavefront
@@ -73,11 +73,11 @@ __device__ __attribute__((always_inline)) inline LiteState lite_of(f32x4 v, int 
 
 // TR column tiles per wavefront (workgroups of 64 TR columns); PR = 2: weights packed in interleaved pairs, 1: single runs.
 template <int MT, int TR, int PR, int EPI>
-__global__ __launch_bounds__(TPB) void gemm_tiled_kernel(const bf16x8* __restrict__ xt, const bf16x8* __restrict__ wt, int M, int N, int K,
+__global__ __launch_bounds__(TPB) void gemm_tiled_kernel(const op8* __restrict__ xt, const op8* __restrict__ wt, int M, int N, int K,
                                                          int kt_per_split, int splits, int groups, int mblocks, GemmEpi e) {
   constexpr int XPIECES = MT * KC * 64;            // 16-byte pieces of X per chunk
   constexpr int XP = (XPIECES + TPB - 1) / TPB;    // per thread
-  __shared__ bf16x8 xs[3][XPIECES];
+  __shared__ op8 xs[3][XPIECES];
   __shared__ float s_rinv[MT * 16];
   __shared__ float s_ssq[4][MT * 16];
   __shared__ int s_last;
@@ -97,9 +97,9 @@ __global__ __launch_bounds__(TPB) void gemm_tiled_kernel(const bf16x8* __restric
   const int t_begin = split * kt_per_split;
   const int t_end = min(KT, t_begin + kt_per_split);
   const int n_chunks = (t_end - t_begin + KC - 1) / KC;
-  const bf16x8 zero8 = {0, 0, 0, 0, 0, 0, 0, 0};
+  const op8 zero8 = {0, 0, 0, 0, 0, 0, 0, 0};
 
-  const bf16x8* wptr[TR];  // fragment (nt0 + r, k-tile t) = wptr[r][t * wstep]
+  const op8* wptr[TR];  // fragment (nt0 + r, k-tile t) = wptr[r][t * wstep]
   constexpr size_t wstep = PR == 2 ? 128 : 64;
 #pragma unroll
   for (int r = 0; r < TR; ++r) {
@@ -112,9 +112,9 @@ __global__ __launch_bounds__(TPB) void gemm_tiled_kernel(const bf16x8* __restric
   for (int r = 0; r < TR; ++r)
 #pragma unroll
     for (int j = 0; j < MT; ++j) acc[r][j] = f32x4{0.f, 0.f, 0.f, 0.f};
-  bf16x8 wreg[3][KC][TR], xreg[3][XP];
+  op8 wreg[3][KC][TR], xreg[3][XP];
 
-  auto load_w = [&](bf16x8(&dst)[KC][TR], int chunk) {
+  auto load_w = [&](op8(&dst)[KC][TR], int chunk) {
 #pragma unroll
     for (int tc = 0; tc < KC; ++tc) {
       const int t = t_begin + chunk * KC + tc;
@@ -122,7 +122,7 @@ __global__ __launch_bounds__(TPB) void gemm_tiled_kernel(const bf16x8* __restric
       for (int r = 0; r < TR; ++r) dst[tc][r] = (nt0 + r < NT && t < t_end) ? wptr[r][t * wstep] : zero8;
     }
   };
-  auto load_x = [&](bf16x8(&dst)[XP], int chunk) {
+  auto load_x = [&](op8(&dst)[XP], int chunk) {
 #pragma unroll
     for (int i = 0; i < XP; ++i) {
       const int p = tid + TPB * i;
@@ -131,19 +131,19 @@ __global__ __launch_bounds__(TPB) void gemm_tiled_kernel(const bf16x8* __restric
       dst[i] = (p < XPIECES && mt0 + j < MTILES && t < t_end) ? xt[((size_t)(mt0 + j) * KT + t) * 64 + ln] : zero8;
     }
   };
-  auto store_x = [&](int buf, const bf16x8(&src)[XP]) {
+  auto store_x = [&](int buf, const op8(&src)[XP]) {
 #pragma unroll
     for (int i = 0; i < XP; ++i)
       if (tid + TPB * i < XPIECES) xs[buf][tid + TPB * i] = src[i];
   };
-  auto compute = [&](const bf16x8(&w)[KC][TR], int buf) {
+  auto compute = [&](const op8(&w)[KC][TR], int buf) {
 #pragma unroll
     for (int tc = 0; tc < KC; ++tc) {
 #pragma unroll
       for (int j = 0; j < MT; ++j) {
-        const bf16x8 xf = xs[buf][(j * KC + tc) * 64 + lane];
+        const op8 xf = xs[buf][(j * KC + tc) * 64 + lane];
 #pragma unroll
-        for (int r = 0; r < TR; ++r) acc[r][j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(w[tc][r], xf, acc[r][j], 0, 0, 0);
+        for (int r = 0; r < TR; ++r) acc[r][j] = mfma_op(w[tc][r], xf, acc[r][j]);
       }
     }
   };
@@ -312,9 +312,9 @@ Plan plan(int M, int N, int K, bool may_split = true) {
 }
 
 template <int MT, int EPI>
-void launch_mt(const bf16_t* xt, const bf16_t* wt, int M, int N, int K, const Plan& p, const GemmEpi& e, hipStream_t st) {
+void launch_mt(const op_t* xt, const op_t* wt, int M, int N, int K, const Plan& p, const GemmEpi& e, hipStream_t st) {
   const int grid = (p.groups + 7) / 8 * 8 * p.splits * p.mblocks;
-#define GO(TR, PR) DLM_LAUNCH((gemm_tiled_kernel<MT, TR, PR, EPI>), grid, TPB, 0, st, (const bf16x8*)xt, (const bf16x8*)wt, M, N, K, p.kps, p.splits, p.groups, p.mblocks, e)
+#define GO(TR, PR) DLM_LAUNCH((gemm_tiled_kernel<MT, TR, PR, EPI>), grid, TPB, 0, st, (const op8*)xt, (const op8*)wt, M, N, K, p.kps, p.splits, p.groups, p.mblocks, e)
   if (p.pr == 1) GO(2, 1);
   else if (p.tr == 2) GO(2, 2);
   else GO(4, 2);
@@ -322,7 +322,7 @@ void launch_mt(const bf16_t* xt, const bf16_t* wt, int M, int N, int K, const Pl
 }
 
 // EPI_STATS serves at most GEMM_STATS_MAX_ROWS = 64 rows: four row tiles
-void launch_stats(const bf16_t* xt, const bf16_t* wt, int M, int N, int K, const Plan& p, const GemmEpi& e, hipStream_t st) {
+void launch_stats(const op_t* xt, const op_t* wt, int M, int N, int K, const Plan& p, const GemmEpi& e, hipStream_t st) {
   switch (p.mt) {
     case 1: launch_mt<1, EPI_STATS>(xt, wt, M, N, K, p, e, st); break;
     case 2: launch_mt<2, EPI_STATS>(xt, wt, M, N, K, p, e, st); break;
@@ -332,7 +332,7 @@ void launch_stats(const bf16_t* xt, const bf16_t* wt, int M, int N, int K, const
 }
 
 template <int EPI>
-void launch_epi(const bf16_t* xt, const bf16_t* wt, int M, int N, int K, const Plan& p, const GemmEpi& e, hipStream_t st) {
+void launch_epi(const op_t* xt, const op_t* wt, int M, int N, int K, const Plan& p, const GemmEpi& e, hipStream_t st) {
   switch (p.mt) {
     case 1: launch_mt<1, EPI>(xt, wt, M, N, K, p, e, st); break;
     case 2: launch_mt<2, EPI>(xt, wt, M, N, K, p, e, st); break;
@@ -353,13 +353,13 @@ int gemm_tiled_ssq_chunks(int M, int N) { return plan(M, N, 32).groups; }
 int gemm_tiled_stat_parts(int M, int N) { return plan(M, N, 32, false).groups; }
 int gemm_tiled_counters(int max_rows, int max_n) { return ((max_n + 127) / 128) * (((max_rows + 15) / 16 + 7) / 8); }  // 128-column groups are the narrowest
 
-void launch_gemm_tiled(const bf16_t* xt, const bf16_t* wt, int M, int N, int K, const GemmEpi& e, hipStream_t st) {
+void launch_gemm_tiled(const op_t* xt, const op_t* wt, int M, int N, int K, const GemmEpi& e, hipStream_t st) {
   const Plan p = plan(M, N, K, e.kind != EPI_DIRECT && e.kind != EPI_STATS);  // the LM head's epilogues have no workspace
   switch (e.kind) {
     case EPI_STATS: launch_stats(xt, wt, M, N, K, p, e, st); break;
     case EPI_QKV: launch_epi<EPI_QKV>(xt, wt, M, N, K, p, e, st); break;
     case EPI_SWIGLU: launch_epi<EPI_SWIGLU>(xt, wt, M, N, K, p, e, st); break;
-    // (EPI_RESID, whose X is a pair of planes, is never sent here: choose_kernel in gemm_bf16.hip)
+    // (EPI_RESID is never sent here: choose_kernel in gemm_bf16.hip)
     default: launch_epi<EPI_SUM>(xt, wt, M, N, K, p, e, st); break;
   }
 }
