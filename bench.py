@@ -277,7 +277,7 @@ def main():
         from paper_2604_15750_amd import api
         buf = torch.empty(2 << 30, dtype=torch.uint8, device="cuda:0")
         print(json.dumps({"micro": "peaks", "hbm_read_GBs": api.probe_hbm_read(buf, reps=20), "hbm_published_GBs": HBM_PEAK_GBS,
-                          "mfma_bf16_TFLOPs": api.probe_mfma_bf16(reps=10), "mfma_bf16_published_TFLOPs": 2500.0}))
+                          "mfma_f16_random_operands_TFLOPs": api.probe_mfma(reps=10), "mfma_f16_published_TFLOPs": 2500.0}))
         return
 
     import torch
@@ -364,9 +364,9 @@ def main():
     # what this GPU achieves on the same resources with kernels that do nothing else (a plain streaming read of 2 GiB; matrix-core
     # products out of registers): the published peaks are not reachable by any kernel
     probe_buf = torch.empty(2 << 30, dtype=torch.uint8, device=dev)
-    achievable = {"hbm_read_GBs": api.probe_hbm_read(probe_buf, reps=10), "mfma_bf16_TFLOPs": api.probe_mfma_bf16(reps=5)}
+    achievable = {"hbm_read_GBs": api.probe_hbm_read(probe_buf, reps=10), "mfma_f16_random_operands_TFLOPs": api.probe_mfma(reps=5)}
     del probe_buf
-    roof["achievable_peak"] = achievable["hbm_read_GBs"] if roof["bound"] == "hbm" else achievable["mfma_bf16_TFLOPs"]
+    roof["achievable_peak"] = achievable["hbm_read_GBs"] if roof["bound"] == "hbm" else achievable["mfma_f16_random_operands_TFLOPs"]
     roof["frac_of_achievable"] = roof["achieved"] / roof["achievable_peak"]
     others = {cls: class_roofline(cls, *prof[cls]) for cls in GEMM_CLASSES}
     # attention against the HBM time of its K/V reads (cached prefix + the span's own rows, every layer); vocabulary statistics
@@ -392,7 +392,9 @@ def main():
         "metric": "decoded tokens/s + denoise-step latency, 8B-shaped DLM, gen 256, 1 GPU",
         "value": tokens / elapsed, "unit": "tokens/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
         "ms_per_step": elapsed / args.steps * 1e3, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
-        "dtype": cfg["dtype"], "data": "synthetic",
+        # what the matrix cores multiply: a bf16 model's operands are IEEE half (bf16 weights converted once, activations rounded
+        # to half), accumulated in fp32; weights, embeddings and logits are bf16 in the caller's memory
+        "dtype": "f16" if cfg["dtype"] == "bf16" else cfg["dtype"], "storage_dtype": cfg["dtype"], "data": "synthetic",
         "config": {"workload": args.workload, "batch": B, "prompt_len": P, "gen_len": N, "l_max": lmax, "n_layers": cfg["n_layers"], "weight_copies": args.weight_copies, "stats": args.stats,
                    "thresholds": "paper defaults (lambda 1.2, L_min 8, tau 0.8/0.95, gamma -16)" if args.thresholds == "paper" else
                                  "scaled to a random-init model (lambda 0.9, L_min 8, tau 0.04/0.25, gamma -36)"},

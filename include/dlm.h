@@ -244,11 +244,12 @@ int dlm_attention(const void* q, const void* k, const void* v, void* out, int A,
  *
  * dlm_probe_hbm_read: streams `bytes` of DEVICE memory at src `reps` times (16-byte loads, every byte
  * once per repetition; use a buffer larger than the 256 MB memory-side cache) and reports the read
- * rate in GB/s.  dlm_probe_mfma_bf16: `reps` launches of independent 16x16x32 bf16 products out of
- * registers on every SIMD, reports TFLOP/s.
+ * rate in GB/s.  dlm_probe_mfma: `reps` launches of independent 16x16x32 half-precision products out of
+ * registers on every SIMD, on operands of pseudo-random values (what the chip sustains then is set by
+ * its power limit, below the published rate, which constant operands reach), reports TFLOP/s.
  * Errors: DLM_EINVAL, DLM_ESHAPE (fewer than 16 MiB), DLM_ENOMEM, DLM_EHIP. */
 int dlm_probe_hbm_read(const void* src, size_t bytes, int reps, double* gb_per_s, void* stream);
-int dlm_probe_mfma_bf16(int reps, double* tflop_per_s, void* stream);
+int dlm_probe_mfma(int reps, double* tflop_per_s, void* stream);
 
 /* Where dlm_step takes the vocabulary statistics of a bf16 model's pass that compares no row with a
  * retained distribution and retains none (kl_count and save_count all zero: the in-block passes of

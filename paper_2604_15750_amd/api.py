@@ -55,7 +55,7 @@ class dlm_select_params(C.Structure):
 
 EXPORTS = ["dlm_last_error", "dlm_model_create", "dlm_model_destroy", "dlm_state_create", "dlm_state_destroy", "dlm_state_reset",
            "dlm_state_kv_len", "dlm_step", "block_boundary", "select_parallel", "dlm_vocab_stats_workspace", "dlm_vocab_stats",
-           "dlm_gemm_nt", "dlm_attention", "dlm_profile_enable", "dlm_profile_read", "dlm_probe_hbm_read", "dlm_probe_mfma_bf16",
+           "dlm_gemm_nt", "dlm_attention", "dlm_profile_enable", "dlm_profile_read", "dlm_probe_hbm_read", "dlm_probe_mfma",
            "dlm_state_fuse_stats", "dlm_vocab_stats_static"]
 
 
@@ -277,10 +277,10 @@ def probe_hbm_read(buf, reps=10):
     return out.value
 
 
-def probe_mfma_bf16(reps=5):
-    """TFLOP/s of independent bf16 matrix-core products out of registers."""
+def probe_mfma(reps=5):
+    """TFLOP/s of independent half-precision matrix-core products out of registers, on operands of pseudo-random values."""
     out = C.c_double()
-    _check(lib().dlm_probe_mfma_bf16(reps, C.byref(out), _stream()))
+    _check(lib().dlm_probe_mfma(reps, C.byref(out), _stream()))
     return out.value
 
 

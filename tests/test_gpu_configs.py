@@ -98,9 +98,10 @@ def test_full_depth_first_passes(device):
     logit and statistic against the oracle run at full depth on the host, at the benchmark spec's tolerance: 2e-2 of
     max(row maximum, sigma_logit) for the worst logit of every row.
 
-    What makes that bound reachable at this depth is where the kernels keep more than bf16's 8 mantissa bits: the attention
-    operands (Q, K, V, probabilities) in IEEE half and the inputs of the O and down projections as bf16 pairs.  The same pass
-    in exact fp32 torch operations with every activation rounded to bf16 between the GEMMs is printed beside it, as
+    What keeps the path well inside that bound at this depth is what the kernels feed the matrix cores: IEEE half (11
+    significant bits) for every GEMM input, the packed weights and the attention operands, instead of bf16's 8 bits; the
+    measured worst logit error is 0.5e-2, and the test also holds the path to 1e-2 so that a lost bit somewhere shows.  The
+    same pass in exact fp32 torch operations with every activation rounded to bf16 between the GEMMs is printed beside it, as
     information: that dataflow is about 2.3e-2 (relative L2 per row) from the oracle, whoever does the arithmetic."""
     cfg, _, P, N, lmax = inputs.WORKLOADS["llada8b_p256_g256"]
     W = inputs.make_weights(cfg, seed=0, device=device)
@@ -110,7 +111,7 @@ def test_full_depth_first_passes(device):
     kinds = [t["kind"] for t in r["trace"] if t["op"] == "pass"]
     assert kinds[0] == "prefill" and kinds[-1] == "boundary" and "inblock" in kinds, kinds
     assert r["boundaries"] == 1 and r["worst"] <= 2e-2
-    assert r["rms"] <= 1.6e-2, st  # a row's relative L2 error: well inside what the worst-element bound needs
+    assert r["worst"] <= 1e-2 and r["rms"] <= 6e-3, st  # (measured 0.5e-2 and 0.37e-2)
     pre = [t for t in r["trace"] if t["op"] == "pass"][0]
     ref = pre["logits"]
     emu = _bf16_dataflow(cfg, W, pre["tokens"], device)
@@ -129,6 +130,7 @@ def test_full_depth_grouped_query_first_passes(device):
     r = replay(cfg, W, prompt, N, dict(SCALED, l_max=lmax), device, logit_tol=2e-2, max_passes=2, stats_out=st)
     kinds = [t["kind"] for t in r["trace"] if t["op"] == "pass"]
     assert kinds == ["prefill", "inblock"] and r["worst"] <= 2e-2
+    assert r["worst"] <= 1e-2, st  # (measured 0.54e-2)
     print("full depth, grouped-query shape:", st)
 
 

@@ -237,10 +237,11 @@ def test_select_parallel(device, dt, mode):
 # ---- measurement helpers --------------------------------------------------------------------------
 def test_probes_report_plausible_rates(device):
     """The two probes bench.py quotes rooflines against: a plain streaming read reaches most of, and no more than, the
-    published 8 TB/s; the matrix-core loop most of, and no more than, the published 2.5 PFLOP/s."""
+    published 8 TB/s; the matrix-core loop (operands of pseudo-random values: power-limited) a good part of, and no more
+    than, the published 2.5 PFLOP/s."""
     buf = torch.empty(1 << 30, dtype=torch.uint8, device=device)
     gbs = api.probe_hbm_read(buf, reps=5)
-    tf = api.probe_mfma_bf16(reps=2)
+    tf = api.probe_mfma(reps=2)
     assert 3000 < gbs < 8000, gbs
     assert 1000 < tf < 2600, tf
     with pytest.raises(api.DlmError):
