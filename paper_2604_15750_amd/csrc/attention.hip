@@ -98,12 +98,25 @@ __global__ __launch_bounds__(256) void attention_kernel(const T* __restrict__ q,
 
 // ---- bf16 models: on the matrix cores, half-precision operands (attention_core.h) -----------------------------
 // One workgroup per (16-query tile, head, sequence), or DS of them with a share of the head's output dims each.
+// per_unit = 0: grid (tiles * DS, heads, sequences).  per_unit > 0: a 1-D grid in which the per_unit workgroups that read the
+// same K and V (the query tiles, output-dim shares and query heads of one kv head of one sequence) have ids congruent mod 8:
+// they run on the same XCD, and all but the first reader find K and V in its L2 (the XCDs' L2s are separate: spread over
+// them, every tile of a block fetches its own copy from memory).
 template <int HD, int NWV, int DS>
 __global__ __launch_bounds__(NWV * 64) void attention_mfma_kernel(const f16_t* __restrict__ q, const f16_t* __restrict__ kcache,
                                                                   const f16_t* __restrict__ vcache, size_t slot_stride, size_t head_stride,
-                                                                  AttnMeta meta, op_t* __restrict__ out_tiles, bf16_t* __restrict__ out_rows, int n_q, int n_kv) {
+                                                                  AttnMeta meta, op_t* __restrict__ out_tiles, bf16_t* __restrict__ out_rows, int n_q, int n_kv,
+                                                                  int per_unit, int tiles) {
   __shared__ AttnLds<HD, NWV, DS> L;
-  const int b = blockIdx.z, head = blockIdx.y, tile = blockIdx.x / DS, dpart = blockIdx.x - tile * DS;
+  int b = blockIdx.z, head = blockIdx.y, x = blockIdx.x;
+  if (per_unit > 0) {
+    const int j = blockIdx.x >> 3, w = j % per_unit, unit = (j / per_unit) * 8 + (blockIdx.x & 7);
+    if (unit >= n_kv * meta.n_seqs) return;
+    b = unit / n_kv;
+    head = (unit - b * n_kv) * (n_q / n_kv) + w / (tiles * DS);
+    x = w % (tiles * DS);
+  }
+  const int tile = x / DS, dpart = x - tile * DS;
   const int row0 = meta.row_off[b] + tile * 16;
   const int row_end = meta.row_off[b + 1];
   if (row0 >= row_end) return;
@@ -149,7 +162,16 @@ void launch_attention_f16(const f16_t* q, const f16_t* kcache, const f16_t* vcac
   // loads, and the output dims of a head split over four workgroups (two for 64 dims) to spread its K / V traffic
   const bool narrow = (size_t)tiles * n_q * meta.n_seqs < 128 && hd >= 64;
   const bool wide = (size_t)tiles * n_q * meta.n_seqs >= 512;  // enough workgroups to fill the chip with 4 wavefronts each
-#define GO(HD, NWV, DS) attention_mfma_kernel<HD, NWV, DS><<<dim3(tiles * DS, n_q, meta.n_seqs), NWV * 64, 0, st>>>(q, kcache, vcache, slot_stride, head_stride, meta, out_tiles, out_rows, n_q, n_kv)
+  // enough (kv head, sequence) units to keep every XCD busy: the workgroups of a unit share an XCD (see the kernel)
+  const int units = n_kv * meta.n_seqs;
+  const bool by_unit = units >= 64;
+#define GO(HD, NWV, DS)                                                                                                                          \
+  do {                                                                                                                                           \
+    const int per_unit = by_unit ? tiles * DS * (n_q / n_kv) : 0;                                                                                \
+    const dim3 grid = by_unit ? dim3((units + 7) / 8 * 8 * per_unit) : dim3(tiles * DS, n_q, meta.n_seqs);                                       \
+    attention_mfma_kernel<HD, NWV, DS><<<grid, NWV * 64, 0, st>>>(q, kcache, vcache, slot_stride, head_stride, meta, out_tiles, out_rows, n_q,   \
+                                                                  n_kv, per_unit, tiles);                                                        \
+  } while (0)
   if (hd == 32) { if (wide) GO(32, 4, 1); else GO(32, 8, 1); }
   else if (hd == 64) { if (narrow) GO(64, 8, 2); else if (wide) GO(64, 4, 1); else GO(64, 8, 1); }
   else { if (narrow) GO(128, 8, 4); else if (wide) GO(128, 4, 1); else GO(128, 8, 1); }
