@@ -308,8 +308,9 @@ MacroPlan macro_plan(int M, int N, int K, bool may_split) {
     const bool two = g_macro_shared_pair[c] > 0 && rounds >= 2;
     const double turns = two ? (rounds / 2) * g_macro_shared_pair[c] + (rounds & 1) * g_macro_shared_single[c] : rounds;
     // microseconds: the rounds' products, 1 / sp of K each; a split launch also writes and re-reads one partial tile (8 bytes per
-    // element) per workgroup, at about 2.5 TB/s over the chip
-    const double cost = turns * bm * bn * g_macro_penalty[c] * K * g_macro_us_per_mac / sp + (sp > 1 ? (double)tiles * sp * bm * bn * 3.2e-6 : 0.0);
+    // element) per workgroup, at about 2.5 TB/s over the chip, and its last arriver fetches the splits one trip after another
+    const double cost = turns * bm * bn * g_macro_penalty[c] * K * g_macro_us_per_mac / sp + (sp > 1 ? (double)tiles * sp * bm * bn * 3.2e-6 : 0.0) +
+                        (sp > 2 ? 4.0 * (sp - 2) : 0.0);
     if (cost < best_cost) { best_cost = cost; best = MacroPlan{cand[c][0], cand[c][1], cand[c][2], nb, mb, sp, kps, two}; }
   }
   return best;
