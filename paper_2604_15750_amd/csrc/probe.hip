@@ -112,7 +112,7 @@ extern "C" int dlm_probe_hbm_read(const void* src, size_t bytes, int reps, doubl
 
 extern "C" int dlm_probe_mfma(int reps, double* tflop_per_s, void* stream) {
   REQUIRE(tflop_per_s && reps >= 1, DLM_EINVAL, "dlm_probe_mfma: bad argument");
-  constexpr int WGS = 2048, ITERS = 2048;
+  constexpr int WGS = 2048, ITERS = 8192;  // 14 ms per launch: long enough for the clock to settle at what the power limit allows
   hipStream_t st = (hipStream_t)stream;
   float* sink = nullptr;
   if (hipMalloc(&sink, 4) != hipSuccess) { (void)hipGetLastError(); return dlm_fail(DLM_ENOMEM, "dlm_probe_mfma: allocation failed"); }
