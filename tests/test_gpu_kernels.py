@@ -53,6 +53,35 @@ def test_gemm_bf16(device, M, N, K):
     assert np.abs(got - ref).mean() <= 4e-3 * np.abs(ref).mean() + 1e-6
 
 
+@pytest.mark.parametrize("M", [8, 100, 300])
+def test_gemm_operand_conversion_at_the_ends_of_halfs_range(device, M):
+    """A bf16 model's matrix-core operands are IEEE half.  Weights far below half's smallest normal number (2^-14) land on its
+    subnormal grid: each keeps an absolute error of at most 2^-25.  Activations beyond half's largest number saturate at
+    +-65504 instead of becoming infinite.  Everything in between converts exactly (covered by test_gemm_bf16)."""
+    N, K = 256, 512
+    g = torch.Generator(device="cpu").manual_seed(M)
+    x = torch.randn(M, K, generator=g).to(torch.bfloat16)
+    w = (torch.randn(N, K, generator=g) * 2.0 ** -17).to(torch.bfloat16)  # most of them subnormal in half, many below its resolution
+    y = api.dlm_gemm_nt(x.to(device), w.to(device))
+    torch.cuda.synchronize()
+    ref = o_fwd.matmul_nt(_np(x), _np(w))
+    got = o_fwd.widen(_np(y))
+    bound = 2.0 ** -25 * np.abs(o_fwd.widen(_np(x))).sum(-1, keepdims=True) + 2.0 ** -8 * np.abs(ref) + 1e-12
+    assert (np.abs(got - ref) <= bound).all(), (np.abs(got - ref) / bound).max()
+    assert np.abs(ref).max() > 0 and np.abs(got).max() > 0.25 * np.abs(ref).max()  # (not flushed to zero)
+    # saturation: one activation per row far beyond 65504
+    x2 = x.clone()
+    x2[:, 3] = 3.0e5
+    w2 = (torch.randn(N, K, generator=g) * 0.05).to(torch.bfloat16)
+    y2 = api.dlm_gemm_nt(x2.to(device), w2.to(device))
+    torch.cuda.synchronize()
+    got2 = o_fwd.widen(_np(y2))
+    assert np.isfinite(got2).all()
+    xc = o_fwd.widen(_np(x2)).clip(-65504.0, 65504.0)
+    ref2 = xc @ o_fwd.widen(_np(w2)).T
+    assert (np.abs(got2 - ref2) <= _rowtol(ref2, 2e-2)).all()
+
+
 @pytest.mark.parametrize("M,N,K", [(1, 1, 1), (5, 7, 3), (64, 128, 128), (130, 1024, 384), (67, 384, 129)])
 def test_gemm_f32(device, M, N, K):
     g = torch.Generator(device="cpu").manual_seed(M + N + K)
