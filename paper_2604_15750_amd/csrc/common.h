@@ -153,7 +153,7 @@ void launch_pack_weight(const bf16_t* w, op_t* out, int N, int K, int perm, int 
 // chip's reads at any moment are one moving window instead of thousands of separate streams.
 void launch_pack_weight_steps(const bf16_t* w, op_t* out, int N, int K, int ct, int perm, int perm_param, hipStream_t st);
 int gemm_bf16_steps_ct(int N, int K, int kind);  // ct of that layout for (N, K) under epilogue `kind`, 0 if the kernel that serves 16 rows has none
-int gemm_mid_steps_ct(int N, int K, int kind);   // ... if the mid kernel serves (N, K) at up to 16 rows without a K split, else 0
+int gemm_mid_steps_ct(int N, int K);   // ... if the mid kernel serves (N, K) at up to 16 rows without a K split, else 0
 void launch_pack_act(const bf16_t* x, op_t* out, int M, int K, hipStream_t st);  // row-major bf16 -> fragment tiles in half (rows padded to 16 with zeros)
 int gemm_bf16_splits(int M, int N, int K, int kind);  // partial tiles [splits][M][N] the launch of this shape and epilogue needs in GemmEpi::part (1: none)
 int gemm_bf16_ssq_chunks(int M, int N, int K);     // chunks per row of the sums of squares an EPI_RESID launch of this shape writes
@@ -222,15 +222,15 @@ void launch_gemm_skinny(const op_t* xt, const op_t* wt, int pr, int M, int N, in
 void launch_gemm_tiled(const op_t* xt, const op_t* wt, int M, int N, int K, const GemmEpi& e, hipStream_t st);
 #define GEMM_MID_MAX_ROWS 160  // 65 .. this many rows: the mid kernel (all rows in one workgroup, wavefronts split K)
 #define GEMM_MID_MAX_ROWS_NARROW 256  // ... for matrices of at most 8192 columns
-int gemm_mid_splits(int M, int N, int K, int kind);
+int gemm_mid_splits(int M, int N, int K);
 int gemm_mid_ssq_chunks(int M, int N, int K);
-bool gemm_mid_fills_chip(int M, int N, int K, int kind);  // its column groups are a whole number of rounds over the compute units, without a K split
+bool gemm_mid_fills_chip(int M, int N, int K);  // its column groups are a whole number of rounds over the compute units, without a K split
 int gemm_mid_counters(int max_n);
 void gemm_mid_set_target(int wgs);  // tuning: workgroups the K split aims at
 void launch_gemm_mid(const op_t* xt, const op_t* wt, int M, int N, int K, const GemmEpi& e, hipStream_t st);  // M <= GEMM_MID_MAX_ROWS(_NARROW); narrow matrices from 17 rows
 #define GEMM_MACRO_MIN_ROWS_NARROW 256  // more rows than this: the macro-tile kernel whatever the width
 int gemm_macro_ssq_chunks(int M, int N, int K);
-int gemm_macro_splits(int M, int N, int K, int kind);
+int gemm_macro_splits(int M, int N, int K);
 int gemm_macro_counters(int max_rows, int max_n);
 void gemm_macro_set_target(int wgs);  // tuning: workgroups the K split aims at
 void gemm_macro_set_penalty(int tile, double p);  // tuning: relative cost per product of tile candidate 0 .. 4 (256x256, 128x256, 128x128, 192x256, 256x192)

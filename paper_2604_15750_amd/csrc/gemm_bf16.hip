@@ -93,7 +93,7 @@ int choose_kernel(int M, int N, int K, int kind) {
   const int pr = weight_pack_rows(N);
   const bool whole_groups = N % (16 * pr) == 0;
   if (M <= GEMM_SKINNY_MAX_ROWS && kind != EPI_DIRECT && whole_groups) {
-    if (pr == 2 && (M > 16 || gemm_mid_fills_chip(M, N, K, kind))) return KERNEL_MID;
+    if (pr == 2 && (M > 16 || gemm_mid_fills_chip(M, N, K))) return KERNEL_MID;
     if (pr == 1 && M > 16 && K >= 8192) return KERNEL_MID;
     // a narrow matrix with a few more than 256 column tiles: the skinny kernel's one-tile workgroups would run a second,
     // nearly empty round over the compute units; 32-column groups fit in one
@@ -119,7 +119,7 @@ void launch_pack_weight_steps(const bf16_t* w, op_t* out, int N, int K, int ct, 
 }
 int gemm_bf16_steps_ct(int N, int K, int kind) {
   switch (choose_kernel(16, N, K, kind)) {
-    case KERNEL_MID: return gemm_mid_steps_ct(N, K, kind);
+    case KERNEL_MID: return gemm_mid_steps_ct(N, K);
     case KERNEL_SKINNY: {  // one column tile and 8 wavefronts per workgroup, or a pair of tiles and 4
       const int pr = weight_pack_rows(N);
       return ((K >> 5) % (pr == 1 ? 8 : 4) == 0 && N % (16 * pr) == 0) ? pr : 0;
@@ -133,8 +133,8 @@ void launch_pack_act(const bf16_t* x, op_t* out, int M, int K, hipStream_t st) {
 
 int gemm_bf16_splits(int M, int N, int K, int kind) {
   switch (choose_kernel(M, N, K, kind)) {
-    case KERNEL_MID: return gemm_mid_splits(M, N, K, kind);
-    case KERNEL_MACRO: return gemm_macro_splits(M, N, K, kind);
+    case KERNEL_MID: return gemm_mid_splits(M, N, K);
+    case KERNEL_MACRO: return gemm_macro_splits(M, N, K);
     case KERNEL_TILED: return gemm_tiled_splits(M, N, K);
     default: return 1;
   }

@@ -351,7 +351,7 @@ void launch_epi(const op_t* xt, const op_t* wt, int M, int N, int K, const Macro
 }  // namespace
 
 int gemm_macro_ssq_chunks(int M, int N, int K) { return macro_plan(M, N, K, true).nblocks; }  // (the plan of the launch itself)
-int gemm_macro_splits(int M, int N, int K, int) { return macro_plan(M, N, K, true).splits; }
+int gemm_macro_splits(int M, int N, int K) { return macro_plan(M, N, K, true).splits; }
 int gemm_macro_counters(int max_rows, int max_n) { return ((max_n + 127) / 128) * ((max_rows + 127) / 128); }  // 128 x 128 tiles are the smallest
 void gemm_macro_set_target(int wgs) { g_macro_wgs = wgs; }
 void gemm_macro_set_penalty(int tile, double p) {

@@ -376,17 +376,17 @@ void launch_epi(const op_t* xt, const op_t* wt, int M, int N, int K, const MidPl
 }  // namespace
 
 // one compute unit's worth of workgroups per 96-column group, no K split: the shapes the mid kernel takes even below 17 rows
-bool gemm_mid_fills_chip(int M, int N, int K, int) {
+bool gemm_mid_fills_chip(int M, int N, int K) {
   const MidPlan p = mid_plan(M, N, K, true);
   return p.splits == 1 && p.groups % 256 == 0;
 }
-int gemm_mid_splits(int M, int N, int K, int) { return mid_plan(M, N, K, true).splits; }
+int gemm_mid_splits(int M, int N, int K) { return mid_plan(M, N, K, true).splits; }
 int gemm_mid_ssq_chunks(int M, int N, int K) { return mid_plan(M, N, K, true).groups; }
 int gemm_mid_counters(int max_n) { return (max_n + 31) / 32; }  // 32-column groups are the narrowest
 void gemm_mid_set_target(int wgs) { g_mid_wgs = wgs; }
 
 
-int gemm_mid_steps_ct(int N, int K, int) {
+int gemm_mid_steps_ct(int N, int K) {
   const MidPlan p = mid_plan(16, N, K, true);
   return (p.splits == 1 && N % (16 * p.ct) == 0 && (K >> 5) % NWV == 0) ? p.ct : 0;
 }
