@@ -37,25 +37,30 @@ __device__ inline __amdgpu_buffer_rsrc_t part_rsrc(const float* base) {
 #define GLOBAL_PTR(p) ((const void __attribute__((address_space(1)))*)(p))
 #define LDS_PTR(p) ((void __attribute__((address_space(3)))*)(p))
 
-template <int WM, int WN, int NW = 4, bool TWO = false>
+// KB: k-tiles per pipeline stage (and barrier).  With one wavefront per SIMD nothing hides what a step costs besides its
+// products (barrier, copy issue, waits): a 128 x 128 tile that has a compute unit to itself takes two k-tiles per step (four
+// stages of 32 KiB; -10 % at 256 .. 1024 rows of the layer matrices.  For 128 x 256 the stages would be 48 KiB, three deep:
+// measured slower than one k-tile per step, five deep).
+template <int WM, int WN, int NW = 4, bool TWO = false, int KB = 1>
 struct MacroShape {
   static constexpr int TPB = NW * 64;
   static constexpr int AT = (NW / 2) * WM;         // row tiles of the workgroup
-  static constexpr int AF = AT, BF = 2 * WN;       // X (row) and W (column) fragments of a stage
+  static constexpr int AF = AT, BF = 2 * WN;       // X (row) and W (column) fragments of a k-tile
   static constexpr int NFR = AF + BF;
-  static constexpr int LPS = (NFR + NW - 1) / NW;  // direct-to-LDS loads per wavefront and stage (surplus ones repeat the last fragment)
-  static constexpr int STAGE = NFR * 1024;
+  static constexpr int LPT = (NFR + NW - 1) / NW;  // direct-to-LDS loads per wavefront and k-tile (surplus ones repeat the last fragment)
+  static constexpr int LPS = KB * LPT;             // ... and stage
+  static constexpr int STAGE = KB * NFR * 1024;
   // TWO: two workgroups share a compute unit (three stages each; see macro_plan)
   static constexpr int LDSB = TWO ? 75776 : 131072;
   static constexpr int S = LDSB / STAGE > 8 ? 8 : LDSB / STAGE;  // stages: at most 128 KiB (of the 160 KiB of a compute unit)
   static constexpr int LDS_BYTES = S * STAGE + AT * 16 * 4 * 3;      // + 1/rms of the rows, two partial sums of squares per row
 };
 
-template <int WM, int WN, int PR, int EPI, int NW = 4, bool TWO = false>
+template <int WM, int WN, int PR, int EPI, int NW = 4, bool TWO = false, int KB = 1>
 __global__ __launch_bounds__(NW * 64, TWO ? 2 : 1) void gemm_macro_kernel(const op8* __restrict__ xt, const op8* __restrict__ wt, int M, int N,
                                                                           int K, int nblocks, int mblocks, int splits, int kt_per_split, GemmEpi e) {
-  typedef MacroShape<WM, WN, NW, TWO> SH;
-  constexpr int TPB = SH::TPB, AT = SH::AT, AF = SH::AF, BF = SH::BF, LPS = SH::LPS, STAGE = SH::STAGE, S = SH::S;
+  typedef MacroShape<WM, WN, NW, TWO, KB> SH;
+  constexpr int TPB = SH::TPB, AT = SH::AT, AF = SH::AF, BF = SH::BF, NFR = SH::NFR, LPT = SH::LPT, LPS = SH::LPS, STAGE = SH::STAGE, S = SH::S;
   static_assert(AF % NW == 0 && S >= 3 && (S - 2) * LPS < 64, "pipeline shape");
   extern __shared__ __align__(16) unsigned char lds[];
   float* s_rinv = (float*)(lds + S * STAGE);  // [AT * 16]
@@ -75,14 +80,16 @@ __global__ __launch_bounds__(NW * 64, TWO ? 2 : 1) void gemm_macro_kernel(const 
   const int KT = K >> 5, MTILES = (M + 15) >> 4, NT = N >> 4;
   const int mt0 = rb * AT, nt0 = cb * BF;
 
-  // stage kt % S <- k-tile kt: fragment f (f < AF: X row tile mt0 + f, else W column tile nt0 + f - AF) is
-  // moved by wavefront f % NW
-  const int kb = split * kt_per_split, nk = min(KT, kb + kt_per_split) - kb;  // this workgroup's k-tiles: kb .. kb + nk - 1
+  // stage kt % S <- k-tiles kt KB .. kt KB + KB - 1 (the host gives every workgroup a whole number of stages): fragment f of a
+  // k-tile (f < AF: X row tile mt0 + f, else W column tile nt0 + f - AF) is moved by wavefront f % NW
+  const int kb = split * kt_per_split, nk = (min(KT, kb + kt_per_split) - kb) / KB;  // this workgroup's stages: k-tiles kb .. kb + nk KB - 1
   auto issue = [&](int kt) {
-    const int t = kb + min(kt, nk - 1);
-    unsigned char* base = lds + (kt % S) * STAGE;
 #pragma unroll
-    for (int i = 0; i < LPS; ++i) {
+    for (int sub = 0; sub < KB; ++sub) {
+    const int t = kb + min(kt, nk - 1) * KB + sub;
+    unsigned char* base = lds + (kt % S) * STAGE + sub * NFR * 1024;
+#pragma unroll
+    for (int i = 0; i < LPT; ++i) {
       const int f = i * NW + wave;
       const op8* src;
       if (i < AF / NW) {
@@ -97,6 +104,7 @@ __global__ __launch_bounds__(NW * 64, TWO ? 2 : 1) void gemm_macro_kernel(const 
       }
       __builtin_amdgcn_global_load_lds(GLOBAL_PTR(src), LDS_PTR(base + f * 1024), 16, 0, 0);
     }
+    }
   };
 
   f32x4 acc[WN][WM];
@@ -104,19 +112,24 @@ __global__ __launch_bounds__(NW * 64, TWO ? 2 : 1) void gemm_macro_kernel(const 
   for (int j = 0; j < WN; ++j)
 #pragma unroll
     for (int i = 0; i < WM; ++i) acc[j][i] = f32x4{0.f, 0.f, 0.f, 0.f};
-  op8 xf[2][WM], wf[2][WN];
+  op8 xf[2][KB][WM], wf[2][KB][WN];
   auto read_frags = [&](int buf, int kt) {
-    const op8* st = (const op8*)(lds + (kt % S) * STAGE) + lane;
 #pragma unroll
-    for (int i = 0; i < WM; ++i) xf[buf][i] = st[(wm * WM + i) * 64];
+    for (int sub = 0; sub < KB; ++sub) {
+      const op8* st = (const op8*)(lds + (kt % S) * STAGE + sub * NFR * 1024) + lane;
 #pragma unroll
-    for (int j = 0; j < WN; ++j) wf[buf][j] = st[(AF + wn * WN + j) * 64];
+      for (int i = 0; i < WM; ++i) xf[buf][sub][i] = st[(wm * WM + i) * 64];
+#pragma unroll
+      for (int j = 0; j < WN; ++j) wf[buf][sub][j] = st[(AF + wn * WN + j) * 64];
+    }
   };
   auto multiply = [&](int buf) {
 #pragma unroll
-    for (int j = 0; j < WN; ++j)
+    for (int sub = 0; sub < KB; ++sub)
 #pragma unroll
-      for (int i = 0; i < WM; ++i) acc[j][i] = mfma_op(wf[buf][j], xf[buf][i], acc[j][i]);
+      for (int j = 0; j < WN; ++j)
+#pragma unroll
+        for (int i = 0; i < WM; ++i) acc[j][i] = mfma_op(wf[buf][sub][j], xf[buf][sub][i], acc[j][i]);
   };
 
   // 1/rms of the workgroup's input rows, needed only by the epilogue: fetched before the pipeline starts (its loads are counted
@@ -144,7 +157,7 @@ __global__ __launch_bounds__(NW * 64, TWO ? 2 : 1) void gemm_macro_kernel(const 
     // Issue order, fixed by hand: the products (which depend on registers only) start right behind the barrier, and the copies
     // and the LDS reads of the next k-tile go out between them.  Left alone, the scheduler puts the reads next to their uses,
     // and all wavefronts of a SIMD, which leave the barrier together, would issue their loads while its matrix core idles.
-    constexpr int NM = WN * WM, RF = WM + WN;
+    constexpr int NM = KB * WN * WM, RF = KB * (WM + WN);
     constexpr int OPS = 2 * (LPS + RF) <= NM ? 1 : 2;  // copies / reads per product: all of them go out in the first half of the products,
                                                         // so that the last read has the second half's time to return
 #pragma unroll
@@ -272,6 +285,7 @@ __global__ __launch_bounds__(NW * 64, TWO ? 2 : 1) void gemm_macro_kernel(const 
 struct MacroPlan {
   int wm, wn, nw, nblocks, mblocks, splits, kps;
   bool two;  // two workgroups per compute unit (the three-stage variant of a four-wavefront tile)
+  int kb;    // k-tiles per pipeline stage
 };
 
 // the tile with the least estimated time: rounds of workgroups over the chip x products per workgroup, each tile charged
@@ -280,18 +294,18 @@ int g_macro_wgs = 256;  // workgroups a K split aims at
 constexpr int NCAND = 5;
 // time of a round of workgroups over the chip / tile area, relative to 128 x 256 with four wavefronts (measured on the layer
 // matrices of an 8B model with random operand values)
-double g_macro_penalty[NCAND] = {0.63, 1.0, 1.21, 0.86, 0.72};
-// A four-wavefront tile of single planes that needs two or more rounds runs as two workgroups per compute unit, three stages
-// each: the pair hides each other's barriers, waits and output stores and takes 1.45 of one deep workgroup's time instead of 2;
-// the odd round's workgroups run at about the deep variant's pace (measured at 256 .. 2048 rows, operands of random values:
+double g_macro_penalty[NCAND] = {0.63, 1.0, 1.08, 0.86, 0.72};
+// A four-wavefront tile that needs two or more rounds runs as two workgroups per compute unit, three stages each: the pair
+// hides each other's barriers, waits and output stores and takes 1.45 (128 x 256) or 1.63 (128 x 128, against its faster
+// two-k-tile variant) of one deep workgroup's time instead of 2; the odd round's workgroups run at about the deep variant's pace (measured at 256 .. 2048 rows, operands of random values:
 // constant ones let the chip clock higher and flatter the large tiles).
-double g_macro_shared_pair[NCAND] = {0, 1.45, 1.45, 0, 0}, g_macro_shared_single[NCAND] = {0, 1.15, 0.9, 0, 0};
+double g_macro_shared_pair[NCAND] = {0, 1.45, 1.63, 0, 0}, g_macro_shared_single[NCAND] = {0, 1.15, 1.0, 0, 0};
 double g_macro_us_per_mac = 6.2e-7;  // a round of 128 x 256 tiles over the chip: microseconds per element of the tile and column of K
 
 MacroPlan macro_plan(int M, int N, int K, bool may_split) {
   // {WM, WN, wavefronts}: 256 x 256, 128 x 256, 128 x 128, 192 x 256, 256 x 192
   const int cand[NCAND][3] = {{4, 8, 8}, {4, 8, 4}, {4, 4, 4}, {6, 8, 4}, {4, 6, 8}};
-  MacroPlan best{4, 8, 4, 1, 1, 1, 0, false};
+  MacroPlan best{4, 8, 4, 1, 1, 1, 0, false, 1};
   double best_cost = 1e300;
   const int KT = K >> 5;
   for (int c = 0; c < NCAND; ++c) {
@@ -311,21 +325,23 @@ MacroPlan macro_plan(int M, int N, int K, bool may_split) {
     // element) per workgroup, at about 2.5 TB/s over the chip, and its last arriver fetches the splits one trip after another
     const double cost = turns * bm * bn * g_macro_penalty[c] * K * g_macro_us_per_mac / sp + (sp > 1 ? (double)tiles * sp * bm * bn * 3.2e-6 : 0.0) +
                         (sp > 2 ? 4.0 * (sp - 2) : 0.0);
-    if (cost < best_cost) { best_cost = cost; best = MacroPlan{cand[c][0], cand[c][1], cand[c][2], nb, mb, sp, kps, two}; }
+    // two k-tiles per stage: a 128 x 128 tile alone on its compute unit, every workgroup a whole number of such stages
+    const int kb = (cand[c][2] == 4 && cand[c][1] == 4 && !two && KT % sp == 0 && (KT / sp) % 2 == 0) ? 2 : 1;
+    if (cost < best_cost) { best_cost = cost; best = MacroPlan{cand[c][0], cand[c][1], cand[c][2], nb, mb, sp, kps, two, kb}; }
   }
   return best;
 }
 
-template <int WM, int WN, int NW, int PR, int EPI, bool TWO = false>
+template <int WM, int WN, int NW, int PR, int EPI, bool TWO = false, int KB = 1>
 void launch_one(const op_t* xt, const op_t* wt, int M, int N, int K, const MacroPlan& p, const GemmEpi& e, hipStream_t st) {
-  typedef MacroShape<WM, WN, NW, TWO> SH;
+  typedef MacroShape<WM, WN, NW, TWO, KB> SH;
   static bool configured = false;  // raise the dynamic LDS limit of this instantiation once
   if (!configured) {
-    (void)hipFuncSetAttribute((const void*)gemm_macro_kernel<WM, WN, PR, EPI, NW, TWO>, hipFuncAttributeMaxDynamicSharedMemorySize, SH::LDS_BYTES);
+    (void)hipFuncSetAttribute((const void*)gemm_macro_kernel<WM, WN, PR, EPI, NW, TWO, KB>, hipFuncAttributeMaxDynamicSharedMemorySize, SH::LDS_BYTES);
     configured = true;
   }
   const int grid = (p.nblocks + 7) / 8 * 8 * p.mblocks * p.splits;
-  DLM_LAUNCH((gemm_macro_kernel<WM, WN, PR, EPI, NW, TWO>), grid, SH::TPB, SH::LDS_BYTES, st, (const op8*)xt, (const op8*)wt, M, N, K, p.nblocks,
+  DLM_LAUNCH((gemm_macro_kernel<WM, WN, PR, EPI, NW, TWO, KB>), grid, SH::TPB, SH::LDS_BYTES, st, (const op8*)xt, (const op8*)wt, M, N, K, p.nblocks,
              p.mblocks, p.splits, p.kps, e);
 }
 
@@ -338,6 +354,7 @@ void launch_shape(const op_t* xt, const op_t* wt, int M, int N, int K, const Mac
     if (p.wn == 8) launch_one<4, 8, 4, PR, EPI, true>(xt, wt, M, N, K, p, e, st);
     else launch_one<4, 4, 4, PR, EPI, true>(xt, wt, M, N, K, p, e, st);
   }
+  else if (p.kb == 2) launch_one<4, 4, 4, PR, EPI, false, 2>(xt, wt, M, N, K, p, e, st);
   else if (p.wn == 8) launch_one<4, 8, 4, PR, EPI>(xt, wt, M, N, K, p, e, st);
   else launch_one<4, 4, 4, PR, EPI>(xt, wt, M, N, K, p, e, st);
 }
