@@ -37,10 +37,11 @@ __device__ inline __amdgpu_buffer_rsrc_t part_rsrc(const float* base) {
 #define GLOBAL_PTR(p) ((const void __attribute__((address_space(1)))*)(p))
 #define LDS_PTR(p) ((void __attribute__((address_space(3)))*)(p))
 
-// KB: k-tiles per pipeline stage (and barrier).  With one wavefront per SIMD nothing hides what a step costs besides its
-// products (barrier, copy issue, waits): a 128 x 128 tile that has a compute unit to itself takes two k-tiles per step (four
-// stages of 32 KiB; -10 % at 256 .. 1024 rows of the layer matrices.  For 128 x 256 the stages would be 48 KiB, three deep:
-// measured slower than one k-tile per step, five deep).
+// KB: k-tiles per pipeline stage (and barrier).  A 128 x 128 tile has few products per k-tile to set against what a step
+// costs besides them (barrier, copy issue, waits): when it has a compute unit to itself it is run by eight wavefronts of
+// 32 x 64 outputs (two per SIMD, which hide each other's waits) and takes two k-tiles per step (four stages of 32 KiB):
+// -10 % for the two k-tiles and another -10 % for the eight wavefronts at 256 .. 1024 rows of the layer matrices.  (For
+// 128 x 256 the stages would be 48 KiB, three deep: measured slower than one k-tile per step, five deep.)
 template <int WM, int WN, int NW = 4, bool TWO = false, int KB = 1>
 struct MacroShape {
   static constexpr int TPB = NW * 64;
@@ -294,12 +295,12 @@ int g_macro_wgs = 256;  // workgroups a K split aims at
 constexpr int NCAND = 5;
 // time of a round of workgroups over the chip / tile area, relative to 128 x 256 with four wavefronts (measured on the layer
 // matrices of an 8B model with random operand values)
-double g_macro_penalty[NCAND] = {0.63, 1.0, 1.08, 0.86, 0.72};
+double g_macro_penalty[NCAND] = {0.63, 1.0, 0.96, 0.86, 0.72};
 // A four-wavefront tile that needs two or more rounds runs as two workgroups per compute unit, three stages each: the pair
-// hides each other's barriers, waits and output stores and takes 1.45 (128 x 256) or 1.63 (128 x 128, against its faster
-// two-k-tile variant) of one deep workgroup's time instead of 2; the odd round's workgroups run at about the deep variant's pace (measured at 256 .. 2048 rows, operands of random values:
+// hides each other's barriers, waits and output stores and takes 1.45 (128 x 256) or 1.83 (128 x 128, against its faster
+// eight-wavefront variant) of one deep workgroup's time instead of 2; the odd round's workgroups run at about the deep variant's pace (measured at 256 .. 2048 rows, operands of random values:
 // constant ones let the chip clock higher and flatter the large tiles).
-double g_macro_shared_pair[NCAND] = {0, 1.45, 1.63, 0, 0}, g_macro_shared_single[NCAND] = {0, 1.15, 1.0, 0, 0};
+double g_macro_shared_pair[NCAND] = {0, 1.45, 1.83, 0, 0}, g_macro_shared_single[NCAND] = {0, 1.15, 1.12, 0, 0};
 double g_macro_us_per_mac = 6.2e-7;  // a round of 128 x 256 tiles over the chip: microseconds per element of the tile and column of K
 
 MacroPlan macro_plan(int M, int N, int K, bool may_split) {
@@ -325,9 +326,11 @@ MacroPlan macro_plan(int M, int N, int K, bool may_split) {
     // element) per workgroup, at about 2.5 TB/s over the chip, and its last arriver fetches the splits one trip after another
     const double cost = turns * bm * bn * g_macro_penalty[c] * K * g_macro_us_per_mac / sp + (sp > 1 ? (double)tiles * sp * bm * bn * 3.2e-6 : 0.0) +
                         (sp > 2 ? 4.0 * (sp - 2) : 0.0);
-    // two k-tiles per stage: a 128 x 128 tile alone on its compute unit, every workgroup a whole number of such stages
-    const int kb = (cand[c][2] == 4 && cand[c][1] == 4 && !two && KT % sp == 0 && (KT / sp) % 2 == 0) ? 2 : 1;
-    if (cost < best_cost) { best_cost = cost; best = MacroPlan{cand[c][0], cand[c][1], cand[c][2], nb, mb, sp, kps, two, kb}; }
+    // a 128 x 128 tile alone on its compute unit: eight wavefronts, and two k-tiles per stage if every workgroup has a whole
+    // number of such stages
+    const bool alone = cand[c][2] == 4 && cand[c][1] == 4 && !two;
+    const int kb = (alone && KT % sp == 0 && (KT / sp) % 2 == 0) ? 2 : 1;
+    if (cost < best_cost) { best_cost = cost; best = MacroPlan{alone ? 2 : cand[c][0], cand[c][1], alone ? 8 : cand[c][2], nb, mb, sp, kps, two, kb}; }
   }
   return best;
 }
@@ -347,16 +350,18 @@ void launch_one(const op_t* xt, const op_t* wt, int M, int N, int K, const Macro
 
 template <int PR, int EPI>
 void launch_shape(const op_t* xt, const op_t* wt, int M, int N, int K, const MacroPlan& p, const GemmEpi& e, hipStream_t st) {
-  if (p.nw == 8 && p.wn == 6) launch_one<4, 6, 8, PR, EPI>(xt, wt, M, N, K, p, e, st);
+  if (p.nw == 8 && p.wm == 2) {
+    if (p.kb == 2) launch_one<2, 4, 8, PR, EPI, false, 2>(xt, wt, M, N, K, p, e, st);
+    else launch_one<2, 4, 8, PR, EPI>(xt, wt, M, N, K, p, e, st);
+  }
+  else if (p.nw == 8 && p.wn == 6) launch_one<4, 6, 8, PR, EPI>(xt, wt, M, N, K, p, e, st);
   else if (p.nw == 8) launch_one<4, 8, 8, PR, EPI>(xt, wt, M, N, K, p, e, st);
   else if (p.wm == 6) launch_one<6, 8, 4, PR, EPI>(xt, wt, M, N, K, p, e, st);
   else if (p.two) {
     if (p.wn == 8) launch_one<4, 8, 4, PR, EPI, true>(xt, wt, M, N, K, p, e, st);
     else launch_one<4, 4, 4, PR, EPI, true>(xt, wt, M, N, K, p, e, st);
   }
-  else if (p.kb == 2) launch_one<4, 4, 4, PR, EPI, false, 2>(xt, wt, M, N, K, p, e, st);
-  else if (p.wn == 8) launch_one<4, 8, 4, PR, EPI>(xt, wt, M, N, K, p, e, st);
-  else launch_one<4, 4, 4, PR, EPI>(xt, wt, M, N, K, p, e, st);
+  else launch_one<4, 8, 4, PR, EPI>(xt, wt, M, N, K, p, e, st);
 }
 
 template <int EPI>
