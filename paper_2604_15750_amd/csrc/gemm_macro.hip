@@ -5,8 +5,9 @@
 // cores and by how often operands are re-read.  A workgroup of NW wavefronts (NW / 2 x 2) owns a tile of
 // 8 NW WM rows x 32 WN columns: 256 x 256 with eight wavefronts (two per SIMD, 128 accumulator registers
 // each: what a compute unit fetches per product is half of what a 128 x 256 tile needs, and that fetch rate,
-// L2 / memory-side cache -> LDS, is what bounds the smaller tiles), or 192 x 256, 128 x 256, 128 x 128 with
-// four wavefronts where the larger tile would leave compute units idle; it walks K one k-tile (32) at a time:
+// L2 / memory-side cache -> LDS, is what bounds the smaller tiles), or 192 x 256, 128 x 256 with four
+// wavefronts and 128 x 128 with eight where the larger tile would leave compute units idle; it walks K one
+// k-tile (32) at a time (two for 128 x 128):
 //   * both operands are already stored as 1 KiB matrix-core fragments (16 rows x 32 k), so a stage of
 //     the pipeline is just 2 WM + 2 WN fragments copied HBM/L2 -> LDS by direct-to-LDS loads (no
 //     registers, no LDS writes): 4 to 8 stages of 16 .. 32 KiB rotate through up to 128 KiB of LDS
@@ -310,6 +311,7 @@ MacroPlan macro_plan(int M, int N, int K, bool may_split) {
   double best_cost = 1e300;
   const int KT = K >> 5;
   for (int c = 0; c < NCAND; ++c) {
+    if (g_macro_penalty[c] <= 0) continue;  // (tuning: a candidate switched off)
     const int bm = 8 * cand[c][2] * cand[c][0], bn = 32 * cand[c][1];
     const int mb = (M + bm - 1) / bm, nb = (N + bn - 1) / bn, tiles = mb * nb;
     // tiles that cover at most half of the chip (narrow matrices at a few hundred rows): split K until they cover it
