@@ -80,7 +80,7 @@ __global__ void pack_act_kernel(const bf16x8* __restrict__ x, op8* __restrict__ 
 
 // Which kernel serves a shape (measured crossovers on the layer shapes of 7 .. 8 B models):
 //   skinny  up to 64 rows: nothing crosses workgroups, every wavefront streams W;
-//   mid     65 .. 160 rows (narrow matrices to 256, O and down to 208 / 224); and below that where its wider column groups pay: from 17 rows for
+//   mid     65 .. 160 rows (narrow matrices to 256, O and down to 208); and below that where its wider column groups pay: from 17 rows for
 //           wide matrices (QKV, gate/up) and for narrow ones whose K is long enough for a four-way split (down) - there
 //           the skinny kernel's re-reads of X by every 16- or 32-column group cost more than W itself - and at any row
 //           count when its 96-column groups are exactly one per compute unit (gate/up of an 8B model), or when the skinny
@@ -101,8 +101,8 @@ int choose_kernel(int M, int N, int K, int kind) {
     return KERNEL_SKINNY;
   }
   // narrow matrices: to 256 rows, except that the residual projections, which have the macro kernel to go to, leave the mid
-  // kernel where it starts to lose to it (measured: O from 224 rows, down from 240)
-  const int mid_rows = pr == 2 ? GEMM_MID_MAX_ROWS : kind != EPI_RESID ? GEMM_MID_MAX_ROWS_NARROW : K >= 8192 ? 224 : 208;
+  // kernel where it starts to lose to it (measured: O and down both from 224 rows)
+  const int mid_rows = pr == 2 ? GEMM_MID_MAX_ROWS : kind != EPI_RESID ? GEMM_MID_MAX_ROWS_NARROW : 208;
   if (M > GEMM_SKINNY_MAX_ROWS && M <= mid_rows && whole_groups) return KERNEL_MID;
   // EPI_RESID has no instantiation of the tiled kernel: what the mid kernel does not take goes to the macro kernel
   if (M > GEMM_MACRO_MIN_ROWS_NARROW || (M > GEMM_SKINNY_MAX_ROWS && N > 8192) || kind == EPI_RESID) return KERNEL_MACRO;
