@@ -233,7 +233,7 @@ int gemm_macro_ssq_chunks(int M, int N, int K);
 int gemm_macro_splits(int M, int N, int K);
 int gemm_macro_counters(int max_rows, int max_n);
 void gemm_macro_set_target(int wgs);  // tuning: workgroups the K split aims at
-void gemm_macro_set_penalty(int tile, double p);  // tuning: relative cost per product of tile candidate 0 .. 4 (256x256, 128x256, 128x128, 192x256, 256x192); 0 switches it off
+void gemm_macro_set_penalty(int tile, double p);  // tuning: relative cost per product of tile candidate 0 .. 5 (256x256, 128x256, 128x128, 192x256, 256x192, 192x192); 0 switches it off
 void launch_gemm_macro(const op_t* xt, const op_t* wt, int M, int N, int K, const GemmEpi& e, hipStream_t st);
 void launch_gemm_f32(const float* x, const float* w, float* y, int M, int N, int K, RowScale rs, hipStream_t st);
 

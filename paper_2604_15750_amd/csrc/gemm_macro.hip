@@ -6,8 +6,8 @@
 // 8 NW WM rows x 32 WN columns: 256 x 256 with eight wavefronts (two per SIMD, 128 accumulator registers
 // each: what a compute unit fetches per product is half of what a 128 x 256 tile needs, and that fetch rate,
 // L2 / memory-side cache -> LDS, is what bounds the smaller tiles), or 192 x 256, 128 x 256 with four
-// wavefronts and 128 x 128 with eight where the larger tile would leave compute units idle; it walks K one
-// k-tile (32) at a time (two for 128 x 128):
+// wavefronts and 192 x 192, 128 x 128 with eight where the larger tile would leave compute units idle; it walks
+// K one k-tile (32) at a time (two for 128 x 128):
 //   * both operands are already stored as 1 KiB matrix-core fragments (16 rows x 32 k), so a stage of
 //     the pipeline is just 2 WM + 2 WN fragments copied HBM/L2 -> LDS by direct-to-LDS loads (no
 //     registers, no LDS writes): 4 to 8 stages of 16 .. 32 KiB rotate through up to 128 KiB of LDS
@@ -63,7 +63,7 @@ __global__ __launch_bounds__(NW * 64, TWO ? 2 : 1) void gemm_macro_kernel(const 
                                                                           int K, int nblocks, int mblocks, int splits, int kt_per_split, GemmEpi e) {
   typedef MacroShape<WM, WN, NW, TWO, KB> SH;
   constexpr int TPB = SH::TPB, AT = SH::AT, AF = SH::AF, BF = SH::BF, NFR = SH::NFR, LPT = SH::LPT, LPS = SH::LPS, STAGE = SH::STAGE, S = SH::S;
-  static_assert(AF % NW == 0 && S >= 3 && (S - 2) * LPS < 64, "pipeline shape");
+  static_assert(S >= 3 && (S - 2) * LPS < 64, "pipeline shape");
   extern __shared__ __align__(16) unsigned char lds[];
   float* s_rinv = (float*)(lds + S * STAGE);  // [AT * 16]
   float* s_ssq = s_rinv + AT * 16;            // [2][AT * 16]
@@ -94,7 +94,7 @@ __global__ __launch_bounds__(NW * 64, TWO ? 2 : 1) void gemm_macro_kernel(const 
     for (int i = 0; i < LPT; ++i) {
       const int f = i * NW + wave;
       const op8* src;
-      if (i < AF / NW) {
+      if (AF % NW == 0 ? i < AF / NW : f < AF) {  // (uniform in the wavefront)
         const int mt = min(mt0 + f, MTILES - 1);
         src = xt + ((size_t)mt * KT + t) * 64 + lane;
       } else {
@@ -293,20 +293,20 @@ struct MacroPlan {
 // the tile with the least estimated time: rounds of workgroups over the chip x products per workgroup, each tile charged
 // for what it fetches per product (measured: see penalty), plus the partial-tile traffic of a K split
 int g_macro_wgs = 256;  // workgroups a K split aims at
-constexpr int NCAND = 5;
+constexpr int NCAND = 6;
 // time of a round of workgroups over the chip / tile area, relative to 128 x 256 with four wavefronts (measured on the layer
 // matrices of an 8B model with random operand values)
-double g_macro_penalty[NCAND] = {0.63, 1.0, 0.96, 0.86, 0.72};
+double g_macro_penalty[NCAND] = {0.63, 1.0, 0.96, 0.86, 0.72, 0.83};
 // A four-wavefront tile that needs two or more rounds runs as two workgroups per compute unit, three stages each: the pair
 // hides each other's barriers, waits and output stores and takes 1.45 (128 x 256) or 1.83 (128 x 128, against its faster
 // eight-wavefront variant) of one deep workgroup's time instead of 2; the odd round's workgroups run at about the deep variant's pace (measured at 256 .. 2048 rows, operands of random values:
 // constant ones let the chip clock higher and flatter the large tiles).
-double g_macro_shared_pair[NCAND] = {0, 1.45, 1.83, 0, 0}, g_macro_shared_single[NCAND] = {0, 1.15, 1.12, 0, 0};
+double g_macro_shared_pair[NCAND] = {0, 1.45, 1.83, 0, 0, 0}, g_macro_shared_single[NCAND] = {0, 1.15, 1.12, 0, 0, 0};
 double g_macro_us_per_mac = 6.2e-7;  // a round of 128 x 256 tiles over the chip: microseconds per element of the tile and column of K
 
 MacroPlan macro_plan(int M, int N, int K, bool may_split) {
-  // {WM, WN, wavefronts}: 256 x 256, 128 x 256, 128 x 128, 192 x 256, 256 x 192
-  const int cand[NCAND][3] = {{4, 8, 8}, {4, 8, 4}, {4, 4, 4}, {6, 8, 4}, {4, 6, 8}};
+  // {WM, WN, wavefronts}: 256 x 256, 128 x 256, 128 x 128, 192 x 256, 256 x 192, 192 x 192
+  const int cand[NCAND][3] = {{4, 8, 8}, {4, 8, 4}, {4, 4, 4}, {6, 8, 4}, {4, 6, 8}, {3, 6, 8}};
   MacroPlan best{4, 8, 4, 1, 1, 1, 0, false, 1};
   double best_cost = 1e300;
   const int KT = K >> 5;
@@ -356,6 +356,7 @@ void launch_shape(const op_t* xt, const op_t* wt, int M, int N, int K, const Mac
     if (p.kb == 2) launch_one<2, 4, 8, PR, EPI, false, 2>(xt, wt, M, N, K, p, e, st);
     else launch_one<2, 4, 8, PR, EPI>(xt, wt, M, N, K, p, e, st);
   }
+  else if (p.nw == 8 && p.wm == 3) launch_one<3, 6, 8, PR, EPI>(xt, wt, M, N, K, p, e, st);
   else if (p.nw == 8 && p.wn == 6) launch_one<4, 6, 8, PR, EPI>(xt, wt, M, N, K, p, e, st);
   else if (p.nw == 8) launch_one<4, 8, 8, PR, EPI>(xt, wt, M, N, K, p, e, st);
   else if (p.wm == 6) launch_one<6, 8, 4, PR, EPI>(xt, wt, M, N, K, p, e, st);
