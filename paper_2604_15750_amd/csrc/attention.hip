@@ -162,9 +162,9 @@ void launch_attention_f16(const f16_t* q, const f16_t* kcache, const f16_t* vcac
   // loads, and the output dims of a head split over four workgroups (two for 64 dims) to spread its K / V traffic
   const bool narrow = (size_t)tiles * n_q * meta.n_seqs < 128 && hd >= 64;
   const bool wide = (size_t)tiles * n_q * meta.n_seqs >= 512;  // enough workgroups to fill the chip with 4 wavefronts each
-  // enough (kv head, sequence) units to keep every XCD busy: the workgroups of a unit share an XCD (see the kernel)
+  // enough (kv head, sequence) units to keep every XCD busy (four each): the workgroups of a unit share an XCD (see the kernel)
   const int units = n_kv * meta.n_seqs;
-  const bool by_unit = units >= 64;
+  const bool by_unit = units >= 32;
 #define GO(HD, NWV, DS)                                                                                                                          \
   do {                                                                                                                                           \
     const int per_unit = by_unit ? tiles * DS * (n_q / n_kv) : 0;                                                                                \
